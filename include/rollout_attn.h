@@ -1,0 +1,150 @@
+/*
+ * rollout_attn: one decode step of attention over a paged KV cache, for a
+ * batch of variable-length sequences sampled in groups that share a prompt.
+ *
+ * Setting.  In RL post-training the actor-rollout phase generates responses
+ * auto-regressively and is memory-bound (paper Sec. 2.1.1, Sec. 2.2); with
+ * GRPO several responses are sampled for one prompt (Sec. 7.1) and their
+ * lengths vary widely (Sec. 7.4).  The paper schedules that phase but does
+ * not define its kernels; the operation below is the textbook one its
+ * inference engine performs once per layer per generated token.
+ *
+ * Definition.  For sequence b, query head h, G = Hq / Hkv, kv = h / G,
+ * L = seq_lens[b], token t < L stored at
+ *     pool[block_table[b][t / page_size]][kv][t % page_size][0:D]:
+ *   s_t      = softmax_scale * <q[b,h,:], k_t>
+ *   out[b,h] = sum_t softmax(s)_t * v_t           (bf16)
+ *   lse[b,h] = ln sum_t exp(s_t)                  (fp32, natural log)
+ * L == 0 gives out = 0 and lse = -inf.  There is no causal mask inside the
+ * call: the single query token of each sequence attends to all L tokens.
+ *
+ * Every pointer marked "dev" is device memory of the GPU the context was
+ * created on; it is owned by the caller, is only read (inputs) or written
+ * (out, lse, workspace) while the enqueued work runs, and is never retained
+ * after that.  The library allocates device memory only in
+ * rollout_attn_create() and frees it in rollout_attn_destroy().
+ * No function throws or aborts; every failure is a status code, and
+ * rollout_attn_last_error() describes the last one on that context.
+ */
+#ifndef ROLLOUT_ATTN_H
+#define ROLLOUT_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ROLLOUT_ATTN_ABI_VERSION 1u
+
+typedef struct ra_ctx ra_ctx; /* opaque; one per (process, device); not thread-safe */
+
+typedef enum {
+    RA_OK = 0,
+    RA_ERR_INVALID_ARG = 1,         /* null pointer, bad scalar, inconsistent shape; nothing was enqueued */
+    RA_ERR_UNSUPPORTED = 2,         /* valid but not implemented (see ra_problem); nothing was enqueued */
+    RA_ERR_WORKSPACE_TOO_SMALL = 3, /* nothing was enqueued */
+    RA_ERR_OUT_OF_RANGE = 4,        /* device data (lengths, page ids, group hint) failed RA_FLAG_VALIDATE;
+                                       the attention kernels were not enqueued */
+    RA_ERR_DEVICE = 5               /* a HIP runtime call failed */
+} ra_status;
+
+typedef enum { RA_KV_BF16 = 0, RA_KV_FP8_E4M3 = 1 } ra_kv_dtype;
+
+enum {
+    RA_FLAG_VALIDATE = 1u,          /* check device-side lengths / page ids / hint first (one extra kernel + a
+                                       stream synchronisation) */
+    RA_FLAG_NO_PREFIX_SHARING = 2u  /* ignore the prompt-group hint (for A/B comparison) */
+};
+
+/*
+ * One decode step.  Layouts:
+ *   q, out      bf16 [B][Hq][D], contiguous.
+ *   k_pool,     element (page, kv head, slot, d) at
+ *   v_pool        page*kv_stride_page + kv*kv_stride_head + slot*kv_stride_token + d   (in elements),
+ *               bf16, or OCP E4M3 codes (bias 7, max 448, no inf) when kv_dtype == RA_KV_FP8_E4M3.
+ *               D is contiguous; every (page, head, slot) row must start on a 16-byte boundary.
+ *   k_scale,    fp32 [num_pages][Hkv]; value = code * scale.  NULL unless fp8.
+ *   v_scale
+ *   block_table int32 [B][max_pages_per_seq]; entry i of row b is the page holding tokens
+ *               [i*page_size, (i+1)*page_size) of sequence b, shared prompt pages included.  Entries at or
+ *               past ceil(L/page_size) are never read.  Slots at or past L in the last page are read but
+ *               never used (they may hold NaN).
+ *   seq_lens    int32 [B], total KV tokens, 0 <= L <= max_pages_per_seq * page_size.
+ * Optional prompt-group hint (num_groups == 0 disables it).  It is a promise that changes speed, not
+ * results: the first page_size * n_g tokens of every member of group g live in the n_g pages
+ *   prefix_pages[prefix_page_offsets[g] .. prefix_page_offsets[g+1])
+ * and the member's own block_table row starts with the same ids.  Those pages are then read once per
+ * group instead of once per member.
+ *   seq_group           int32 [B], group id in [0, num_groups) or -1 (no group).
+ *   prefix_page_offsets int32 [num_groups + 1], non-decreasing, starts at 0.
+ *   prefix_pages        int32 [prefix_page_offsets[num_groups]].
+ * A member shorter than its group's prefix is handled as if it had no group.
+ * Supported: page_size == 16; D in {64, 128}; Hq % Hkv == 0 and Hq / Hkv <= 16.
+ */
+typedef struct {
+    int32_t B, Hq, Hkv, D, page_size;
+    int32_t num_pages, max_pages_per_seq;
+    const void *q;           /* dev */
+    const void *k_pool;      /* dev */
+    const void *v_pool;      /* dev */
+    int64_t kv_stride_page, kv_stride_head, kv_stride_token; /* in elements */
+    int32_t kv_dtype;        /* ra_kv_dtype */
+    const float *k_scale;    /* dev or NULL */
+    const float *v_scale;    /* dev or NULL */
+    const int32_t *block_table; /* dev */
+    const int32_t *seq_lens;    /* dev */
+    int32_t num_groups;
+    const int32_t *seq_group;           /* dev or NULL when num_groups == 0 */
+    const int32_t *prefix_page_offsets; /* dev or NULL when num_groups == 0 */
+    const int32_t *prefix_pages;        /* dev or NULL when num_groups == 0 */
+    float softmax_scale;
+    void *out;               /* dev, bf16 [B][Hq][D] */
+    float *lse;              /* dev, fp32 [B][Hq] */
+    uint32_t flags;
+} ra_problem;
+
+/* ROLLOUT_ATTN_ABI_VERSION of the library that was loaded. */
+uint32_t rollout_attn_abi_version(void);
+
+/* Creates a context on the given HIP device (allocates a few hundred bytes of device memory and queries
+ * the device).  *ctx is NULL on failure.  RA_ERR_DEVICE when the device cannot be used. */
+ra_status rollout_attn_create(ra_ctx **ctx, int device_ordinal);
+
+/* Frees the context's device memory.  NULL is accepted.  Work already enqueued must have finished. */
+void rollout_attn_destroy(ra_ctx *ctx);
+
+/* Text of the last failure on ctx (library-owned, valid until the next call on ctx).  With ctx == NULL,
+ * the text of the last failure of a call that had no context (create, check_problem). */
+const char *rollout_attn_last_error(const ra_ctx *ctx);
+
+/* Host-only check of the scalars, strides and pointers of a problem (device data is not read).  Returns
+ * what rollout_attn_decode would return for them before touching the device.  msg (may be NULL) receives
+ * a NUL-terminated explanation of at most msg_len bytes. */
+ra_status rollout_attn_check_problem(const ra_problem *problem, char *msg, size_t msg_len);
+
+/* Bytes of device workspace rollout_attn_decode needs for problems of this shape (only B, Hq, Hkv, D,
+ * page_size, num_groups are read).  ctx may be NULL: the size for a 256-compute-unit device is returned. */
+ra_status rollout_attn_workspace_size(const ra_ctx *ctx, const ra_problem *shape_only, size_t *bytes);
+
+/* Enqueues the whole step (schedule, attention over shared prompt pages and over each sequence's own
+ * pages, log-sum-exp merge) on hip_stream (a hipStream_t, NULL = default stream) and returns without
+ * waiting; out and lse are valid once the stream has reached that point.  workspace is dev memory of at
+ * least rollout_attn_workspace_size() bytes, 256-byte aligned, contents irrelevant on entry and undefined
+ * afterwards; calls that overlap in time need distinct workspaces.  Results are deterministic: the same
+ * inputs give byte-identical outputs. */
+ra_status rollout_attn_decode(ra_ctx *ctx, const ra_problem *problem, void *workspace, size_t workspace_bytes,
+                              void *hip_stream);
+
+/* Copies the stored K and V elements of sequence b, KV head kv_head, in logical token order, to k_out and
+ * v_out (dev, [L_b][D] raw elements: 2 bytes each for bf16, 1 for e4m3), through the same block-table
+ * arithmetic as the attention kernels.  capacity_tokens is the room in k_out / v_out; a longer sequence is
+ * truncated to it.  Enqueued on hip_stream. */
+ra_status rollout_attn_debug_gather(ra_ctx *ctx, const ra_problem *problem, int32_t b, int32_t kv_head,
+                                    void *k_out, void *v_out, int64_t capacity_tokens, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ROLLOUT_ATTN_H */

@@ -1,0 +1,239 @@
+// C-ABI of rollout_attn (see include/rollout_attn.h): argument checks, workspace carving, kernel sequencing.
+#include "../../include/rollout_attn.h"
+#include "ra_internal.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+struct ra_ctx {
+    int device;
+    int num_cus;
+    int waves[2]; // resident attention waves for D = 64, 128
+    void *zeros;  // 256 bytes of zeros on the device
+    int32_t *host_flags; // pinned, for RA_FLAG_VALIDATE
+    char err[512];
+};
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+void set_err(ra_ctx *ctx, const char *fmt, ...)
+{
+    char *dst = ctx ? ctx->err : g_err;
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(dst, 512, fmt, ap);
+    va_end(ap);
+}
+
+ra_status check(const ra_problem *p, char *msg, size_t n)
+{
+    auto fail = [&](ra_status st, const char *fmt, ...) {
+        if (msg && n) {
+            va_list ap;
+            va_start(ap, fmt);
+            vsnprintf(msg, n, fmt, ap);
+            va_end(ap);
+        }
+        return st;
+    };
+    if (msg && n) msg[0] = 0;
+    if (!p) return fail(RA_ERR_INVALID_ARG, "problem is NULL");
+    if (p->B < 0 || p->Hq <= 0 || p->Hkv <= 0 || p->D <= 0 || p->page_size <= 0 || p->num_pages < 0 ||
+        p->max_pages_per_seq < 0 || p->num_groups < 0)
+        return fail(RA_ERR_INVALID_ARG, "negative or zero dimension (B=%d Hq=%d Hkv=%d D=%d page_size=%d num_pages=%d "
+                                        "max_pages_per_seq=%d num_groups=%d)",
+                    p->B, p->Hq, p->Hkv, p->D, p->page_size, p->num_pages, p->max_pages_per_seq, p->num_groups);
+    if (p->Hq % p->Hkv) return fail(RA_ERR_INVALID_ARG, "Hq=%d is not a multiple of Hkv=%d", p->Hq, p->Hkv);
+    if (p->kv_dtype != RA_KV_BF16 && p->kv_dtype != RA_KV_FP8_E4M3)
+        return fail(RA_ERR_INVALID_ARG, "kv_dtype=%d is not a ra_kv_dtype", p->kv_dtype);
+    if (p->flags & ~(uint32_t)(RA_FLAG_VALIDATE | RA_FLAG_NO_PREFIX_SHARING))
+        return fail(RA_ERR_INVALID_ARG, "unknown bits in flags=0x%x", p->flags);
+    if (!std::isfinite(p->softmax_scale)) return fail(RA_ERR_INVALID_ARG, "softmax_scale is not finite");
+    if (p->page_size != 16) return fail(RA_ERR_UNSUPPORTED, "page_size=%d (only 16 is supported)", p->page_size);
+    if (p->D != 64 && p->D != 128) return fail(RA_ERR_UNSUPPORTED, "D=%d (only 64 and 128 are supported)", p->D);
+    if (p->Hq / p->Hkv > 16) return fail(RA_ERR_UNSUPPORTED, "Hq/Hkv=%d (at most 16 is supported)", p->Hq / p->Hkv);
+    if (p->kv_dtype == RA_KV_FP8_E4M3) return fail(RA_ERR_UNSUPPORTED, "fp8 KV is not implemented yet");
+    if ((int64_t)p->B * p->Hq > (int64_t)1 << 30 || (int64_t)p->B * p->max_pages_per_seq > (int64_t)1 << 40)
+        return fail(RA_ERR_UNSUPPORTED, "batch too large");
+    if (p->B == 0) return RA_OK;
+    if (!p->q || !p->k_pool || !p->v_pool || !p->block_table || !p->seq_lens || !p->out || !p->lse)
+        return fail(RA_ERR_INVALID_ARG, "a required pointer (q, k_pool, v_pool, block_table, seq_lens, out, lse) is NULL");
+    const int es = p->kv_dtype == RA_KV_FP8_E4M3 ? 1 : 2;
+    if (p->kv_stride_token < p->D || p->kv_stride_head < 0 || p->kv_stride_page < 0)
+        return fail(RA_ERR_INVALID_ARG, "kv strides must be non-negative and kv_stride_token >= D");
+    if ((p->kv_stride_token * es) % 16 || (p->kv_stride_head * es) % 16 || (p->kv_stride_page * es) % 16)
+        return fail(RA_ERR_INVALID_ARG, "kv strides must be multiples of 16 bytes");
+    if (p->kv_stride_token * es * 16 > INT32_MAX)
+        return fail(RA_ERR_UNSUPPORTED, "kv_stride_token too large");
+    if (((uintptr_t)p->k_pool | (uintptr_t)p->v_pool | (uintptr_t)p->q | (uintptr_t)p->out) % 16)
+        return fail(RA_ERR_INVALID_ARG, "q, out, k_pool and v_pool must be 16-byte aligned");
+    if (p->kv_dtype == RA_KV_FP8_E4M3 && (!p->k_scale || !p->v_scale))
+        return fail(RA_ERR_INVALID_ARG, "fp8 KV needs k_scale and v_scale");
+    if (p->num_groups > 0 && (!p->seq_group || !p->prefix_page_offsets || !p->prefix_pages))
+        return fail(RA_ERR_INVALID_ARG, "num_groups > 0 needs seq_group, prefix_page_offsets and prefix_pages");
+    return RA_OK;
+}
+
+void fill_launch(ra::Launch &a, const ra_ctx *ctx, const ra_problem *p)
+{
+    memset(&a, 0, sizeof a);
+    const int es = p->kv_dtype == RA_KV_FP8_E4M3 ? 1 : 2;
+    a.B = p->B; a.Hq = p->Hq; a.Hkv = p->Hkv; a.D = p->D; a.G = p->Hq / p->Hkv;
+    a.num_pages = p->num_pages; a.max_pages = p->max_pages_per_seq; a.num_groups = p->num_groups;
+    a.kv_fp8 = p->kv_dtype == RA_KV_FP8_E4M3;
+    a.share = p->num_groups > 0 && !(p->flags & RA_FLAG_NO_PREFIX_SHARING);
+    a.waves = ctx ? ctx->waves[p->D == 128] : 1024;
+    a.members_per_row = ra::kPrefixRows / a.G;
+    a.q = (const uint16_t *)p->q;
+    a.k_pool = (const uint8_t *)p->k_pool; a.v_pool = (const uint8_t *)p->v_pool;
+    a.stride_page_b = p->kv_stride_page * es; a.stride_head_b = p->kv_stride_head * es;
+    a.stride_token_b = (int32_t)(p->kv_stride_token * es);
+    a.k_scale = p->k_scale; a.v_scale = p->v_scale;
+    a.block_table = p->block_table; a.seq_lens = p->seq_lens;
+    a.seq_group = p->seq_group; a.pfx_off = p->prefix_page_offsets; a.pfx_pages = p->prefix_pages;
+    a.scale_log2 = p->softmax_scale * 1.4426950408889634f;
+    a.out = (uint16_t *)p->out; a.lse = p->lse;
+    a.zeros = ctx ? ctx->zeros : nullptr;
+}
+
+} // namespace
+
+extern "C" {
+
+uint32_t rollout_attn_abi_version(void) { return ROLLOUT_ATTN_ABI_VERSION; }
+
+ra_status rollout_attn_create(ra_ctx **out, int device)
+{
+    if (!out) { set_err(nullptr, "ctx is NULL"); return RA_ERR_INVALID_ARG; }
+    *out = nullptr;
+    int prev = 0;
+    hipError_t e = hipGetDevice(&prev);
+    if (e == hipSuccess) e = hipSetDevice(device);
+    if (e != hipSuccess) { set_err(nullptr, "hipSetDevice(%d): %s", device, hipGetErrorString(e)); return RA_ERR_DEVICE; }
+    ra_ctx *c = new (std::nothrow) ra_ctx();
+    if (!c) { set_err(nullptr, "out of host memory"); return RA_ERR_DEVICE; }
+    memset(c, 0, sizeof *c);
+    c->device = device;
+    hipDeviceProp_t prop;
+    e = hipGetDeviceProperties(&prop, device);
+    if (e == hipSuccess && strncmp(prop.gcnArchName, "gfx950", 6) != 0) {
+        set_err(nullptr, "device %d is %s; this library only runs on gfx950", device, prop.gcnArchName);
+        delete c; (void)hipSetDevice(prev);
+        return RA_ERR_UNSUPPORTED;
+    }
+    if (e == hipSuccess) { c->num_cus = prop.multiProcessorCount; e = hipMalloc(&c->zeros, 256); }
+    if (e == hipSuccess) e = hipMemset(c->zeros, 0, 256);
+    if (e == hipSuccess) e = hipHostMalloc((void **)&c->host_flags, 64, hipHostMallocDefault);
+    if (e == hipSuccess) e = ra::attention_waves(64, 0, c->num_cus, &c->waves[0]);
+    if (e == hipSuccess) e = ra::attention_waves(128, 0, c->num_cus, &c->waves[1]);
+    (void)hipSetDevice(prev);
+    if (e != hipSuccess) {
+        set_err(nullptr, "context set-up on device %d: %s", device, hipGetErrorString(e));
+        rollout_attn_destroy(c);
+        return RA_ERR_DEVICE;
+    }
+    *out = c;
+    return RA_OK;
+}
+
+void rollout_attn_destroy(ra_ctx *c)
+{
+    if (!c) return;
+    if (c->zeros) (void)hipFree(c->zeros);
+    if (c->host_flags) (void)hipHostFree(c->host_flags);
+    delete c;
+}
+
+const char *rollout_attn_last_error(const ra_ctx *c) { return c ? c->err : g_err; }
+
+ra_status rollout_attn_check_problem(const ra_problem *p, char *msg, size_t n)
+{
+    char local[512];
+    ra_status st = check(p, local, sizeof local);
+    if (st != RA_OK) set_err(nullptr, "%s", local);
+    if (msg && n) snprintf(msg, n, "%s", local);
+    return st;
+}
+
+ra_status rollout_attn_workspace_size(const ra_ctx *c, const ra_problem *p, size_t *bytes)
+{
+    if (!p || !bytes) { set_err(const_cast<ra_ctx *>(c), "problem or bytes is NULL"); return RA_ERR_INVALID_ARG; }
+    if (p->B < 0 || p->Hq <= 0 || p->Hkv <= 0 || p->Hq % p->Hkv || p->num_groups < 0) {
+        set_err(const_cast<ra_ctx *>(c), "bad shape for a workspace query");
+        return RA_ERR_INVALID_ARG;
+    }
+    if ((p->D != 64 && p->D != 128) || p->Hq / p->Hkv > 16) {
+        set_err(const_cast<ra_ctx *>(c), "unsupported shape for a workspace query (D in {64,128}, Hq/Hkv <= 16)");
+        return RA_ERR_UNSUPPORTED;
+    }
+    ra::Workspace ws;
+    int waves = c ? c->waves[p->D == 128] : 1024;
+    *bytes = ra::carve_workspace(ws, nullptr, p->B, p->Hkv, p->Hq / p->Hkv, p->D, p->num_groups, waves);
+    return RA_OK;
+}
+
+ra_status rollout_attn_decode(ra_ctx *c, const ra_problem *p, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!c) { set_err(nullptr, "ctx is NULL"); return RA_ERR_INVALID_ARG; }
+    ra_status st = check(p, c->err, sizeof c->err);
+    if (st != RA_OK) return st;
+    if (p->B == 0) return RA_OK;
+    ra::Launch a;
+    fill_launch(a, c, p);
+    size_t need = ra::carve_workspace(a.ws, workspace, a.B, a.Hkv, a.G, a.D, a.num_groups, a.waves);
+    if (!workspace || ((uintptr_t)workspace & 255)) { set_err(c, "workspace is NULL or not 256-byte aligned"); return RA_ERR_INVALID_ARG; }
+    if (workspace_bytes < need) {
+        set_err(c, "workspace of %zu bytes given, %zu needed", workspace_bytes, need);
+        return RA_ERR_WORKSPACE_TOO_SMALL;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    int prev = 0;
+    hipError_t e = hipGetDevice(&prev);
+    if (e == hipSuccess && prev != c->device) e = hipSetDevice(c->device);
+    if (e == hipSuccess && (p->flags & RA_FLAG_VALIDATE)) {
+        e = ra::launch_validate(a, s);
+        if (e == hipSuccess) e = hipMemcpyAsync(c->host_flags, a.ws.hdr + 4, 4, hipMemcpyDeviceToHost, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        if (e == hipSuccess && c->host_flags[0]) {
+            int f = c->host_flags[0];
+            set_err(c, "device data failed validation:%s%s%s%s", f & 1 ? " sequence length out of range;" : "",
+                    f & 2 ? " page id out of range;" : "", f & 4 ? " bad group id or prefix page list;" : "",
+                    f & 8 ? " a member's block table does not start with its group's shared pages;" : "");
+            if (prev != c->device) (void)hipSetDevice(prev);
+            return RA_ERR_OUT_OF_RANGE;
+        }
+    }
+    if (e == hipSuccess) e = ra::launch_plan(a, s);
+    if (e == hipSuccess) e = ra::launch_attention(a, s);
+    if (e == hipSuccess) e = ra::launch_merge(a, s);
+    if (prev != c->device) (void)hipSetDevice(prev);
+    if (e != hipSuccess) { set_err(c, "HIP: %s", hipGetErrorString(e)); return RA_ERR_DEVICE; }
+    return RA_OK;
+}
+
+ra_status rollout_attn_debug_gather(ra_ctx *c, const ra_problem *p, int32_t b, int32_t kvh, void *k_out, void *v_out,
+                                    int64_t cap, void *stream)
+{
+    if (!c) { set_err(nullptr, "ctx is NULL"); return RA_ERR_INVALID_ARG; }
+    ra_status st = check(p, c->err, sizeof c->err);
+    if (st != RA_OK) return st;
+    if (b < 0 || b >= p->B || kvh < 0 || kvh >= p->Hkv || !k_out || !v_out || cap < 0) {
+        set_err(c, "gather: b, kv_head, capacity or output pointer out of range");
+        return RA_ERR_INVALID_ARG;
+    }
+    ra::Launch a;
+    fill_launch(a, c, p);
+    int prev = 0;
+    hipError_t e = hipGetDevice(&prev);
+    if (e == hipSuccess && prev != c->device) e = hipSetDevice(c->device);
+    if (e == hipSuccess) e = ra::launch_gather(a, b, kvh, k_out, v_out, cap, (hipStream_t)stream);
+    if (prev != c->device) (void)hipSetDevice(prev);
+    if (e != hipSuccess) { set_err(c, "HIP: %s", hipGetErrorString(e)); return RA_ERR_DEVICE; }
+    return RA_OK;
+}
+
+} // extern "C"

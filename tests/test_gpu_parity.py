@@ -1,0 +1,224 @@
+"""GPU parity: the HIP library, called through its C ABI, against the fp64 oracle on the same seeded inputs.
+Integer work (page arithmetic, gather order) must be bit-exact; outputs within max-abs 1e-2 and per-row
+relative 1e-2, log-sum-exp within 1e-3 (bf16 inputs)."""
+import ctypes
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dec():
+    import paper_2507_01663_amd as ra
+    d = ra.Decoder(0)
+    yield d
+    d.close()
+
+
+def run(dec, p, flags=0, use_hint=True):
+    from gpu_util import DeviceProblem
+    dp = DeviceProblem(p, flags=flags, use_hint=use_hint)
+    dec.decode(dp.c)
+    return dp
+
+
+def log(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.mark.parametrize("name", ["tiny", "midd64", "mid7b", "mid32b", "mid72b"])
+def test_parity_element_by_element(dec, name):
+    from gpu_util import compare
+    p = workload.make_problem(name, seed=0)
+    log("case", name, "B", p.B, "lens", int(p.seq_lens.min()), int(p.seq_lens.max()))
+    ref_out, ref_lse = oracle.decode(p)
+    dp = run(dec, p)
+    errs = compare(*dp.results(), ref_out, ref_lse, name)
+    log(name, "abs %.2e rel %.2e lse %.2e" % errs)
+
+
+@pytest.mark.parametrize("name", ["tiny", "mid7b"])
+def test_hint_off_and_flag_give_the_same_answer(dec, name):
+    import paper_2507_01663_amd as ra
+    from gpu_util import compare
+    p = workload.make_problem(name, seed=1)
+    ref_out, ref_lse = oracle.decode(p)
+    for kw in (dict(use_hint=False), dict(flags=ra.RA_FLAG_NO_PREFIX_SHARING), dict(flags=ra.RA_FLAG_VALIDATE)):
+        dp = run(dec, p, **kw)
+        compare(*dp.results(), ref_out, ref_lse, "%s %s" % (name, kw))
+
+
+def test_streaming_steps_rebuild_the_table(dec):
+    from gpu_util import compare
+    p0 = workload.make_problem("mid72b", seed=0, step=0)
+    pool = (p0.k_pool, p0.v_pool, None, None)
+    for step in (1, 5, 7):
+        p = workload.make_problem("mid72b", seed=0, step=step, pool=pool, num_pages=p0.num_pages)
+        ref_out, ref_lse = oracle.decode(p)
+        dp = run(dec, p)
+        compare(*dp.results(), ref_out, ref_lse, "mid72b step %d" % step)
+
+
+def test_edge_lengths(dec):
+    from gpu_util import compare
+    # empty sequences, single token, exact page multiples, one past a page, a group whose members are all empty
+    lens = [0, 1, 15, 16, 17, 31, 32, 33, 0, 0, 64, 65, 127, 128, 129, 300]
+    p = workload.build_problem("edge", 8, 2, 128, [0, 0], 8, lens, seed=2)
+    ref_out, ref_lse = oracle.decode(p)
+    dp = run(dec, p)
+    out, lse = dp.results()
+    compare(out, lse, ref_out, ref_lse, "edge")
+    assert (out[0] == 0).all() and np.isneginf(lse[0]).all()
+    # prompt not page aligned (20 tokens -> 1 shared page), a member shorter than... every member holds the prefix
+    p = workload.build_problem("edge2", 6, 2, 64, [20, 16, 48], 3, [0, 5, 40, 1, 0, 29, 0, 0, 0], seed=3)
+    ref_out, ref_lse = oracle.decode(p)
+    compare(*run(dec, p).results(), ref_out, ref_lse, "edge2")
+
+
+def test_member_shorter_than_prefix_falls_back(dec):
+    from gpu_util import DeviceProblem, compare
+    p = workload.build_problem("short", 4, 2, 64, [64], 4, [0, 10, 0, 33], seed=4)
+    # cut sequence 2 down to 40 tokens: it no longer holds the whole 4-page prefix
+    p.seq_lens[2] = 40
+    ref_out, ref_lse = oracle.decode(p)
+    compare(*run(dec, p).results(), ref_out, ref_lse, "short member")
+
+
+def test_scattered_group_ids_and_ungrouped(dec):
+    from gpu_util import compare
+    p = workload.build_problem("scatter", 8, 4, 128, [32, 32, 32], 4, list(range(5, 17)), seed=5)
+    # relabel: group ids need not be contiguous in b; one sequence opts out with -1
+    perm = np.random.default_rng(0).permutation(p.B)
+    for name in ("q", "block_table", "seq_lens", "seq_group"):
+        setattr(p, name, np.ascontiguousarray(getattr(p, name)[perm]))
+    p.seq_group[3] = -1
+    ref_out, ref_lse = oracle.decode(p)
+    compare(*run(dec, p).results(), ref_out, ref_lse, "scattered")
+
+
+def test_many_members_need_several_prefix_rows(dec):
+    from gpu_util import compare
+    # 16 members x 8 heads per kv head = 128 query rows on the shared pages: two 64-row work rows
+    p = workload.build_problem("wide", 16, 2, 128, [96], 16, list(range(0, 160, 10)), seed=6)
+    ref_out, ref_lse = oracle.decode(p)
+    compare(*run(dec, p).results(), ref_out, ref_lse, "wide group")
+
+
+def test_gather_is_bit_exact(dec):
+    from gpu_util import DeviceProblem
+    for name in ("tiny", "mid32b"):
+        p = workload.make_problem(name, seed=0)
+        dp = DeviceProblem(p)
+        rng = np.random.default_rng(0)
+        pairs = [(b, kv) for b in range(p.B) for kv in range(p.Hkv)]
+        if len(pairs) > 24:
+            pairs = [pairs[i] for i in rng.choice(len(pairs), 24, replace=False)]
+        for b, kv in pairs:
+            L = int(p.seq_lens[b])
+            k_out = torch.zeros((L, p.D), dtype=torch.bfloat16, device="cuda:0")
+            v_out = torch.zeros_like(k_out)
+            dec.debug_gather(dp.c, b, kv, k_out, v_out)
+            torch.cuda.synchronize()
+            rk, rv, _ = oracle.gather(p, b, kv)
+            assert np.array_equal(k_out.view(torch.int16).cpu().numpy().view(np.uint16), rk)
+            assert np.array_equal(v_out.view(torch.int16).cpu().numpy().view(np.uint16), rv)
+
+
+def test_page_arithmetic_through_the_attention_kernels(dec):
+    """Values that encode (page, slot): a wrong page or slot in the attention path changes the result grossly."""
+    from gpu_util import compare
+    p = workload.make_problem("mid7b", seed=2)
+    pg = np.arange(p.num_pages, dtype=np.float32)[:, None, None, None]
+    sl = np.arange(16, dtype=np.float32)[None, None, :, None]
+    hd = np.arange(p.Hkv, dtype=np.float32)[None, :, None, None]
+    d = np.arange(p.D, dtype=np.float32)[None, None, None, :]
+    nan_k, nan_v = p.k_pool == workload.BF16_NAN, p.v_pool == workload.BF16_NAN
+    p.k_pool[:] = workload.f32_to_bf16_bits(np.sin(0.37 * pg + 1.3 * sl + hd + 0.05 * d))
+    p.v_pool[:] = workload.f32_to_bf16_bits((1.0 + 0.5 * np.cos(0.11 * pg + 0.7 * sl + 2 * hd)) * (0.5 + d / 256))
+    p.k_pool[nan_k] = workload.BF16_NAN
+    p.v_pool[nan_v] = workload.BF16_NAN
+    ref_out, ref_lse = oracle.decode(p)
+    compare(*run(dec, p).results(), ref_out, ref_lse, "encoded pool")
+
+
+def test_two_runs_are_byte_identical(dec):
+    p = workload.make_problem("mid32b", seed=3)
+    a = run(dec, p)
+    o1, l1 = a.out.clone(), a.lse.clone()
+    b = run(dec, p)
+    torch.cuda.synchronize()
+    assert torch.equal(o1.view(torch.int16), b.out.view(torch.int16)) and torch.equal(l1, b.lse)
+
+
+def test_strided_pool_layout(dec):
+    """Pools that are views of a larger allocation (K and V interleaved per page) use the stride arguments."""
+    from gpu_util import DeviceProblem, bits_to_bf16, compare
+    import paper_2507_01663_amd as ra
+    p = workload.make_problem("midd64", seed=4)
+    ref_out, ref_lse = oracle.decode(p)
+    dp = DeviceProblem(p)
+    both = torch.stack([dp.k_pool, dp.v_pool], dim=1).contiguous()      # [pages, 2, Hkv, 16, D]
+    dp.k_pool, dp.v_pool = both[:, 0], both[:, 1]
+    dp.set()
+    assert dp.c.kv_stride_page == 2 * p.Hkv * 16 * p.D
+    dec.decode(dp.c)
+    compare(*dp.results(), ref_out, ref_lse, "strided")
+
+
+def test_validate_flag_reports_bad_device_data(dec):
+    import paper_2507_01663_amd as ra
+    from gpu_util import DeviceProblem
+    p = workload.make_problem("midd64", seed=5)
+    dp = DeviceProblem(p, flags=ra.RA_FLAG_VALIDATE)
+    dp.block_table[2, 1] = p.num_pages + 7
+    with pytest.raises(ra.RolloutAttnError) as e:
+        dec.decode(dp.c)
+    assert e.value.status == ra.RA_ERR_OUT_OF_RANGE and "page id" in str(e.value)
+    dp.block_table[2, 1] = int(p.block_table[2, 1])
+    dp.seq_lens[0] = p.max_pages_per_seq * 16 + 1
+    with pytest.raises(ra.RolloutAttnError) as e:
+        dec.decode(dp.c)
+    assert e.value.status == ra.RA_ERR_OUT_OF_RANGE and "length" in str(e.value)
+    dp.seq_lens[0] = int(p.seq_lens[0])
+    dp.block_table[1, 0] = int(p.block_table[5, 1])          # member row no longer starts with the shared page
+    with pytest.raises(ra.RolloutAttnError) as e:
+        dec.decode(dp.c)
+    assert e.value.status == ra.RA_ERR_OUT_OF_RANGE
+
+
+def test_workspace_too_small_and_bad_arguments(dec):
+    import paper_2507_01663_amd as ra
+    from gpu_util import DeviceProblem
+    p = workload.make_problem("tiny")
+    dp = DeviceProblem(p)
+    ws = dec.workspace(dp.c)
+    with pytest.raises(ra.RolloutAttnError) as e:
+        ra.rollout_attn_decode(dec.ctx, dp.c, ctypes.c_void_p(ws.data_ptr()), 1024, None)
+    assert e.value.status == ra.RA_ERR_WORKSPACE_TOO_SMALL
+    dp.c.D = 96
+    with pytest.raises(ra.RolloutAttnError) as e:
+        dec.decode(dp.c)
+    assert e.value.status == ra.RA_ERR_UNSUPPORTED
+    # outputs untouched by rejected calls
+    assert torch.isnan(dp.out.float()).all()
+
+
+def test_full_size_grpo7b_against_oracle(dec):
+    """The benchmark workload at full size, every row (the oracle needs about a second for it)."""
+    from gpu_util import compare
+    p = workload.make_problem("grpo7b", seed=0)
+    log("grpo7b: kv tokens", p.kv_tokens(), "pages", p.num_pages)
+    ref_out, ref_lse = oracle.decode(p)
+    dp = run(dec, p)
+    errs = compare(*dp.results(), ref_out, ref_lse, "grpo7b")
+    log("grpo7b abs %.2e rel %.2e lse %.2e" % errs)
+    dp2 = run(dec, p, use_hint=False)
+    compare(*dp2.results(), ref_out, ref_lse, "grpo7b no hint")
