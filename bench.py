@@ -1,0 +1,155 @@
+#!/usr/bin/env python3
+"""Benchmark of the rollout_attn decode step on one MI355X.
+
+A step is one rollout_attn_decode call over the whole batch (schedule + attention + merge = one layer's
+attention for one generated token).  The workload is the 7B-shaped GRPO batch (32 prompts x 8 responses,
+Hq=28, Hkv=4, D=128, prompt 512, responses U[0,3584], page 16, pages randomly permuted).  Several
+independent instances (own pools and tables, distinct seeds) are resident in HBM and the timed loop rotates
+over them, so no step finds its pages in the 256 MB last-level cache.
+
+Prints ONE JSON line: whole-step throughput in algorithmic GB/s (every distinct KV token once, shared
+prompt pages once per group), steps/s, the roofline of the dominant kernel from HIP events, and the fp64
+oracle timed on the host cores as a reported baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+
+
+def kernel_source_hash():
+    import hashlib
+    h = hashlib.sha256()
+    for f in ("ra_kernels.hip", "ra_internal.h"):
+        h.update(open(os.path.join(ROOT, "paper_2507_01663_amd", "csrc", f), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def recorded_traffic(workload_name):
+    """HBM bytes per launch of the attention kernel from the committed rocprofv3 --pmc runs, if they were taken
+    on the current kernel source; else None."""
+    path = os.path.join(ROOT, "profiles", "attention_traffic.json")
+    try:
+        rec = json.load(open(path))
+    except (OSError, ValueError):
+        return None
+    ent = rec.get(workload_name)
+    if not ent or ent.get("kernel_source_hash") != kernel_source_hash():
+        return None
+    return ent.get("hbm_bytes_per_launch")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", default="grpo7b")
+    ap.add_argument("--kv-dtype", default="bf16")
+    ap.add_argument("--instances", type=int, default=4)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sharing", action="store_true", help="ignore the prompt-group hint (A/B)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (the path needs no exchange between GPUs; "
+              "see DESIGN.md, 'More than one GPU'); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2507_01663_amd as ra
+    import workload
+    from gpu_util import DeviceProblem
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    ra.load_library()                                  # fails loudly when the HIP library is not built
+    dec = ra.Decoder(0)
+    flags = ra.RA_FLAG_NO_PREFIX_SHARING if args.no_sharing else 0
+
+    t0 = time.time()
+    probs, devs = [], []
+    for i in range(args.instances):
+        p = workload.make_problem(args.workload, seed=i, kv_dtype=args.kv_dtype)
+        probs.append(p)
+        devs.append(DeviceProblem(p, flags=flags))
+    alg_bytes = [p.algorithmic_bytes(share_prefix=True) for p in probs]
+    print("# %d instances of %s generated and uploaded in %.1f s; algorithmic MB/step: %s" %
+          (args.instances, args.workload, time.time() - t0, [round(b / 1e6, 1) for b in alg_bytes]), file=sys.stderr)
+
+    stream = torch.cuda.current_stream(0)
+
+    def run(n, first=0):
+        for i in range(n):
+            dec.decode(devs[(first + i) % len(devs)].c, stream)
+
+    run(args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    total_bytes = sum(alg_bytes[i % len(devs)] for i in range(args.steps))
+    ms_per_step = wall * 1e3 / args.steps
+    gbps = total_bytes / wall / 1e9
+
+    # per-kernel durations from HIP events recorded by the library on the same stream, over the same steps
+    ra.rollout_attn_set_timing(dec.ctx, True)
+    run(min(args.warmup, 8))
+    phase = np.zeros(3)
+    att_bytes = 0
+    for i in range(args.steps):
+        dec.decode(devs[i % len(devs)].c, stream)
+        phase += np.array(ra.rollout_attn_get_timing(dec.ctx))
+        att_bytes += alg_bytes[i % len(devs)]
+    ra.rollout_attn_set_timing(dec.ctx, False)
+    phase /= args.steps
+    att_gbps = att_bytes / args.steps / (phase[1] * 1e-3) / 1e9
+
+    out = {
+        "metric": "decode_attn_hbm_GBps", "value": round(gbps, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if args.kv_dtype == "bf16" else "fp8_e4m3 KV, bf16 MFMA", "data": "synthetic",
+        "steps_per_s": round(args.steps / wall, 1), "pct_of_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 2),
+        "config": {"workload": args.workload + ("" if args.kv_dtype == "bf16" else "_fp8"), "B": probs[0].B, "Hq": probs[0].Hq,
+                   "Hkv": probs[0].Hkv, "D": probs[0].D, "page": 16, "instances": args.instances,
+                   "prefix_sharing": not args.no_sharing,
+                   "algorithmic_MB_per_step": round(sum(alg_bytes) / len(alg_bytes) / 1e6, 2),
+                   "kv_tokens_per_step": int(sum(p.kv_tokens() for p in probs) / len(probs))},
+        "phases_ms": {"schedule": round(float(phase[0]), 5), "attention": round(float(phase[1]), 5),
+                      "merge": round(float(phase[2]), 5)},
+        "roofline": {"bound": "hbm", "kernel": "attention_kernel", "achieved": round(att_gbps, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(att_gbps / HBM_PEAK_GBPS, 4),
+                     "traffic": recorded_traffic(args.workload)},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        reps = 3
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            ref_out, ref_lse = oracle.decode(probs[0])
+        cpu = (time.perf_counter() - t0) / reps
+        out["cpu_baseline"] = {"value": round(alg_bytes[0] / cpu / 1e9, 3), "unit": "GB/s", "cores": oracle.threads(),
+                               "kind": "oracle", "steps_per_s": round(1 / cpu, 3),
+                               "sample": "all %d (sequence, head) rows of instance 0, %d repetitions, fp64 C oracle with OpenMP"
+                                         % (probs[0].B * probs[0].Hq, reps)}
+        # the timed GPU result of instance 0 must agree with what was just computed
+        from gpu_util import compare
+        dec.decode(devs[0].c, stream)
+        errs = compare(*devs[0].results(), ref_out, ref_lse, "bench instance 0")
+        out["parity"] = {"max_abs": float("%.3g" % errs[0]), "max_row_rel": float("%.3g" % errs[1]), "max_lse": float("%.3g" % errs[2])}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

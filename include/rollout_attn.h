@@ -144,6 +144,14 @@ ra_status rollout_attn_decode(ra_ctx *ctx, const ra_problem *problem, void *work
 ra_status rollout_attn_debug_gather(ra_ctx *ctx, const ra_problem *problem, int32_t b, int32_t kv_head,
                                     void *k_out, void *v_out, int64_t capacity_tokens, void *hip_stream);
 
+/* Per-kernel timing for benchmarks.  While enabled, rollout_attn_decode records HIP events on its stream
+ * around its three phases (schedule, attention, merge); rollout_attn_get_timing waits for the events of the
+ * most recent decode call and returns the three durations in milliseconds.  Off by default: the events cost
+ * a little time between kernels.  The numbers are measurements, not part of the result (the decode step is
+ * memory-bound, paper Sec. 2.1.1, so the attention phase is the one to watch). */
+ra_status rollout_attn_set_timing(ra_ctx *ctx, int enable);
+ra_status rollout_attn_get_timing(ra_ctx *ctx, float phase_ms[3]);
+
 #ifdef __cplusplus
 }
 #endif

@@ -69,6 +69,10 @@ def load_library():
     lib.rollout_attn_debug_gather.restype = ctypes.c_int
     lib.rollout_attn_debug_gather.argtypes = [ctypes.c_void_p, P(ra_problem), ctypes.c_int32, ctypes.c_int32,
                                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+    lib.rollout_attn_set_timing.restype = ctypes.c_int
+    lib.rollout_attn_set_timing.argtypes = [ctypes.c_void_p, ctypes.c_int]
+    lib.rollout_attn_get_timing.restype = ctypes.c_int
+    lib.rollout_attn_get_timing.argtypes = [ctypes.c_void_p, P(ctypes.c_float)]
     _lib = lib
     return lib
 
@@ -119,6 +123,17 @@ def rollout_attn_decode(ctx, problem, workspace_ptr, workspace_bytes, hip_stream
 def rollout_attn_debug_gather(ctx, problem, b, kv_head, k_out_ptr, v_out_ptr, capacity_tokens, hip_stream=None):
     _check(load_library().rollout_attn_debug_gather(ctx, ctypes.byref(problem), b, kv_head, k_out_ptr, v_out_ptr,
                                                     capacity_tokens, hip_stream), ctx)
+
+
+def rollout_attn_set_timing(ctx, enable):
+    _check(load_library().rollout_attn_set_timing(ctx, int(bool(enable))), ctx)
+
+
+def rollout_attn_get_timing(ctx):
+    """(schedule_ms, attention_ms, merge_ms) of the most recent timed decode call."""
+    ms = (ctypes.c_float * 3)()
+    _check(load_library().rollout_attn_get_timing(ctx, ms), ctx)
+    return tuple(float(x) for x in ms)
 
 
 # ---- helpers over torch tensors (device memory and streams only) --------------------------------------

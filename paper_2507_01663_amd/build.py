@@ -8,6 +8,7 @@ LIB = os.path.join(HERE, "librollout_attn.so")
 SOURCES = ["ra_kernels.hip", "ra_api.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1",
          "-Wall", "-Wno-inline-asm", "-Wno-int-to-pointer-cast", "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option"]
 
 

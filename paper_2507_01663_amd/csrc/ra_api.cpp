@@ -5,14 +5,22 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 
 struct ra_ctx {
     int device;
     int num_cus;
-    int waves[2]; // resident attention waves for D = 64, 128
+    int waves[2];  // resident attention waves for D = 64, 128
+    int stages[2]; // LDS ring depth for D = 64, 128
+    int cost_prefix; // scheduling weight of a shared-prefix page
+    int static_pct;  // share of the work that is assigned to waves up front
+    int dyn_pages;   // pages per dynamically scheduled span
     void *zeros;  // 256 bytes of zeros on the device
     int32_t *host_flags; // pinned, for RA_FLAG_VALIDATE
+    int timing;          // record events around the phases
+    int timed;           // a decode call has recorded them
+    hipEvent_t ev[4];
     char err[512];
 };
 
@@ -86,8 +94,12 @@ void fill_launch(ra::Launch &a, const ra_ctx *ctx, const ra_problem *p)
     a.num_pages = p->num_pages; a.max_pages = p->max_pages_per_seq; a.num_groups = p->num_groups;
     a.kv_fp8 = p->kv_dtype == RA_KV_FP8_E4M3;
     a.share = p->num_groups > 0 && !(p->flags & RA_FLAG_NO_PREFIX_SHARING);
-    a.waves = ctx ? ctx->waves[p->D == 128] : 1024;
+    a.waves = ctx ? ctx->waves[p->D == 128] : 2048;
+    a.stages = ctx ? ctx->stages[p->D == 128] : 4;
     a.members_per_row = ra::kPrefixRows / a.G;
+    a.cost_prefix = ctx ? ctx->cost_prefix : ra::kCostPrefix;
+    a.static_pct = ctx ? ctx->static_pct : 100;
+    a.dyn_pages = ctx ? ctx->dyn_pages : 16;
     a.q = (const uint16_t *)p->q;
     a.k_pool = (const uint8_t *)p->k_pool; a.v_pool = (const uint8_t *)p->v_pool;
     a.stride_page_b = p->kv_stride_page * es; a.stride_head_b = p->kv_stride_head * es;
@@ -118,6 +130,21 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
     if (!c) { set_err(nullptr, "out of host memory"); return RA_ERR_DEVICE; }
     memset(c, 0, sizeof *c);
     c->device = device;
+    c->cost_prefix = ra::kCostPrefix;
+    c->static_pct = 100;
+    c->dyn_pages = 16;
+    if (const char *ev = getenv("ROLLOUT_ATTN_STATIC_PCT")) {
+        int v = atoi(ev);
+        if (v >= 0 && v <= 100) c->static_pct = v;
+    }
+    if (const char *ev = getenv("ROLLOUT_ATTN_DYN_PAGES")) {
+        int v = atoi(ev);
+        if (v >= 1 && v <= 4096) c->dyn_pages = v;
+    }
+    if (const char *ev = getenv("ROLLOUT_ATTN_COST_PREFIX")) {
+        int v = atoi(ev);
+        if (v >= 1 && v <= 64) c->cost_prefix = v;
+    }
     hipDeviceProp_t prop;
     e = hipGetDeviceProperties(&prop, device);
     if (e == hipSuccess && strncmp(prop.gcnArchName, "gfx950", 6) != 0) {
@@ -128,8 +155,9 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
     if (e == hipSuccess) { c->num_cus = prop.multiProcessorCount; e = hipMalloc(&c->zeros, 256); }
     if (e == hipSuccess) e = hipMemset(c->zeros, 0, 256);
     if (e == hipSuccess) e = hipHostMalloc((void **)&c->host_flags, 64, hipHostMallocDefault);
-    if (e == hipSuccess) e = ra::attention_waves(64, 0, c->num_cus, &c->waves[0]);
-    if (e == hipSuccess) e = ra::attention_waves(128, 0, c->num_cus, &c->waves[1]);
+    for (int i = 0; i < 4 && e == hipSuccess; i++) e = hipEventCreate(&c->ev[i]);
+    if (e == hipSuccess) e = ra::attention_config(64, 0, c->num_cus, &c->stages[0], &c->waves[0]);
+    if (e == hipSuccess) e = ra::attention_config(128, 0, c->num_cus, &c->stages[1], &c->waves[1]);
     (void)hipSetDevice(prev);
     if (e != hipSuccess) {
         set_err(nullptr, "context set-up on device %d: %s", device, hipGetErrorString(e));
@@ -145,6 +173,8 @@ void rollout_attn_destroy(ra_ctx *c)
     if (!c) return;
     if (c->zeros) (void)hipFree(c->zeros);
     if (c->host_flags) (void)hipHostFree(c->host_flags);
+    for (int i = 0; i < 4; i++)
+        if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
     delete c;
 }
 
@@ -171,7 +201,7 @@ ra_status rollout_attn_workspace_size(const ra_ctx *c, const ra_problem *p, size
         return RA_ERR_UNSUPPORTED;
     }
     ra::Workspace ws;
-    int waves = c ? c->waves[p->D == 128] : 1024;
+    int waves = c ? c->waves[p->D == 128] : 2048;
     *bytes = ra::carve_workspace(ws, nullptr, p->B, p->Hkv, p->Hq / p->Hkv, p->D, p->num_groups, waves);
     return RA_OK;
 }
@@ -207,9 +237,15 @@ ra_status rollout_attn_decode(ra_ctx *c, const ra_problem *p, void *workspace, s
             return RA_ERR_OUT_OF_RANGE;
         }
     }
+    const bool tm = c->timing != 0;
+    if (e == hipSuccess && tm) e = hipEventRecord(c->ev[0], s);
     if (e == hipSuccess) e = ra::launch_plan(a, s);
+    if (e == hipSuccess && tm) e = hipEventRecord(c->ev[1], s);
     if (e == hipSuccess) e = ra::launch_attention(a, s);
+    if (e == hipSuccess && tm) e = hipEventRecord(c->ev[2], s);
     if (e == hipSuccess) e = ra::launch_merge(a, s);
+    if (e == hipSuccess && tm) e = hipEventRecord(c->ev[3], s);
+    if (e == hipSuccess && tm) c->timed = 1;
     if (prev != c->device) (void)hipSetDevice(prev);
     if (e != hipSuccess) { set_err(c, "HIP: %s", hipGetErrorString(e)); return RA_ERR_DEVICE; }
     return RA_OK;
@@ -232,6 +268,24 @@ ra_status rollout_attn_debug_gather(ra_ctx *c, const ra_problem *p, int32_t b, i
     if (e == hipSuccess && prev != c->device) e = hipSetDevice(c->device);
     if (e == hipSuccess) e = ra::launch_gather(a, b, kvh, k_out, v_out, cap, (hipStream_t)stream);
     if (prev != c->device) (void)hipSetDevice(prev);
+    if (e != hipSuccess) { set_err(c, "HIP: %s", hipGetErrorString(e)); return RA_ERR_DEVICE; }
+    return RA_OK;
+}
+
+ra_status rollout_attn_set_timing(ra_ctx *c, int enable)
+{
+    if (!c) { set_err(nullptr, "ctx is NULL"); return RA_ERR_INVALID_ARG; }
+    c->timing = enable != 0;
+    c->timed = 0;
+    return RA_OK;
+}
+
+ra_status rollout_attn_get_timing(ra_ctx *c, float ms[3])
+{
+    if (!c || !ms) { set_err(c, "ctx or phase_ms is NULL"); return RA_ERR_INVALID_ARG; }
+    if (!c->timed) { set_err(c, "no decode call has been timed (rollout_attn_set_timing first)"); return RA_ERR_INVALID_ARG; }
+    hipError_t e = hipEventSynchronize(c->ev[3]);
+    for (int i = 0; i < 3 && e == hipSuccess; i++) e = hipEventElapsedTime(&ms[i], c->ev[i], c->ev[i + 1]);
     if (e != hipSuccess) { set_err(c, "HIP: %s", hipGetErrorString(e)); return RA_ERR_DEVICE; }
     return RA_OK;
 }

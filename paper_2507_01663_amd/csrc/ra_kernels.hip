@@ -7,6 +7,8 @@
 // equal spans, one per resident wave.  MFMA does the two tile products; softmax is fp32 on the VALU.
 #include "ra_internal.h"
 
+#include <stdlib.h>
+
 namespace ra {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -14,6 +16,7 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
 // ------------------------------------------------------------------------------------------------------
 // workspace
@@ -45,27 +48,35 @@ size_t carve_workspace(Workspace &ws, void *base, int B, int Hkv, int G, int D, 
     ws.seq_rank = (int32_t *)take((size_t)B * 4);
     ws.seq_pfx_row = (int32_t *)take((size_t)B * 4);
     ws.members = (int32_t *)take((size_t)B * 4);
-    ws.row_units = (int32_t *)take((size_t)2 * B * 4);
     ws.row_start = (int32_t *)take(((size_t)2 * B + 1) * 4);
     ws.row_info = (int4 *)take((size_t)2 * B * 16);
-    ws.wave_first_row = (int32_t *)take((size_t)(waves + 1) * 4);
-    size_t nsuf = (size_t)B * Hkv + waves;
+    const size_t spans = (size_t)(1 + kDynSpansPerWave) * waves; // upper bound on spans of the cost stream
+    ws.span_first_row = (int32_t *)take((spans + 1) * 4);
+    size_t nsuf = (size_t)B * Hkv + spans;
     ws.suf_o = (float *)take(nsuf * G * D * 4);
     ws.suf_lse = (float *)take(nsuf * G * 4);
-    size_t npfx = prm ? (size_t)prm * Hkv + waves : 0;
+    size_t npfx = prm ? (size_t)prm * Hkv + spans : 0;
     ws.pfx_o = (float *)take(npfx * kPrefixRows * D * 4);
     ws.pfx_lse = (float *)take(npfx * kPrefixRows * 4);
     return off;
 }
 
 // ------------------------------------------------------------------------------------------------------
-// schedule (one workgroup): work rows, their page counts, the scan, and each wave's first row
+// schedule (one workgroup): work rows, their cost, the scan, and each wave's first row
+//
+// Work rows: first the shared-prefix rows (one per group and block of kPrefixRows/G members), then one row
+// per sequence for its own pages.  A row of n pages costs weight*n per kv head, and the rows, each repeated
+// for every kv head, form one stream of cost units that is cut into equal spans, one per resident wave: the
+// ragged lengths (paper Sec. 7.4) never leave a compute unit idle.  A page belongs to the wave whose span
+// holds the page's first cost unit.  Prefix pages weigh more because a wave spends more time on them (more
+// query rows per byte); the weights only balance time, they never change results.
 // ------------------------------------------------------------------------------------------------------
 
 constexpr int kPlanThreads = 1024;
+constexpr int kPlanCap = 2048; // sequences / groups whose intermediate arrays fit in LDS; beyond, the workspace is used
 
-// Exclusive scan of in[0..n) into out[0..n], out[n] = total.  All threads of the block call it.
-__device__ void block_scan(const int32_t *in, int32_t *out, int n, int32_t *lds /*[17]*/)
+// Exclusive scan of in[0..n) into out[0..n], out[n] = total (in == out is allowed).  All threads call it.
+__device__ void block_scan(const int32_t *in, int32_t *out, int n, int32_t *tmp /*[17], LDS*/)
 {
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     int carry = 0;
@@ -78,22 +89,22 @@ __device__ void block_scan(const int32_t *in, int32_t *out, int n, int32_t *lds 
             int y = __shfl_up(x, d);
             if (lane >= d) x += y;
         }
-        if (lane == 63) lds[wv] = x;
+        if (lane == 63) tmp[wv] = x;
         __syncthreads();
         if (wv == 0) {
-            int t = lane < kPlanThreads / 64 ? lds[lane] : 0;
-            int s = t;
+            int t = lane < kPlanThreads / 64 ? tmp[lane] : 0;
+            int sc = t;
 #pragma unroll
             for (int d = 1; d < 16; d <<= 1) {
-                int y = __shfl_up(s, d);
-                if (lane >= d) s += y;
+                int y = __shfl_up(sc, d);
+                if (lane >= d) sc += y;
             }
-            if (lane < kPlanThreads / 64) lds[lane] = s - t;
-            if (lane == kPlanThreads / 64 - 1) lds[16] = s;
+            if (lane < kPlanThreads / 64) tmp[lane] = sc - t;
+            if (lane == kPlanThreads / 64 - 1) tmp[16] = sc;
         }
         __syncthreads();
-        if (i < n) out[i] = carry + lds[wv] + x - v;
-        carry += lds[16];
+        if (i < n) out[i] = carry + tmp[wv] + x - v;
+        carry += tmp[16];
         __syncthreads();
     }
     if (tid == 0) out[n] = carry;
@@ -103,88 +114,114 @@ __device__ void block_scan(const int32_t *in, int32_t *out, int n, int32_t *lds 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
 {
     __shared__ int32_t scan_tmp[17];
+    __shared__ int32_t l_grp_count[kPlanCap], l_grp_rowbase[kPlanCap + 1], l_grp_membase[kPlanCap + 1];
+    __shared__ int32_t l_seq_rank[kPlanCap], l_row_start[2 * kPlanCap + 1];
     const int tid = threadIdx.x;
     const Workspace &w = a.ws;
+    const int B = a.B;
     const int NG = a.share ? a.num_groups : 0;
     const int MPR = a.members_per_row;
+    // intermediates live in LDS when they fit (the usual case), else in the workspace
+    const bool small = B <= kPlanCap && NG <= kPlanCap;
+    int32_t *grp_count = small ? l_grp_count : w.grp_count;
+    int32_t *grp_rowbase = small ? l_grp_rowbase : w.grp_rowbase;
+    int32_t *grp_membase = small ? l_grp_membase : w.grp_membase;
+    int32_t *seq_rank = small ? l_seq_rank : w.seq_rank;
+    int32_t *row_start = small ? l_row_start : w.row_start;
 
-    for (int g = tid; g < NG; g += kPlanThreads) w.grp_count[g] = 0;
+    for (int g = tid; g < NG; g += kPlanThreads) grp_count[g] = 0;
     __syncthreads();
     // membership: a sequence uses the shared pass when its group has shared pages and it holds all of them
-    for (int b = tid; b < a.B; b += kPlanThreads) {
+    for (int b = tid; b < B; b += kPlanThreads) {
         int rank = -1;
         if (NG) {
             int g = a.seq_group[b];
             if (g >= 0 && g < NG) {
                 int np = a.pfx_off[g + 1] - a.pfx_off[g];
-                if (np > 0 && a.seq_lens[b] >= np * kPage) rank = atomicAdd(&w.grp_count[g], 1);
+                if (np > 0 && a.seq_lens[b] >= np * kPage) rank = atomicAdd(&grp_count[g], 1);
             }
         }
-        w.seq_rank[b] = rank;
+        seq_rank[b] = rank;
     }
     __syncthreads();
     int nPR = 0;
     if (NG) {
-        block_scan(w.grp_count, w.grp_membase, NG, scan_tmp);
-        // rows per group = ceil(count / MPR), scanned in place
-        for (int g = tid; g < NG; g += kPlanThreads) w.grp_rowbase[g] = (w.grp_count[g] + MPR - 1) / MPR;
+        block_scan(grp_count, grp_membase, NG, scan_tmp);
+        for (int g = tid; g < NG; g += kPlanThreads) grp_rowbase[g] = (grp_count[g] + MPR - 1) / MPR;
         __syncthreads();
-        block_scan(w.grp_rowbase, w.grp_rowbase, NG, scan_tmp);
-        nPR = w.grp_rowbase[NG];
+        block_scan(grp_rowbase, grp_rowbase, NG, scan_tmp);
+        nPR = grp_rowbase[NG];
     }
-    __syncthreads();
-    const int B = a.B;
+    // rows and their cost (staged in row_start, scanned in place)
     for (int g = tid; g < NG; g += kPlanThreads) {
-        int cnt = w.grp_count[g], np = a.pfx_off[g + 1] - a.pfx_off[g];
-        int r0 = w.grp_rowbase[g], m0 = w.grp_membase[g];
+        int cnt = grp_count[g], np = a.pfx_off[g + 1] - a.pfx_off[g];
+        int r0 = grp_rowbase[g], m0 = grp_membase[g];
         for (int k = 0; k * MPR < cnt; k++) {
             int left = cnt - k * MPR;
-            w.row_units[B + r0 + k] = np;
-            w.row_info[B + r0 + k] = make_int4(g, m0 + k * MPR, left < MPR ? left : MPR, 0);
+            row_start[r0 + k] = np * a.cost_prefix;
+            w.row_info[r0 + k] = make_int4(g, m0 + k * MPR, left < MPR ? left : MPR, np);
         }
     }
     for (int b = tid; b < B; b += kPlanThreads) {
         int L = a.seq_lens[b];
         if (L > a.max_pages * kPage) L = a.max_pages * kPage; // never walk past the table row
-        int rank = w.seq_rank[b];
+        int rank = seq_rank[b];
         int skip = 0, prow = -1;
         if (rank >= 0) {
             int g = a.seq_group[b];
             skip = a.pfx_off[g + 1] - a.pfx_off[g];
-            prow = w.grp_rowbase[g] + rank / MPR;
-            w.members[w.grp_membase[g] + rank] = b;
-            w.seq_rank[b] = rank % MPR;
+            prow = grp_rowbase[g] + rank / MPR;
+            w.members[grp_membase[g] + rank] = b;
+            rank = rank % MPR;
         }
         w.seq_pfx_row[b] = prow;
+        w.seq_rank[b] = rank;
         int pages = L > 0 ? (L + kPage - 1) / kPage - skip : 0;
-        w.row_units[b] = pages;
-        w.row_info[b] = make_int4(b, skip, L - skip * kPage, 0);
+        row_start[nPR + b] = pages * kCostSuffix;
+        w.row_info[nPR + b] = make_int4(b, skip, L - skip * kPage, pages);
     }
     __syncthreads();
     const int nR = B + nPR;
-    block_scan(w.row_units, w.row_start, nR, scan_tmp);
-    const long U = (long)a.Hkv * w.row_start[nR];
-    long upw = (U + a.waves - 1) / a.waves;
-    if (upw < kMinUnitsPerWave) upw = kMinUnitsPerWave;
-    upw += upw & 1;
+    block_scan(row_start, row_start, nR, scan_tmp);
+    // Spans of the cost stream.  The first `waves` spans are equal and assigned one per resident wave; the rest
+    // of the stream is cut into smaller spans that the waves take from a counter as they finish, so that
+    // compute units that happen to get less memory bandwidth than others do not hold the kernel up.
+    const long U = (long)a.Hkv * row_start[nR];
+    const long min_span = (long)kMinUnitsPerWave * kCostSuffix;
+    long S0 = U * a.static_pct / 100 / a.waves;
+    if (S0 < min_span) S0 = min_span;
+    long cd = (long)a.dyn_pages * kCostSuffix;
+    long ndyn = 0;
+    const long Ud = U - S0 * a.waves;
+    if (Ud > 0) {
+        const long most = (long)kDynSpansPerWave * a.waves;
+        if ((Ud + cd - 1) / cd > most) cd = (Ud + most - 1) / most;
+        ndyn = (Ud + cd - 1) / cd;
+    }
+    const int nspans = a.waves + (int)ndyn;
     if (tid == 0) {
         w.hdr[0] = (int)U;
-        w.hdr[1] = (int)upw;
+        w.hdr[1] = (int)S0;
         w.hdr[2] = nR;
         w.hdr[3] = nPR;
+        w.hdr[5] = a.waves; // next span to hand out
+        w.hdr[6] = (int)cd;
+        w.hdr[7] = nspans;
     }
-    // first row of every wave: the last row whose first unit is <= the wave's first unit
-    for (int wv = tid; wv <= a.waves; wv += kPlanThreads) {
-        long target = (long)wv * upw;
-        int lo = 0, hi = nR; // invariant: Hkv*row_start[lo] <= target
+    if (small)
+        for (int r = tid; r <= nR; r += kPlanThreads) w.row_start[r] = row_start[r];
+    // first row of every span: the last row that starts at or before the span's first unit
+    for (int c = tid; c <= nspans; c += kPlanThreads) {
+        long target = c < a.waves ? (long)c * S0 : (long)a.waves * S0 + (long)(c - a.waves) * cd;
+        int lo = 0, hi = nR; // invariant: Hkv*row_start[lo] <= target < Hkv*row_start[hi]
         if (target >= U) lo = nR;
         else
             while (hi - lo > 1) {
                 int mid = (lo + hi) >> 1;
-                if ((long)a.Hkv * w.row_start[mid] <= target) lo = mid;
+                if ((long)a.Hkv * row_start[mid] <= target) lo = mid;
                 else hi = mid;
             }
-        w.wave_first_row[wv] = lo;
+        w.span_first_row[c] = lo;
     }
 }
 
@@ -192,6 +229,22 @@ hipError_t launch_plan(const Launch &a, hipStream_t s)
 {
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, s, a);
     return hipGetLastError();
+}
+
+// The cost stream is cut into spans: `waves` spans of S0 units, then spans of cd units.
+struct Spans {
+    int waves, S0, cd;
+    __device__ __forceinline__ int lo(int c) const { return c < waves ? c * S0 : waves * S0 + (c - waves) * cd; }
+    __device__ __forceinline__ int hi(int c) const { return c < waves ? (c + 1) * S0 : waves * S0 + (c - waves + 1) * cd; }
+    __device__ __forceinline__ int of(int pos) const { return pos < waves * S0 ? pos / S0 : waves + (pos - waves * S0) / cd; }
+};
+
+// Pages [p_lo, p_hi) of an item (first cost unit S, weight cw per page, n pages) that belong to the span
+// [lo, hi) of the cost stream: those whose first unit S + cw*p lies in the span.
+__device__ __forceinline__ void span_pages(int S, int cw, int n, int lo, int hi, int &p_lo, int &p_hi)
+{
+    p_lo = lo <= S ? 0 : min(n, (lo - S + cw - 1) / cw);
+    p_hi = hi <= S ? 0 : min(n, (hi - S + cw - 1) / cw);
 }
 
 // ------------------------------------------------------------------------------------------------------
@@ -205,10 +258,33 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 
 // 16 bytes per lane from global memory straight into LDS at lds_addr + lane*16 (no registers in between).
 // The compiler does not see these as loads, so their completion is tracked by hand with wait_vmcnt().
+// Two address forms: a full 64-bit address per lane, or a wave-uniform base plus a 32-bit lane offset.
 __device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_addr)
 {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr)
                  : "memory", "m0");
+}
+__device__ __forceinline__ void dma16_base(uint32_t lane_off, const void *uniform_base, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(uniform_base),
+                 "s"(lds_addr)
+                 : "memory", "m0");
+}
+
+// Reductions over the four lanes that own one query row (l, l^16, l^32, l^48), on the VALU (no LDS trip).
+__device__ __forceinline__ float row_max(float x)
+{
+    u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float row_sum(float x)
+{
+    u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
 // LDS placement of 16-byte unit c of tile row r: rows are kept whole, units are XOR-swizzled inside the
@@ -220,8 +296,8 @@ template <int D, int KVB> struct Geo {
     static constexpr int kUnits = kRowBytes / 16;       // 16-byte units per row
     static constexpr int kTile = kPage * kRowBytes;     // one (page, head) tile of K or of V
     static constexpr int kDmaPerTile = kTile / 1024;    // wave-wide 16-byte loads per tile
-    static constexpr int kStage = 4 * kTile;            // K0 K1 V0 V1
-    static constexpr int kDmaPerStage = 4 * kDmaPerTile;
+    static constexpr int kStage = 2 * kTile;            // K tile, V tile of one page
+    static constexpr int kDmaPerStage = 2 * kDmaPerTile;
     static constexpr int kKSteps = D / 32;
     static constexpr int kDTiles = D / 16;
 };
@@ -257,73 +333,75 @@ template <int D, int KVB> __device__ __forceinline__ void lane_setup(LaneConst<D
     }
 }
 
-// One tile: rows at or past nvalid come from the zero block instead (so stale or poisoned slots never reach
-// the MFMA, and a page id is only dereferenced when the page exists).
+// One tile.  A full page goes the cheap way (uniform base + lane offset).  In the last page of a sequence
+// the rows at or past nvalid come from the zero block instead, so stale or poisoned slots never reach the
+// MFMA; a page id is only dereferenced when the page exists.
 template <int D, int KVB>
 __device__ __forceinline__ void issue_tile(const LaneConst<D, KVB> &lc, const uint8_t *tile, int nvalid, uint32_t lds_addr,
                                            const void *zeros)
 {
     using G = Geo<D, KVB>;
+    if (nvalid >= kPage) {
 #pragma unroll
-    for (int n = 0; n < G::kDmaPerTile; n++) {
-        const void *src = lc.dma_row[n] < nvalid ? (const void *)(tile + lc.dma_off[n]) : zeros;
-        dma16(src, lds_addr + 1024 * n);
+        for (int n = 0; n < G::kDmaPerTile; n++) dma16_base((uint32_t)lc.dma_off[n], tile, lds_addr + 1024 * n);
+    } else {
+#pragma unroll
+        for (int n = 0; n < G::kDmaPerTile; n++) {
+            const void *src = lc.dma_row[n] < nvalid ? (const void *)(tile + lc.dma_off[n]) : zeros;
+            dma16(src, lds_addr + 1024 * n);
+        }
     }
 }
 
 struct Segment {
     const int32_t *__restrict__ pages; // page ids of the work row (uniform)
-    int pg_lo, pg_hi;     // pages of the row this wave covers
-    int limit;            // tokens of the row that exist and belong to this span: min(valid, 16*pg_hi)
+    int pg_lo, pg_hi;                  // pages of the row this wave covers
+    int limit;                         // tokens of the row that exist and belong to this span: min(valid, 16*pg_hi)
     int kvh;
 };
 
+// Waits until at most min(stages_after, N) younger stages of DPS loads each are still in flight.
+template <int N, int DPS> struct WaitTail {
+    static __device__ __forceinline__ void run(int stages_after)
+    {
+        if (stages_after >= N) wait_vmcnt<N * DPS>();
+        else WaitTail<N - 1, DPS>::run(stages_after);
+    }
+};
+template <int DPS> struct WaitTail<0, DPS> {
+    static __device__ __forceinline__ void run(int) { wait_vmcnt<0>(); }
+};
+
 // Attention of NQT*16 query rows over the pages [pg_lo, pg_hi) of one work row; writes the normalised
-// partial output and its log2-sum-exp.
-//   S^T[key, row] = K_tile . Q^T      (A = K rows straight from LDS, B = Q held in registers)
-//   O^T[d, row]  += V_tile^T . P^T    (A = V through the transposing LDS read, B = P repacked in place)
+// partial output and its log2-sum-exp.  One page (16 keys) per ring stage:
+//   S^T[key, row] = K_tile . Q^T      (16x16x32 MFMA over D; A = K rows straight from LDS, B = Q in registers)
+//   O^T[d, row]  += V_tile^T . P^T    (16x16x16 MFMA over the 16 keys; A = V through the transposing LDS read,
+//                                      B = P, which is the S^T accumulator layout as it stands)
 // In both products a lane owns one query row (lane % 16), so the running max, the rescale factor and the
 // row sum are per-lane scalars; only the row max needs a cross-lane step (lanes l, l^16, l^32, l^48).
-template <int D, int NQT>
+template <int D, int NQT, int NST>
 __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__restrict__ q, const Segment &sg,
                                             const LaneConst<D, 2> &lc, uint8_t *lds, uint32_t lds_addr,
                                             const int (&qrow_seq)[NQT], const int (&qrow_head)[NQT], float *part_o,
                                             float *part_lse, int part_rows)
 {
     using G = Geo<D, 2>;
+    static_assert((NST - 1) * G::kDmaPerStage < 64, "the vector-memory counter holds 6 bits");
     const int lane = threadIdx.x, j = lane >> 4;
+    const int niter = sg.pg_hi - sg.pg_lo;
 
-    const int npages = sg.pg_hi - sg.pg_lo;
-    const int niter = (npages + 1) >> 1;
-
-    auto tile_ptr = [&](const uint8_t *pool, int pid) {
-        return pool + (int64_t)pid * a.stride_page_b + (int64_t)sg.kvh * a.stride_head_b;
+    auto issue = [&](int it, int pid) {
+        int nv = sg.limit - (sg.pg_lo + it) * kPage;
+        nv = nv > kPage ? kPage : nv;
+        const uint32_t sb = lds_addr + (it % NST) * G::kStage;
+        const int64_t off = (int64_t)pid * a.stride_page_b + (int64_t)sg.kvh * a.stride_head_b;
+        issue_tile<D, 2>(lc, a.k_pool + off, nv, sb, a.zeros);
+        issue_tile<D, 2>(lc, a.v_pool + off, nv, sb + G::kTile, a.zeros);
     };
-    auto issue = [&](int it, int pid0, int pid1) {
-        const int p0 = sg.pg_lo + 2 * it;
-        int nv0 = sg.limit - p0 * kPage, nv1 = nv0 - kPage;
-        nv0 = nv0 > kPage ? kPage : nv0;
-        nv1 = nv1 > kPage ? kPage : (nv1 < 0 ? 0 : nv1);
-        const uint32_t sb = lds_addr + (it % kStages) * G::kStage;
-        issue_tile<D, 2>(lc, tile_ptr(a.k_pool, pid0), nv0, sb, a.zeros);
-        issue_tile<D, 2>(lc, tile_ptr(a.k_pool, pid1), nv1, sb + G::kTile, a.zeros);
-        issue_tile<D, 2>(lc, tile_ptr(a.v_pool, pid0), nv0, sb + 2 * G::kTile, a.zeros);
-        issue_tile<D, 2>(lc, tile_ptr(a.v_pool, pid1), nv1, sb + 3 * G::kTile, a.zeros);
-    };
-    auto page_id = [&](int it, int h) {
-        int p = sg.pg_lo + 2 * it + h;
+    auto page_id = [&](int it) {
+        int p = sg.pg_lo + it;
         return p < sg.pg_hi ? sg.pages[p] : 0;
     };
-
-    // page ids run one stage ahead of the loads that use them
-    int nid0 = page_id(0, 0), nid1 = page_id(0, 1);
-#pragma unroll
-    for (int s = 0; s < kStages - 1; s++)
-        if (s < niter) {
-            issue(s, nid0, nid1);
-            nid0 = page_id(s + 1, 0);
-            nid1 = page_id(s + 1, 1);
-        }
 
     // Q^T operand: lane (row = lane%16, j) holds d = 32*i + 8*j .. +7 of its row for k-step i
     bf16x8 qf[NQT][G::kKSteps];
@@ -337,6 +415,16 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
             qf[t][i] = v;
         }
     }
+
+    // page ids run one stage ahead of the loads that use them
+    int nid = page_id(0);
+#pragma unroll
+    for (int s = 0; s < NST - 1; s++)
+        if (s < niter) {
+            issue(s, nid);
+            nid = page_id(s + 1);
+        }
+
     // Make the compiler wait for the query loads here, once, instead of at their first use inside the loop
     // (where a full vector-memory wait would drain the ring every iteration).
 #pragma unroll
@@ -356,78 +444,61 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
     }
 
     for (int it = 0; it < niter; it++) {
-        if (it + kStages - 1 < niter) {
-            issue(it + kStages - 1, nid0, nid1);
-            nid0 = page_id(it + kStages, 0);
-            nid1 = page_id(it + kStages, 1);
-            wait_vmcnt<(kStages - 1) * G::kDmaPerStage>();
+        if (it + NST - 1 < niter) {
+            issue(it + NST - 1, nid);
+            nid = page_id(it + NST);
+            wait_vmcnt<(NST - 1) * G::kDmaPerStage>();
         } else {
-            wait_vmcnt<0>();
+            WaitTail<NST - 2, G::kDmaPerStage>::run(niter - 1 - it);
         }
-        const uint8_t *st = lds + (it % kStages) * G::kStage;
+        const uint8_t *st = lds + (it % NST) * G::kStage;
 
-        // scores
-        f32x4 s[NQT][2];
+        // scores of the 16 keys of this page
+        f32x4 s[NQT];
 #pragma unroll
-        for (int pg = 0; pg < 2; pg++) {
+        for (int t = 0; t < NQT; t++) s[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int t = 0; t < NQT; t++) s[t][pg] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < G::kKSteps; i++) {
+            bf16x8 kf = *(const bf16x8 *)(st + lc.k_off[i]);
 #pragma unroll
-            for (int i = 0; i < G::kKSteps; i++) {
-                bf16x8 kf = *(const bf16x8 *)(st + pg * G::kTile + lc.k_off[i]);
-#pragma unroll
-                for (int t = 0; t < NQT; t++)
-                    s[t][pg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[t][i], s[t][pg], 0, 0, 0);
-            }
+            for (int t = 0; t < NQT; t++) s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[t][i], s[t], 0, 0, 0);
         }
-        const int tok0 = (sg.pg_lo + 2 * it) * kPage + 4 * j; // this lane's first token in page 0 of the stage
-        const bool ragged = (sg.pg_lo + 2 * it + 2) * kPage > sg.limit;
-        bf16x8 pf[NQT];
+        const int tok0 = (sg.pg_lo + it) * kPage + 4 * j; // this lane's first token of the page
+        const bool ragged = (sg.pg_lo + it + 1) * kPage > sg.limit;
+        s16x4 pf[NQT];
 #pragma unroll
         for (int t = 0; t < NQT; t++) {
-            float v[8];
-#pragma unroll
-            for (int e = 0; e < 4; e++) {
-                v[e] = s[t][0][e] * a.scale_log2;
-                v[4 + e] = s[t][1][e] * a.scale_log2;
-            }
+            f32x4 v = s[t] * a.scale_log2;
             if (ragged) {
 #pragma unroll
-                for (int e = 0; e < 4; e++) {
+                for (int e = 0; e < 4; e++)
                     if (tok0 + e >= sg.limit) v[e] = -INFINITY;
-                    if (tok0 + kPage + e >= sg.limit) v[4 + e] = -INFINITY;
-                }
             }
-            float mx = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float mx = row_max(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])));
             const float mn = fmaxf(m[t], mx);
-            const float alpha = __builtin_amdgcn_exp2f(m[t] - mn);
-            m[t] = mn;
-            f32x8 p;
-            float ps = 0.f;
+            f32x4 p;
 #pragma unroll
-            for (int e = 0; e < 8; e++) {
-                p[e] = __builtin_amdgcn_exp2f(v[e] - mn);
-                ps += p[e];
+            for (int e = 0; e < 4; e++) p[e] = __builtin_amdgcn_exp2f(v[e] - mn);
+            const float ps = (p[0] + p[1]) + (p[2] + p[3]);
+            pf[t] = __builtin_bit_cast(s16x4, __builtin_convertvector(p, bf16x4));
+            // the running max rarely moves after the first pages: rescale only when some row's did
+            if (__any(mn != m[t])) {
+                const float alpha = __builtin_amdgcn_exp2f(m[t] - mn);
+                m[t] = mn;
+                lsum[t] *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < G::kDTiles; dt++) o[t][dt] *= alpha;
             }
-            lsum[t] = lsum[t] * alpha + ps;
-            pf[t] = __builtin_convertvector(p, bf16x8);
-#pragma unroll
-            for (int dt = 0; dt < G::kDTiles; dt++) o[t][dt] *= alpha;
+            lsum[t] += ps;
         }
         // O^T += V^T P^T
         typedef s16x4 __attribute__((address_space(3))) * lds_s16x4;
-        const uint32_t vb = lds_addr + (it % kStages) * G::kStage + 2 * G::kTile;
+        const uint32_t vb = lds_addr + (it % NST) * G::kStage + G::kTile;
 #pragma unroll
         for (int dt = 0; dt < G::kDTiles; dt++) {
-            s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(vb + lc.v_off[dt]));
-            s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(vb + G::kTile + lc.v_off[dt]));
-            typedef short s16x8 __attribute__((ext_vector_type(8)));
-            s16x8 vv = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-            bf16x8 vf = __builtin_bit_cast(bf16x8, vv);
+            s16x4 vf = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(vb + lc.v_off[dt]));
 #pragma unroll
-            for (int t = 0; t < NQT; t++) o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[t], o[t][dt], 0, 0, 0);
+            for (int t = 0; t < NQT; t++) o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf, pf[t], o[t][dt], 0, 0, 0);
         }
         // every LDS read of this stage has returned before a later load may overwrite it
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -436,9 +507,7 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
     // normalise and store the partial
 #pragma unroll
     for (int t = 0; t < NQT; t++) {
-        float l = lsum[t];
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
+        const float l = row_sum(lsum[t]);
         const int row = 16 * t + (lane & 15);
         if (row < part_rows) {
             const float inv = 1.0f / l;
@@ -453,172 +522,244 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
 // The read-only inputs and the schedule come in as separate restrict pointers so that the compiler can keep
 // every wave-uniform lookup (page ids, row bounds) on the scalar unit, away from the vector-memory counter
 // that paces the LDS ring.
-template <int D>
-__global__ __launch_bounds__(64) void attention_kernel(Launch a, const uint16_t *__restrict__ q,
-                                                       const int32_t *__restrict__ block_table,
-                                                       const int32_t *__restrict__ pfx_off,
-                                                       const int32_t *__restrict__ pfx_pages, const int32_t *__restrict__ hdr,
-                                                       const int32_t *__restrict__ row_start, const int4 *__restrict__ row_info,
-                                                       const int32_t *__restrict__ wave_first_row,
-                                                       const int32_t *__restrict__ members)
+#define RA_ATTN_PARAMS                                                                                                    \
+    Launch a, const uint16_t *__restrict__ q, const int32_t *__restrict__ block_table, const int32_t *__restrict__ pfx_off, \
+        const int32_t *__restrict__ pfx_pages, const int32_t *__restrict__ hdr, const int32_t *__restrict__ row_start,     \
+        const int4 *__restrict__ row_info, const int32_t *__restrict__ span_first_row, const int32_t *__restrict__ members
+#define RA_ATTN_ARGS a, q, block_table, pfx_off, pfx_pages, hdr, row_start, row_info, span_first_row, members
+
+template <int D, int NST> __device__ __forceinline__ void attention_body(RA_ATTN_PARAMS, int32_t *next_span)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     const uint32_t lds_addr = (uint32_t)(uintptr_t)lds;
     const Workspace &w = a.ws;
     const int lane = threadIdx.x;
-    const int wave = blockIdx.x;
-    const int U = hdr[0], upw = hdr[1];
-    int u = wave * upw;
-    const int u_hi = min(U, u + upw);
-    if (u >= u_hi) return;
+    const int U = hdr[0], nR = hdr[2], nPR = hdr[3], nspans = hdr[7];
+    Spans sp;
+    sp.waves = a.waves;
+    sp.S0 = hdr[1];
+    sp.cd = hdr[6];
 
     LaneConst<D, 2> lc;
     lane_setup<D, 2>(lc, lane, a.stride_token_b);
 
-    int r = wave_first_row[wave];
-    while (u < u_hi) {
-        while (a.Hkv * row_start[r + 1] <= u) r++;
-        const int rs = row_start[r];
-        const int units = row_start[r + 1] - rs;
-        const int rel = u - a.Hkv * rs;
-        Segment sg;
-        sg.kvh = rel / units;
-        sg.pg_lo = rel - sg.kvh * units;
-        sg.pg_hi = min(units, sg.pg_lo + (u_hi - u));
-        const int4 info = row_info[r];
-        if (r < a.B) {
-            // a sequence's own pages: the G query heads of this kv head form one 16-row tile
-            const int b = info.x;
-            sg.pages = block_table + (int64_t)b * a.max_pages + info.y;
-            sg.limit = min(info.z, sg.pg_hi * kPage);
-            const int slot = r * a.Hkv + sg.kvh + wave;
-            int qs[1], qh[1];
-            const int row = lane & 15;
-            qs[0] = row < a.G ? b : -1;
-            qh[0] = sg.kvh * a.G + row;
-            run_segment<D, 1>(a, q, sg, lc, lds, lds_addr, qs, qh, w.suf_o + (int64_t)slot * a.G * D,
-                              w.suf_lse + (int64_t)slot * a.G, a.G);
-        } else {
-            // shared prompt pages of a group: rows = members x G, packed densely into four 16-row tiles
-            const int g = info.x;
-            sg.pages = pfx_pages + pfx_off[g];
-            sg.limit = sg.pg_hi * kPage;
-            const int slot = (r - a.B) * a.Hkv + sg.kvh + wave;
-            const int nrows = info.z * a.G;
-            int qs[4], qh[4];
+    int span = blockIdx.x;
+    while (span < nspans) {
+        const int u_lo = sp.lo(span);
+        const int u_hi = min(U, sp.hi(span));
+        if (u_lo >= u_hi) break;
+        // take the next span now; the answer is needed only when this one is done
+        int next = 0;
+        if (lane == 0) next = atomicAdd(next_span, 1);
+
+        for (int r = span_first_row[span]; r < nR; r++) {
+            const int rs = a.Hkv * row_start[r];
+            if (rs >= u_hi) break;
+            const int4 info = row_info[r];
+            const int units = info.w;
+            if (units == 0) continue;
+            const bool prefix = r < nPR;
+            const int cw = prefix ? a.cost_prefix : kCostSuffix;
+            const int ic = cw * units; // cost of one (row, kv head) item
+            int kvh = u_lo > rs ? (u_lo - rs) / ic : 0;
+            for (; kvh < a.Hkv; kvh++) {
+                const int S = rs + kvh * ic;
+                if (S >= u_hi) break;
+                Segment sg;
+                sg.kvh = kvh;
+                span_pages(S, cw, units, u_lo, u_hi, sg.pg_lo, sg.pg_hi);
+                if (sg.pg_lo >= sg.pg_hi) continue;
+                if (!prefix) {
+                    // a sequence's own pages: the G query heads of this kv head form one 16-row tile
+                    const int b = info.x;
+                    sg.pages = block_table + (int64_t)b * a.max_pages + info.y;
+                    sg.limit = min(info.z, sg.pg_hi * kPage);
+                    const int slot = b * a.Hkv + kvh + span;
+                    int qs[1], qh[1];
+                    const int row = lane & 15;
+                    qs[0] = row < a.G ? b : -1;
+                    qh[0] = kvh * a.G + row;
+                    run_segment<D, 1, NST>(a, q, sg, lc, lds, lds_addr, qs, qh, w.suf_o + (int64_t)slot * a.G * D,
+                                           w.suf_lse + (int64_t)slot * a.G, a.G);
+                } else {
+                    // shared prompt pages of a group: rows = members x G, packed densely into 16-row tiles
+                    const int g = info.x;
+                    sg.pages = pfx_pages + pfx_off[g];
+                    sg.limit = sg.pg_hi * kPage;
+                    const int slot = r * a.Hkv + kvh + span;
+                    const int nrows = info.z * a.G;
+                    int qs[kPrefixTiles], qh[kPrefixTiles];
 #pragma unroll
-            for (int t = 0; t < 4; t++) {
-                const int row = 16 * t + (lane & 15);
-                const int mi = row / a.G;
-                qs[t] = row < nrows ? members[info.y + mi] : -1;
-                qh[t] = sg.kvh * a.G + (row - mi * a.G);
+                    for (int t = 0; t < kPrefixTiles; t++) {
+                        const int row = 16 * t + (lane & 15);
+                        const int mi = row / a.G;
+                        qs[t] = row < nrows ? members[info.y + mi] : -1;
+                        qh[t] = kvh * a.G + (row - mi * a.G);
+                    }
+                    run_segment<D, kPrefixTiles, NST>(a, q, sg, lc, lds, lds_addr, qs, qh,
+                                                      w.pfx_o + (int64_t)slot * kPrefixRows * D,
+                                                      w.pfx_lse + (int64_t)slot * kPrefixRows, nrows);
+                }
             }
-            run_segment<D, 4>(a, q, sg, lc, lds, lds_addr, qs, qh, w.pfx_o + (int64_t)slot * kPrefixRows * D,
-                              w.pfx_lse + (int64_t)slot * kPrefixRows, nrows);
         }
-        u += sg.pg_hi - sg.pg_lo;
+        span = __builtin_amdgcn_readfirstlane(next);
     }
 }
 
-static size_t attention_lds_bytes(int D) { return (size_t)kStages * (D == 128 ? Geo<128, 2>::kStage : Geo<64, 2>::kStage); }
+// Two ring depths: four stages with one wave per SIMD, or two stages with two waves per SIMD (256 VGPRs each).
+template <int D> __global__ __launch_bounds__(64) void attention_kernel_s4(RA_ATTN_PARAMS, int32_t *next_span)
+{
+    attention_body<D, 4>(RA_ATTN_ARGS, next_span);
+}
+template <int D>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attention_kernel_s2(RA_ATTN_PARAMS, int32_t *next_span)
+{
+    attention_body<D, 2>(RA_ATTN_ARGS, next_span);
+}
 
-hipError_t attention_waves(int D, int kv_fp8, int num_cus, int *waves)
+static size_t attention_lds_bytes(int D, int stages) { return (size_t)stages * (D == 128 ? Geo<128, 2>::kStage : Geo<64, 2>::kStage); }
+
+static const void *attention_fn(int D, int stages)
+{
+    if (stages == 2) return D == 128 ? (const void *)attention_kernel_s2<128> : (const void *)attention_kernel_s2<64>;
+    return D == 128 ? (const void *)attention_kernel_s4<128> : (const void *)attention_kernel_s4<64>;
+}
+
+hipError_t attention_config(int D, int kv_fp8, int num_cus, int *stages, int *waves)
 {
     (void)kv_fp8;
-    const void *fn = D == 128 ? (const void *)attention_kernel<128> : (const void *)attention_kernel<64>;
-    size_t lds = attention_lds_bytes(D);
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    int st = 4, per_cu = 4;
+    if (const char *ev = getenv("ROLLOUT_ATTN_STAGES")) st = atoi(ev) == 2 ? 2 : 4;
+    if (st == 2) per_cu = 8;
+    if (const char *ev = getenv("ROLLOUT_ATTN_WAVES_PER_CU")) {
+        int v = atoi(ev);
+        if (v >= 1 && v <= 16) per_cu = v;
+    }
+    size_t lds = attention_lds_bytes(D, st);
+    hipError_t e = hipFuncSetAttribute(attention_fn(D, st), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    int per_cu = 0;
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 64, lds);
-    if (e != hipSuccess) return e;
-    if (per_cu < 1) per_cu = 1;
-    if (per_cu > 4) per_cu = 4; // one wave per SIMD; more adds nothing once HBM is saturated
+    *stages = st;
     *waves = per_cu * num_cus;
     return hipSuccess;
 }
 
 hipError_t launch_attention(const Launch &a, hipStream_t s)
 {
-    size_t lds = attention_lds_bytes(a.D);
+    size_t lds = attention_lds_bytes(a.D, a.stages);
     const Workspace &w = a.ws;
-    if (a.D == 128)
-        hipLaunchKernelGGL(attention_kernel<128>, dim3(a.waves), dim3(64), lds, s, a, a.q, a.block_table, a.pfx_off, a.pfx_pages,
-                           w.hdr, w.row_start, w.row_info, w.wave_first_row, w.members);
-    else
-        hipLaunchKernelGGL(attention_kernel<64>, dim3(a.waves), dim3(64), lds, s, a, a.q, a.block_table, a.pfx_off, a.pfx_pages,
-                           w.hdr, w.row_start, w.row_info, w.wave_first_row, w.members);
+#define RA_LAUNCH(K)                                                                                                      \
+    hipLaunchKernelGGL(K, dim3(a.waves), dim3(64), lds, s, a, a.q, a.block_table, a.pfx_off, a.pfx_pages, w.hdr, w.row_start, \
+                       w.row_info, w.span_first_row, w.members, w.hdr + 5)
+    if (a.stages == 2) {
+        if (a.D == 128) RA_LAUNCH(attention_kernel_s2<128>);
+        else RA_LAUNCH(attention_kernel_s2<64>);
+    } else {
+        if (a.D == 128) RA_LAUNCH(attention_kernel_s4<128>);
+        else RA_LAUNCH(attention_kernel_s4<64>);
+    }
+#undef RA_LAUNCH
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------------------
-// merge: out[b,h] and lse[b,h] from the partials of the shared-prefix row and of the sequence's own spans
+// merge: out[b,h] and lse[b,h] from the partials of the shared-prefix row and of the sequence's own spans.
+// One workgroup per (sequence, kv head); a thread owns four output elements of one of its G heads.
+// With weights w_i = 2^(lse2_i - M): out = sum w_i o_i / sum w_i, lse = (M + log2 sum w_i) ln 2, always in
+// the same order (prefix spans, then own spans, by wave), so results are reproducible bit for bit.
 // ------------------------------------------------------------------------------------------------------
 
-__global__ void merge_kernel(Launch a)
+constexpr int kMergeThreads = 256;
+
+struct PartList {
+    const float *o, *lse;   // slot 0 of the item (span offset not yet added)
+    int64_t ostride, lstride;
+    int S, cw, n, c_lo, c_hi;
+};
+
+__global__ __launch_bounds__(kMergeThreads) void merge_kernel(Launch a, const int32_t *__restrict__ hdr,
+                                                               const int32_t *__restrict__ row_start,
+                                                               const int4 *__restrict__ row_info,
+                                                               const int32_t *__restrict__ seq_pfx_row,
+                                                               const int32_t *__restrict__ seq_rank)
 {
     const Workspace &w = a.ws;
-    const int bh = blockIdx.x, b = bh / a.Hq, h = bh - b * a.Hq;
-    const int kvh = h / a.G, hl = h - kvh * a.G;
-    const int d = threadIdx.x;
-    const int upw = w.hdr[1];
-    const int D = a.D;
-
-    // two lists of partials: [0] own pages (row b), [1] shared prefix (row B + seq_pfx_row[b])
-    const float *po[2], *pl[2];
-    int cnt[2];
-    int64_t ostride[2], lstride[2];
+    const int b = blockIdx.x / a.Hkv, kvh = blockIdx.x - b * a.Hkv;
+    const int nPR = hdr[3];
+    Spans sp;
+    sp.waves = a.waves;
+    sp.S0 = hdr[1];
+    sp.cd = hdr[6];
+    const int D = a.D, tpr = D / 4; // threads per output row
+    PartList pl[2];
     {
-        const int units = w.row_start[b + 1] - w.row_start[b];
-        const int64_t s0 = (int64_t)a.Hkv * w.row_start[b] + (int64_t)kvh * units;
-        const int w_lo = (int)(s0 / upw), w_hi = units > 0 ? (int)((s0 + units - 1) / upw) : w_lo - 1;
-        const int64_t slot = (int64_t)b * a.Hkv + kvh + w_lo;
-        po[0] = w.suf_o + (slot * a.G + hl) * D;
-        pl[0] = w.suf_lse + slot * a.G + hl;
-        ostride[0] = (int64_t)a.G * D;
-        lstride[0] = a.G;
-        cnt[0] = w_hi - w_lo + 1;
+        const int r = nPR + b;
+        PartList &p = pl[1];
+        p.n = row_info[r].w;
+        p.cw = kCostSuffix;
+        p.S = a.Hkv * row_start[r] + kvh * p.cw * p.n;
+        p.c_lo = sp.of(p.S);
+        p.c_hi = p.n > 0 ? sp.of(p.S + p.cw * (p.n - 1)) : p.c_lo - 1;
+        const int64_t item = (int64_t)b * a.Hkv + kvh;
+        p.o = w.suf_o + item * a.G * D;
+        p.lse = w.suf_lse + item * a.G;
+        p.ostride = (int64_t)a.G * D;
+        p.lstride = a.G;
     }
-    const int prow = w.seq_pfx_row[b];
-    if (prow >= 0) {
-        const int r = a.B + prow;
-        const int units = w.row_start[r + 1] - w.row_start[r];
-        const int64_t s0 = (int64_t)a.Hkv * w.row_start[r] + (int64_t)kvh * units;
-        const int w_lo = (int)(s0 / upw), w_hi = (int)((s0 + units - 1) / upw);
-        const int64_t slot = (int64_t)prow * a.Hkv + kvh + w_lo;
-        const int row = w.seq_rank[b] * a.G + hl;
-        po[1] = w.pfx_o + (slot * kPrefixRows + row) * D;
-        pl[1] = w.pfx_lse + slot * kPrefixRows + row;
-        ostride[1] = (int64_t)kPrefixRows * D;
-        lstride[1] = kPrefixRows;
-        cnt[1] = w_hi - w_lo + 1;
-    } else {
-        cnt[1] = 0;
-        po[1] = po[0];
-        pl[1] = pl[0];
-        ostride[1] = lstride[1] = 0;
-    }
-    float M = -INFINITY;
-    for (int k = 0; k < 2; k++)
-        for (int i = 0; i < cnt[k]; i++) M = fmaxf(M, pl[k][i * lstride[k]]);
-    float acc = 0.f, wsum = 0.f;
-    for (int k = 1; k >= 0; k--) // fixed order: shared prefix first, then own spans in token order
-        for (int i = 0; i < cnt[k]; i++) {
-            const float wgt = __builtin_amdgcn_exp2f(pl[k][i * lstride[k]] - M);
-            wsum += wgt;
-            acc += wgt * po[k][i * ostride[k] + d];
+    const int prow = seq_pfx_row[b];
+    {
+        PartList &p = pl[0];
+        if (prow >= 0) {
+            p.n = row_info[prow].w;
+            p.cw = a.cost_prefix;
+            p.S = a.Hkv * row_start[prow] + kvh * p.cw * p.n;
+            p.c_lo = sp.of(p.S);
+            p.c_hi = sp.of(p.S + p.cw * (p.n - 1));
+            const int64_t item = (int64_t)prow * a.Hkv + kvh;
+            const int row0 = seq_rank[b] * a.G;
+            p.o = w.pfx_o + (item * kPrefixRows + row0) * D;
+            p.lse = w.pfx_lse + item * kPrefixRows + row0;
+            p.ostride = (int64_t)kPrefixRows * D;
+            p.lstride = kPrefixRows;
+        } else {
+            p = pl[1];
+            p.c_hi = p.c_lo - 1;
         }
-    const bool empty = cnt[0] + cnt[1] == 0;
-    const float res = empty ? 0.f : acc / wsum;
-    __bf16 ob = (__bf16)res;
-    a.out[(int64_t)bh * D + d] = __builtin_bit_cast(uint16_t, ob);
-    if (d == 0) a.lse[bh] = empty ? -INFINITY : (M + __builtin_amdgcn_logf(wsum)) * 0.6931471805599453f;
+    }
+    for (int hl = threadIdx.x / tpr; hl < a.G; hl += kMergeThreads / tpr) {
+        const int d4 = (threadIdx.x % tpr) * 4;
+        float M = -INFINITY;
+        for (int k = 0; k < 2; k++)
+            for (int c = pl[k].c_lo; c <= pl[k].c_hi; c++) {
+                int p_lo, p_hi;
+                span_pages(pl[k].S, pl[k].cw, pl[k].n, sp.lo(c), sp.hi(c), p_lo, p_hi);
+                if (p_lo < p_hi) M = fmaxf(M, pl[k].lse[c * pl[k].lstride + hl]);
+            }
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        float wsum = 0.f;
+        for (int k = 0; k < 2; k++)
+            for (int c = pl[k].c_lo; c <= pl[k].c_hi; c++) {
+                int p_lo, p_hi;
+                span_pages(pl[k].S, pl[k].cw, pl[k].n, sp.lo(c), sp.hi(c), p_lo, p_hi);
+                if (p_lo >= p_hi) continue;
+                const float wgt = __builtin_amdgcn_exp2f(pl[k].lse[c * pl[k].lstride + hl] - M);
+                wsum += wgt;
+                acc += wgt * *(const f32x4 *)(pl[k].o + c * pl[k].ostride + (int64_t)hl * D + d4);
+            }
+        const bool empty = wsum == 0.f;
+        const float inv = empty ? 0.f : 1.0f / wsum;
+        const int64_t bh = (int64_t)b * a.Hq + kvh * a.G + hl;
+        bf16x4 ob = __builtin_convertvector(acc * inv, bf16x4);
+        *(bf16x4 *)(a.out + bh * D + d4) = ob;
+        if (d4 == 0) a.lse[bh] = empty ? -INFINITY : (M + __builtin_amdgcn_logf(wsum)) * 0.6931471805599453f;
+    }
 }
 
 hipError_t launch_merge(const Launch &a, hipStream_t s)
 {
     if (a.B == 0) return hipSuccess;
-    hipLaunchKernelGGL(merge_kernel, dim3(a.B * a.Hq), dim3(a.D), 0, s, a);
+    const Workspace &w = a.ws;
+    hipLaunchKernelGGL(merge_kernel, dim3(a.B * a.Hkv), dim3(kMergeThreads), 0, s, a, w.hdr, w.row_start, w.row_info,
+                       w.seq_pfx_row, w.seq_rank);
     return hipGetLastError();
 }
 
