@@ -11,8 +11,8 @@
 struct ra_ctx {
     int device;
     int num_cus;
-    int waves[2];  // resident attention waves for D = 64, 128
-    int stages[2]; // LDS ring depth for D = 64, 128
+    int waves[2][2];  // resident attention waves, [e4m3 KV][D == 128]
+    int stages[2][2]; // LDS ring depth, same indices
     int cost_prefix; // scheduling weight of a shared-prefix page
     int static_pct;  // share of the work that is assigned to waves up front
     int dyn_pages;   // pages per dynamically scheduled span
@@ -64,7 +64,6 @@ ra_status check(const ra_problem *p, char *msg, size_t n)
     if (p->page_size != 16) return fail(RA_ERR_UNSUPPORTED, "page_size=%d (only 16 is supported)", p->page_size);
     if (p->D != 64 && p->D != 128) return fail(RA_ERR_UNSUPPORTED, "D=%d (only 64 and 128 are supported)", p->D);
     if (p->Hq / p->Hkv > 16) return fail(RA_ERR_UNSUPPORTED, "Hq/Hkv=%d (at most 16 is supported)", p->Hq / p->Hkv);
-    if (p->kv_dtype == RA_KV_FP8_E4M3) return fail(RA_ERR_UNSUPPORTED, "fp8 KV is not implemented yet");
     if ((int64_t)p->B * p->Hq > (int64_t)1 << 30 || (int64_t)p->B * p->max_pages_per_seq > (int64_t)1 << 40)
         return fail(RA_ERR_UNSUPPORTED, "batch too large");
     if (p->B == 0) return RA_OK;
@@ -94,8 +93,8 @@ void fill_launch(ra::Launch &a, const ra_ctx *ctx, const ra_problem *p)
     a.num_pages = p->num_pages; a.max_pages = p->max_pages_per_seq; a.num_groups = p->num_groups;
     a.kv_fp8 = p->kv_dtype == RA_KV_FP8_E4M3;
     a.share = p->num_groups > 0 && !(p->flags & RA_FLAG_NO_PREFIX_SHARING);
-    a.waves = ctx ? ctx->waves[p->D == 128] : 2048;
-    a.stages = ctx ? ctx->stages[p->D == 128] : 4;
+    a.waves = ctx ? ctx->waves[a.kv_fp8][p->D == 128] : 2048;
+    a.stages = ctx ? ctx->stages[a.kv_fp8][p->D == 128] : 4;
     a.members_per_row = ra::kPrefixRows / a.G;
     a.cost_prefix = ctx ? ctx->cost_prefix : ra::kCostPrefix;
     a.static_pct = ctx ? ctx->static_pct : 100;
@@ -156,8 +155,9 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
     if (e == hipSuccess) e = hipMemset(c->zeros, 0, 256);
     if (e == hipSuccess) e = hipHostMalloc((void **)&c->host_flags, 64, hipHostMallocDefault);
     for (int i = 0; i < 4 && e == hipSuccess; i++) e = hipEventCreate(&c->ev[i]);
-    if (e == hipSuccess) e = ra::attention_config(64, 0, c->num_cus, &c->stages[0], &c->waves[0]);
-    if (e == hipSuccess) e = ra::attention_config(128, 0, c->num_cus, &c->stages[1], &c->waves[1]);
+    for (int f = 0; f < 2; f++)
+        for (int d = 0; d < 2; d++)
+            if (e == hipSuccess) e = ra::attention_config(d ? 128 : 64, f, c->num_cus, &c->stages[f][d], &c->waves[f][d]);
     (void)hipSetDevice(prev);
     if (e != hipSuccess) {
         set_err(nullptr, "context set-up on device %d: %s", device, hipGetErrorString(e));
@@ -201,7 +201,7 @@ ra_status rollout_attn_workspace_size(const ra_ctx *c, const ra_problem *p, size
         return RA_ERR_UNSUPPORTED;
     }
     ra::Workspace ws;
-    int waves = c ? c->waves[p->D == 128] : 2048;
+    int waves = c ? c->waves[p->kv_dtype == RA_KV_FP8_E4M3][p->D == 128] : 2048;
     *bytes = ra::carve_workspace(ws, nullptr, p->B, p->Hkv, p->Hq / p->Hkv, p->D, p->num_groups, waves);
     return RA_OK;
 }

@@ -271,6 +271,11 @@ __device__ __forceinline__ void dma16_base(uint32_t lane_off, const void *unifor
                  : "memory", "m0");
 }
 
+__device__ __forceinline__ void dma4(const void *gptr, uint32_t lds_addr) // 4 bytes per lane, to lds_addr + lane*4
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(gptr), "s"(lds_addr) : "memory", "m0");
+}
+
 // Reductions over the four lanes that own one query row (l, l^16, l^32, l^48), on the VALU (no LDS trip).
 __device__ __forceinline__ float row_max(float x)
 {
@@ -291,21 +296,24 @@ __device__ __forceinline__ float row_sum(float x)
 // row so that the 16 rows of an MFMA operand read and the 4 rows of a transposed read spread over banks.
 __device__ __forceinline__ int swz(int r) { return 2 * (r & 3) + ((r >> 2) & 1); }
 
+// Geometry of a page in LDS for head dim D and KVB bytes per stored element (2: bf16, 1: e4m3).
 template <int D, int KVB> struct Geo {
     static constexpr int kRowBytes = D * KVB;
     static constexpr int kUnits = kRowBytes / 16;       // 16-byte units per row
     static constexpr int kTile = kPage * kRowBytes;     // one (page, head) tile of K or of V
     static constexpr int kDmaPerTile = kTile / 1024;    // wave-wide 16-byte loads per tile
-    static constexpr int kStage = 2 * kTile;            // K tile, V tile of one page
-    static constexpr int kDmaPerStage = 2 * kDmaPerTile;
-    static constexpr int kKSteps = D / 32;
+    static constexpr int kScaleBytes = KVB == 1 ? 256 : 0; // e4m3: the page's k and v scales ride along
+    static constexpr int kStage = 2 * kTile + kScaleBytes; // K tile, V tile (and scales) of one page
+    static constexpr int kDmaPerStage = 2 * kDmaPerTile + (KVB == 1 ? 1 : 0);
+    static constexpr int kKSteps = D / 32;              // 16x16x32 MFMA steps over the head dim
+    static constexpr int kKReads = kUnits / 4;          // 16-byte K reads per lane per page
     static constexpr int kDTiles = D / 16;
 };
 
 template <int D, int KVB> struct LaneConst {
     int dma_row[Geo<D, KVB>::kDmaPerTile];
     int dma_off[Geo<D, KVB>::kDmaPerTile];
-    int k_off[Geo<D, KVB>::kKSteps];
+    int k_off[Geo<D, KVB>::kKReads];
     int v_off[Geo<D, KVB>::kDTiles];
 };
 
@@ -321,16 +329,37 @@ template <int D, int KVB> __device__ __forceinline__ void lane_setup(LaneConst<D
         lc.dma_row[n] = r;
         lc.dma_off[n] = r * stride_token_b + c * 16;
     }
+    // K operand: lane (key = lane%16, j = lane/16) reads unit 4*i + j of its key's row
     const int r = lane & 15, j = lane >> 4;
 #pragma unroll
-    for (int i = 0; i < G::kKSteps; i++) lc.k_off[i] = 16 * (r * G::kUnits + ((4 * i + j) ^ (swz(r) & UM)));
+    for (int i = 0; i < G::kKReads; i++) lc.k_off[i] = 16 * (r * G::kUnits + ((4 * i + j) ^ (swz(r) & UM)));
+    // V operand through the transposing read: the 16 lanes of group j address a 4-key x 16-d block
     const int a = lane & 15;
-    const int vrow = 4 * j + (a >> 2);
+    if (KVB == 2) {
+        // ds_read_b64_tr_b16: lane a supplies key 4j + a/4, d = 16*dt + 4*(a%4) .. +3 (8 bytes)
+        const int vrow = 4 * j + (a >> 2);
 #pragma unroll
-    for (int dt = 0; dt < G::kDTiles; dt++) {
-        int c = 2 * dt + ((a >> 1) & 1);
-        lc.v_off[dt] = 16 * (vrow * G::kUnits + (c ^ (swz(vrow) & UM))) + 8 * (a & 1);
+        for (int dt = 0; dt < G::kDTiles; dt++) {
+            int c = 2 * dt + ((a >> 1) & 1);
+            lc.v_off[dt] = 16 * (vrow * G::kUnits + (c ^ (swz(vrow) & UM))) + 8 * (a & 1);
+        }
+    } else {
+        // ds_read_b64_tr_b8: lane a supplies row a/2 of eight, d = 16*dt + 8*(a%2) .. +7 (8 bytes); rows 0-3 are
+        // keys 4j .. 4j+3, rows 4-7 repeat them (only the first four result bytes are used)
+        const int vrow = 4 * j + ((a >> 1) & 3);
+#pragma unroll
+        for (int dt = 0; dt < G::kDTiles; dt++)
+            lc.v_off[dt] = 16 * (vrow * G::kUnits + (dt ^ (swz(vrow) & UM))) + 8 * (a & 1);
     }
+}
+
+// e4m3 -> bf16 is exact (3 mantissa bits into 7); four codes of one dword at a time.
+__device__ __forceinline__ bf16x4 fp8x4_to_bf16(int codes)
+{
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    bf16x2 lo = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes, 1.0f, false);
+    bf16x2 hi = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes, 1.0f, true);
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
 }
 
 // One tile.  A full page goes the cheap way (uniform base + lane offset).  In the last page of a sequence
@@ -379,13 +408,13 @@ template <int DPS> struct WaitTail<0, DPS> {
 //                                      B = P, which is the S^T accumulator layout as it stands)
 // In both products a lane owns one query row (lane % 16), so the running max, the rescale factor and the
 // row sum are per-lane scalars; only the row max needs a cross-lane step (lanes l, l^16, l^32, l^48).
-template <int D, int NQT, int NST>
+template <int D, int KVB, int NQT, int NST>
 __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__restrict__ q, const Segment &sg,
-                                            const LaneConst<D, 2> &lc, uint8_t *lds, uint32_t lds_addr,
+                                            const LaneConst<D, KVB> &lc, uint8_t *lds, uint32_t lds_addr,
                                             const int (&qrow_seq)[NQT], const int (&qrow_head)[NQT], float *part_o,
                                             float *part_lse, int part_rows)
 {
-    using G = Geo<D, 2>;
+    using G = Geo<D, KVB>;
     static_assert((NST - 1) * G::kDmaPerStage < 64, "the vector-memory counter holds 6 bits");
     const int lane = threadIdx.x, j = lane >> 4;
     const int niter = sg.pg_hi - sg.pg_lo;
@@ -395,23 +424,31 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
         nv = nv > kPage ? kPage : nv;
         const uint32_t sb = lds_addr + (it % NST) * G::kStage;
         const int64_t off = (int64_t)pid * a.stride_page_b + (int64_t)sg.kvh * a.stride_head_b;
-        issue_tile<D, 2>(lc, a.k_pool + off, nv, sb, a.zeros);
-        issue_tile<D, 2>(lc, a.v_pool + off, nv, sb + G::kTile, a.zeros);
+        issue_tile<D, KVB>(lc, a.k_pool + off, nv, sb, a.zeros);
+        issue_tile<D, KVB>(lc, a.v_pool + off, nv, sb + G::kTile, a.zeros);
+        if (KVB == 1) {
+            // the page's two scales land behind the tiles: lane 0 brings k_scale, lane 1 v_scale
+            const int64_t si = (int64_t)pid * a.Hkv + sg.kvh;
+            const void *src = lane == 0 ? (const void *)(a.k_scale + si) : lane == 1 ? (const void *)(a.v_scale + si) : a.zeros;
+            dma4(src, sb + 2 * G::kTile);
+        }
     };
     auto page_id = [&](int it) {
         int p = sg.pg_lo + it;
         return p < sg.pg_hi ? sg.pages[p] : 0;
     };
 
-    // Q^T operand: lane (row = lane%16, j) holds d = 32*i + 8*j .. +7 of its row for k-step i
+    // Q^T operand: for k-step i, lane (row = lane%16, j) holds the eight d values that its K operand holds.
+    // bf16 K: d = 32*i + 8*j .. +7.  e4m3 K: one 16-byte K read carries 16 d values and feeds two k-steps, so
+    // d = 16*(4*(i/2) + j) + 8*(i%2) .. +7 (the sum over d does not care about the order).
     bf16x8 qf[NQT][G::kKSteps];
 #pragma unroll
     for (int t = 0; t < NQT; t++) {
 #pragma unroll
         for (int i = 0; i < G::kKSteps; i++) {
+            const int d0 = KVB == 2 ? 32 * i + 8 * j : 16 * (4 * (i / 2) + j) + 8 * (i % 2);
             bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (qrow_seq[t] >= 0)
-                v = *(const bf16x8 *)(q + ((int64_t)qrow_seq[t] * a.Hq + qrow_head[t]) * D + 32 * i + 8 * j);
+            if (qrow_seq[t] >= 0) v = *(const bf16x8 *)(q + ((int64_t)qrow_seq[t] * a.Hq + qrow_head[t]) * D + d0);
             qf[t][i] = v;
         }
     }
@@ -458,17 +495,36 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
 #pragma unroll
         for (int t = 0; t < NQT; t++) s[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int i = 0; i < G::kKSteps; i++) {
-            bf16x8 kf = *(const bf16x8 *)(st + lc.k_off[i]);
+        for (int i = 0; i < G::kKReads; i++) {
+            if (KVB == 2) {
+                bf16x8 kf = *(const bf16x8 *)(st + lc.k_off[i]);
 #pragma unroll
-            for (int t = 0; t < NQT; t++) s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[t][i], s[t], 0, 0, 0);
+                for (int t = 0; t < NQT; t++) s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[t][i], s[t], 0, 0, 0);
+            } else {
+                const int4 kc = *(const int4 *)(st + lc.k_off[i]); // 16 codes: two k-steps
+                bf16x8 k0 = __builtin_shufflevector(fp8x4_to_bf16(kc.x), fp8x4_to_bf16(kc.y), 0, 1, 2, 3, 4, 5, 6, 7);
+                bf16x8 k1 = __builtin_shufflevector(fp8x4_to_bf16(kc.z), fp8x4_to_bf16(kc.w), 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+                for (int t = 0; t < NQT; t++) {
+                    s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[t][2 * i], s[t], 0, 0, 0);
+                    s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[t][2 * i + 1], s[t], 0, 0, 0);
+                }
+            }
+        }
+        // e4m3: one scale per (page, head) for K and one for V.  The K scale folds into the fp32 score scale,
+        // the V scale into P before it is rounded to bf16 (the row sum keeps the unscaled weights).
+        float kscale = a.scale_log2, vscale = 1.0f;
+        if (KVB == 1) {
+            const float2 sc = *(const float2 *)(st + 2 * G::kTile);
+            kscale *= sc.x;
+            vscale = sc.y;
         }
         const int tok0 = (sg.pg_lo + it) * kPage + 4 * j; // this lane's first token of the page
         const bool ragged = (sg.pg_lo + it + 1) * kPage > sg.limit;
         s16x4 pf[NQT];
 #pragma unroll
         for (int t = 0; t < NQT; t++) {
-            f32x4 v = s[t] * a.scale_log2;
+            f32x4 v = s[t] * kscale;
             if (ragged) {
 #pragma unroll
                 for (int e = 0; e < 4; e++)
@@ -480,7 +536,7 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
 #pragma unroll
             for (int e = 0; e < 4; e++) p[e] = __builtin_amdgcn_exp2f(v[e] - mn);
             const float ps = (p[0] + p[1]) + (p[2] + p[3]);
-            pf[t] = __builtin_bit_cast(s16x4, __builtin_convertvector(p, bf16x4));
+            pf[t] = __builtin_bit_cast(s16x4, __builtin_convertvector(KVB == 1 ? p * vscale : p, bf16x4));
             // the running max rarely moves after the first pages: rescale only when some row's did
             if (__any(mn != m[t])) {
                 const float alpha = __builtin_amdgcn_exp2f(m[t] - mn);
@@ -493,10 +549,18 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
         }
         // O^T += V^T P^T
         typedef s16x4 __attribute__((address_space(3))) * lds_s16x4;
+        typedef int __attribute__((ext_vector_type(2))) i32x2;
+        typedef i32x2 __attribute__((address_space(3))) * lds_i32x2;
         const uint32_t vb = lds_addr + (it % NST) * G::kStage + G::kTile;
 #pragma unroll
         for (int dt = 0; dt < G::kDTiles; dt++) {
-            s16x4 vf = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(vb + lc.v_off[dt]));
+            s16x4 vf;
+            if (KVB == 2) {
+                vf = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(vb + lc.v_off[dt]));
+            } else {
+                const i32x2 vc = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2)(vb + lc.v_off[dt]));
+                vf = __builtin_bit_cast(s16x4, fp8x4_to_bf16(vc[0]));
+            }
 #pragma unroll
             for (int t = 0; t < NQT; t++) o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf, pf[t], o[t][dt], 0, 0, 0);
         }
@@ -528,7 +592,7 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
         const int4 *__restrict__ row_info, const int32_t *__restrict__ span_first_row, const int32_t *__restrict__ members
 #define RA_ATTN_ARGS a, q, block_table, pfx_off, pfx_pages, hdr, row_start, row_info, span_first_row, members
 
-template <int D, int NST> __device__ __forceinline__ void attention_body(RA_ATTN_PARAMS, int32_t *next_span)
+template <int D, int KVB, int NST> __device__ __forceinline__ void attention_body(RA_ATTN_PARAMS, int32_t *next_span)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     const uint32_t lds_addr = (uint32_t)(uintptr_t)lds;
@@ -540,8 +604,8 @@ template <int D, int NST> __device__ __forceinline__ void attention_body(RA_ATTN
     sp.S0 = hdr[1];
     sp.cd = hdr[6];
 
-    LaneConst<D, 2> lc;
-    lane_setup<D, 2>(lc, lane, a.stride_token_b);
+    LaneConst<D, KVB> lc;
+    lane_setup<D, KVB>(lc, lane, a.stride_token_b);
 
     int span = blockIdx.x;
     while (span < nspans) {
@@ -579,7 +643,7 @@ template <int D, int NST> __device__ __forceinline__ void attention_body(RA_ATTN
                     const int row = lane & 15;
                     qs[0] = row < a.G ? b : -1;
                     qh[0] = kvh * a.G + row;
-                    run_segment<D, 1, NST>(a, q, sg, lc, lds, lds_addr, qs, qh, w.suf_o + (int64_t)slot * a.G * D,
+                    run_segment<D, KVB, 1, NST>(a, q, sg, lc, lds, lds_addr, qs, qh, w.suf_o + (int64_t)slot * a.G * D,
                                            w.suf_lse + (int64_t)slot * a.G, a.G);
                 } else {
                     // shared prompt pages of a group: rows = members x G, packed densely into 16-row tiles
@@ -596,7 +660,7 @@ template <int D, int NST> __device__ __forceinline__ void attention_body(RA_ATTN
                         qs[t] = row < nrows ? members[info.y + mi] : -1;
                         qh[t] = kvh * a.G + (row - mi * a.G);
                     }
-                    run_segment<D, kPrefixTiles, NST>(a, q, sg, lc, lds, lds_addr, qs, qh,
+                    run_segment<D, KVB, kPrefixTiles, NST>(a, q, sg, lc, lds, lds_addr, qs, qh,
                                                       w.pfx_o + (int64_t)slot * kPrefixRows * D,
                                                       w.pfx_lse + (int64_t)slot * kPrefixRows, nrows);
                 }
@@ -606,37 +670,50 @@ template <int D, int NST> __device__ __forceinline__ void attention_body(RA_ATTN
     }
 }
 
-// Two ring depths: four stages with one wave per SIMD, or two stages with two waves per SIMD (256 VGPRs each).
+// bf16 KV: ring of four pages with one wave per SIMD, or of two pages with two waves per SIMD.  e4m3 KV: pages
+// are half the size, so the ring is eight deep.
 template <int D> __global__ __launch_bounds__(64) void attention_kernel_s4(RA_ATTN_PARAMS, int32_t *next_span)
 {
-    attention_body<D, 4>(RA_ATTN_ARGS, next_span);
+    attention_body<D, 2, 4>(RA_ATTN_ARGS, next_span);
 }
 template <int D>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attention_kernel_s2(RA_ATTN_PARAMS, int32_t *next_span)
 {
-    attention_body<D, 2>(RA_ATTN_ARGS, next_span);
+    attention_body<D, 2, 2>(RA_ATTN_ARGS, next_span);
+}
+template <int D> __global__ __launch_bounds__(64) void attention_kernel_fp8(RA_ATTN_PARAMS, int32_t *next_span)
+{
+    attention_body<D, 1, 8>(RA_ATTN_ARGS, next_span);
 }
 
-static size_t attention_lds_bytes(int D, int stages) { return (size_t)stages * (D == 128 ? Geo<128, 2>::kStage : Geo<64, 2>::kStage); }
-
-static const void *attention_fn(int D, int stages)
+static size_t attention_lds_bytes(int D, int kv_fp8, int stages)
 {
+    if (kv_fp8) return (size_t)stages * (D == 128 ? Geo<128, 1>::kStage : Geo<64, 1>::kStage);
+    return (size_t)stages * (D == 128 ? Geo<128, 2>::kStage : Geo<64, 2>::kStage);
+}
+
+static const void *attention_fn(int D, int kv_fp8, int stages)
+{
+    if (kv_fp8) return D == 128 ? (const void *)attention_kernel_fp8<128> : (const void *)attention_kernel_fp8<64>;
     if (stages == 2) return D == 128 ? (const void *)attention_kernel_s2<128> : (const void *)attention_kernel_s2<64>;
     return D == 128 ? (const void *)attention_kernel_s4<128> : (const void *)attention_kernel_s4<64>;
 }
 
 hipError_t attention_config(int D, int kv_fp8, int num_cus, int *stages, int *waves)
 {
-    (void)kv_fp8;
     int st = 4, per_cu = 4;
-    if (const char *ev = getenv("ROLLOUT_ATTN_STAGES")) st = atoi(ev) == 2 ? 2 : 4;
-    if (st == 2) per_cu = 8;
+    if (kv_fp8) {
+        st = 8;
+    } else {
+        if (const char *ev = getenv("ROLLOUT_ATTN_STAGES")) st = atoi(ev) == 2 ? 2 : 4;
+        if (st == 2) per_cu = 8;
+    }
     if (const char *ev = getenv("ROLLOUT_ATTN_WAVES_PER_CU")) {
         int v = atoi(ev);
         if (v >= 1 && v <= 16) per_cu = v;
     }
-    size_t lds = attention_lds_bytes(D, st);
-    hipError_t e = hipFuncSetAttribute(attention_fn(D, st), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    size_t lds = attention_lds_bytes(D, kv_fp8, st);
+    hipError_t e = hipFuncSetAttribute(attention_fn(D, kv_fp8, st), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     *stages = st;
     *waves = per_cu * num_cus;
@@ -645,12 +722,15 @@ hipError_t attention_config(int D, int kv_fp8, int num_cus, int *stages, int *wa
 
 hipError_t launch_attention(const Launch &a, hipStream_t s)
 {
-    size_t lds = attention_lds_bytes(a.D, a.stages);
+    size_t lds = attention_lds_bytes(a.D, a.kv_fp8, a.stages);
     const Workspace &w = a.ws;
 #define RA_LAUNCH(K)                                                                                                      \
     hipLaunchKernelGGL(K, dim3(a.waves), dim3(64), lds, s, a, a.q, a.block_table, a.pfx_off, a.pfx_pages, w.hdr, w.row_start, \
                        w.row_info, w.span_first_row, w.members, w.hdr + 5)
-    if (a.stages == 2) {
+    if (a.kv_fp8) {
+        if (a.D == 128) RA_LAUNCH(attention_kernel_fp8<128>);
+        else RA_LAUNCH(attention_kernel_fp8<64>);
+    } else if (a.stages == 2) {
         if (a.D == 128) RA_LAUNCH(attention_kernel_s2<128>);
         else RA_LAUNCH(attention_kernel_s2<64>);
     } else {

@@ -1,0 +1,36 @@
+"""Checks on the generated gfx950 code that the kernels' hand-managed pieces rely on (CPU only: hipcc
+cross-compiles to assembly, nothing runs)."""
+import os
+import re
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def isa(tmp_path_factory):
+    from paper_2507_01663_amd import build
+    out = tmp_path_factory.mktemp("isa") / "ra_kernels.s"
+    flags = [f for f in build.FLAGS if f not in ("-shared", "-fPIC")]
+    cmd = [os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")] + flags + ["-S", "--cuda-device-only", "-o", str(out),
+                                                                       os.path.join(build.CSRC, "ra_kernels.hip")]
+    subprocess.run(cmd, check=True, stderr=subprocess.DEVNULL)
+    return open(out).read()
+
+
+def kernels(isa):
+    """name -> body text of every attention kernel."""
+    out = {}
+    for m in re.finditer(r"^(_ZN2ra19attention_kernel\w+):.*?s_endpgm", isa, flags=re.S | re.M):
+        out[m.group(1)] = m.group(0)
+    return out
+
+
+def test_no_scratch_and_no_full_drain_in_the_page_loop(isa):
+    for name, body in kernels(isa).items():
+        assert ".private_segment_fixed_size: 0" in isa
+        assert "scratch_" not in body, name
+        # the LDS ring is paced by hand-written waits with a non-zero count; they must be there
+        assert re.search(r"s_waitcnt vmcnt\((4|5|8|12|16|24|35)\)", body), name

@@ -45,6 +45,39 @@ def test_parity_element_by_element(dec, name):
     log(name, "abs %.2e rel %.2e lse %.2e" % errs)
 
 
+@pytest.mark.parametrize("name", ["tiny", "midd64", "mid7b", "mid32b", "mid72b"])
+def test_fp8_kv_parity_element_by_element(dec, name):
+    """K/V stored as e4m3 codes with per-page-per-head fp32 scales; the oracle dequantises in fp64."""
+    from gpu_util import compare
+    p = workload.make_problem(name, seed=0, kv_dtype="fp8_e4m3")
+    log("case", p.name, "B", p.B, "lens", int(p.seq_lens.min()), int(p.seq_lens.max()))
+    ref_out, ref_lse = oracle.decode(p)
+    errs = compare(*run(dec, p).results(), ref_out, ref_lse, p.name)
+    log(p.name, "abs %.2e rel %.2e lse %.2e" % errs)
+    errs = compare(*run(dec, p, use_hint=False).results(), ref_out, ref_lse, p.name + " no hint")
+
+
+def test_fp8_every_code_decodes_exactly(dec):
+    """One key per sequence (softmax weight 1), V rows holding every finite e4m3 code, scale 1: the output must be
+    the code's value rounded to bf16, i.e. exactly the value."""
+    from gpu_util import compare
+    p = workload.build_problem("codes", 4, 4, 64, [0], 16, [1] * 16, kv_dtype="fp8_e4m3", seed=7, poison=False)
+    codes = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], dtype=np.uint8)     # 254 finite codes
+    vals = np.resize(codes, 16 * 4 * 64).reshape(16, 4, 64)
+    for b in range(16):
+        pg = p.block_table[b, 0]
+        p.v_pool[pg, :, 0, :] = vals[b]
+        p.k_pool[pg, :, 0, :] = vals[(b + 5) % 16]
+    p.k_scale[:] = 2.0 ** -9
+    p.v_scale[:] = 1.0
+    ref_out, ref_lse = oracle.decode(p)
+    out, lse = run(dec, p).results()
+    tab = oracle.e4m3_decode_table()
+    assert np.array_equal(ref_out, np.repeat(tab[vals][:, :, None, :], 1, axis=2).reshape(16, 4, 64))
+    assert np.array_equal(out, ref_out)                 # exact: every e4m3 value is a bf16 value
+    compare(out, lse, ref_out, ref_lse, "codes")
+
+
 @pytest.mark.parametrize("name", ["tiny", "mid7b"])
 def test_hint_off_and_flag_give_the_same_answer(dec, name):
     import paper_2507_01663_amd as ra
@@ -222,3 +255,11 @@ def test_full_size_grpo7b_against_oracle(dec):
     log("grpo7b abs %.2e rel %.2e lse %.2e" % errs)
     dp2 = run(dec, p, use_hint=False)
     compare(*dp2.results(), ref_out, ref_lse, "grpo7b no hint")
+
+
+def test_full_size_grpo7b_fp8_against_oracle(dec):
+    from gpu_util import compare
+    p = workload.make_problem("grpo7b", seed=0, kv_dtype="fp8_e4m3")
+    ref_out, ref_lse = oracle.decode(p)
+    errs = compare(*run(dec, p).results(), ref_out, ref_lse, "grpo7b fp8")
+    log("grpo7b fp8 abs %.2e rel %.2e lse %.2e" % errs)
