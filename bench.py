@@ -56,6 +56,7 @@ def main():
     ap.add_argument("--instances", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sharing", action="store_true", help="ignore the prompt-group hint (A/B)")
+    ap.add_argument("--calibrate-copy", action="store_true", help="also run three 1 GiB device copies (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the path needs no exchange between GPUs; "
@@ -77,10 +78,36 @@ def main():
 
     t0 = time.time()
     probs, devs = [], []
-    for i in range(args.instances):
-        p = workload.make_problem(args.workload, seed=i, kv_dtype=args.kv_dtype)
-        probs.append(p)
-        devs.append(DeviceProblem(p, flags=flags))
+    cfg = workload.CONFIGS[args.workload]
+    if cfg["resp"] == "stream":
+        # streaming workload: one static pool; the instances are decode steps spread over the run, each with its
+        # own lengths, block table (re-drawn from the seed) and queries
+        steps = sorted(set(int(round(i * (cfg["steps"] - 1) / max(1, args.instances - 1))) for i in range(args.instances)))
+        width = (cfg["prompt"] + cfg["resp_max"] + cfg["steps"]) // 16 + 1
+        for i, st in enumerate(steps):
+            p = workload.make_problem(args.workload, seed=0, step=st, kv_dtype=args.kv_dtype, make_values=(i == 0),
+                                      pool=None if i == 0 else (probs[0].k_pool, probs[0].v_pool, probs[0].k_scale, probs[0].v_scale),
+                                      num_pages=None if i == 0 else probs[0].num_pages)
+            bt = np.full((p.B, width), -1, dtype=np.int32)
+            bt[:, :p.block_table.shape[1]] = p.block_table
+            p.block_table, p.max_pages_per_seq = bt, width
+            if p.q is None:
+                p.q = workload.normal_bf16(p.B * p.Hq * p.D, 0, 1000 + st).reshape(p.B, p.Hq, p.D)
+            probs.append(p)
+            devs.append(DeviceProblem(p, flags=flags, share_pools_with=devs[0] if i else None))
+    else:
+        for i in range(args.instances):
+            p = workload.make_problem(args.workload, seed=i, kv_dtype=args.kv_dtype)
+            probs.append(p)
+            devs.append(DeviceProblem(p, flags=flags))
+    if args.calibrate_copy:
+        # a plain copy of known size in the same process, so that a counter run can scale its byte counters
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     alg_bytes = [p.algorithmic_bytes(share_prefix=True) for p in probs]
     print("# %d instances of %s generated and uploaded in %.1f s; algorithmic MB/step: %s" %
           (args.instances, args.workload, time.time() - t0, [round(b / 1e6, 1) for b in alg_bytes]), file=sys.stderr)

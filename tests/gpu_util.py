@@ -14,10 +14,13 @@ def bits_to_bf16(a, dev):
 
 
 class DeviceProblem:
-    def __init__(self, p, dev="cuda:0", flags=0, use_hint=True):
+    def __init__(self, p, dev="cuda:0", flags=0, use_hint=True, share_pools_with=None):
         self.p = p
         self.q = bits_to_bf16(p.q, dev)
-        if p.kv_dtype == "bf16":
+        if share_pools_with is not None:
+            o = share_pools_with
+            self.k_pool, self.v_pool, self.k_scale, self.v_scale = o.k_pool, o.v_pool, o.k_scale, o.v_scale
+        elif p.kv_dtype == "bf16":
             self.k_pool, self.v_pool = bits_to_bf16(p.k_pool, dev), bits_to_bf16(p.v_pool, dev)
             self.k_scale = self.v_scale = None
         else:

@@ -263,3 +263,69 @@ def test_full_size_grpo7b_fp8_against_oracle(dec):
     ref_out, ref_lse = oracle.decode(p)
     errs = compare(*run(dec, p).results(), ref_out, ref_lse, "grpo7b fp8")
     log("grpo7b fp8 abs %.2e rel %.2e lse %.2e" % errs)
+
+
+def sampled_rows(p, n, seed):
+    """Row ids (b*Hq + h) for a sampled comparison: the longest and the shortest sequences plus a random draw."""
+    rng = np.random.default_rng(seed)
+    order = np.argsort(p.seq_lens)
+    bs = np.concatenate([order[:2], order[-2:], rng.choice(p.B, size=max(1, n // p.Hq), replace=False)])
+    rows = (bs[:, None] * p.Hq + np.arange(p.Hq)[None, :]).reshape(-1)
+    return np.unique(rows).astype(np.int32)
+
+
+def compare_rows(dp, p, rows, what):
+    from gpu_util import compare
+    out, lse = dp.results()
+    ref_out, ref_lse = oracle.decode(p, rows=rows)
+    return compare(out.reshape(-1, p.D)[rows], lse.reshape(-1)[rows], ref_out, ref_lse, what)
+
+
+def test_full_size_tail32b_sampled(dec):
+    """32B-shaped long-tail batch at full size (B=512, lognormal lengths up to 17408 tokens): a few hundred sampled
+    rows against the oracle, and every row finite."""
+    p = workload.make_problem("tail32b", seed=0)
+    log("tail32b: kv tokens", p.kv_tokens(), "pages", p.num_pages, "max len", int(p.seq_lens.max()))
+    dp = run(dec, p)
+    rows = sampled_rows(p, 400, 1)
+    errs = compare_rows(dp, p, rows, "tail32b")
+    log("tail32b %d rows: abs %.2e rel %.2e lse %.2e" % ((len(rows),) + errs))
+    out, lse = dp.results()
+    assert np.isfinite(out).all() and np.isfinite(lse).all()
+
+
+def test_full_size_stream72b_steps(dec):
+    """72B-shaped streaming batch at full size: static pool, lengths advance and the block table is re-drawn every
+    step; steps 0, 1 and 63 are checked on a fixed 5% sample of the rows (plus the longest and shortest)."""
+    from gpu_util import DeviceProblem
+    p0 = workload.make_problem("stream72b", seed=0, step=0)
+    log("stream72b: kv tokens", p0.kv_tokens(), "pages", p0.num_pages)
+    cfg = workload.CONFIGS["stream72b"]
+    width = (cfg["prompt"] + cfg["resp_max"] + cfg["steps"]) // 16 + 1       # room for every step of the run
+    bt0 = np.full((p0.B, width), -1, dtype=np.int32)
+    bt0[:, :p0.block_table.shape[1]] = p0.block_table
+    p0.block_table, p0.max_pages_per_seq = bt0, width
+    dp = DeviceProblem(p0)
+    pool = (p0.k_pool, p0.v_pool, None, None)
+    for step in (0, 1, 63):
+        p = p0 if step == 0 else workload.make_problem("stream72b", seed=0, step=step, pool=pool, num_pages=p0.num_pages,
+                                                        make_values=False)
+        if step:
+            # same pool on the device; new q, lengths, table and prefix list
+            p.q = workload.normal_bf16(p.B * p.Hq * p.D, 0, 99 + step).reshape(p.B, p.Hq, p.D)
+            from gpu_util import bits_to_bf16
+            dp.p = p
+            dp.q = bits_to_bf16(p.q, "cuda:0")
+            assert p.block_table.shape[1] <= width
+            bt = np.full((p.B, width), -1, dtype=np.int32)
+            bt[:, :p.block_table.shape[1]] = p.block_table
+            dp.block_table.copy_(torch.from_numpy(bt))
+            dp.seq_lens.copy_(torch.from_numpy(p.seq_lens))
+            dp.pfx_pages.copy_(torch.from_numpy(p.prefix_pages))
+            dp.out.fill_(float("nan"))
+            dp.set()
+            p.block_table, p.max_pages_per_seq = bt, width
+        dec.decode(dp.c)
+        rows = sampled_rows(p, int(0.05 * p.B * p.Hq), 2)
+        errs = compare_rows(dp, p, rows, "stream72b step %d" % step)
+        log("stream72b step %d, %d rows: abs %.2e rel %.2e lse %.2e" % ((step, len(rows)) + errs))
