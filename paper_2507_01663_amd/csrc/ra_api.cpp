@@ -16,6 +16,7 @@ struct ra_ctx {
     int cost_prefix; // scheduling weight of a shared-prefix page
     int static_pct;  // share of the work that is assigned to waves up front
     int dyn_pages;   // pages per dynamically scheduled span
+    int xcd_w[8];    // relative speed of the accelerator dies
     void *zeros;  // 256 bytes of zeros on the device
     int32_t *host_flags; // pinned, for RA_FLAG_VALIDATE
     int timing;          // record events around the phases
@@ -99,6 +100,17 @@ void fill_launch(ra::Launch &a, const ra_ctx *ctx, const ra_problem *p)
     a.cost_prefix = ctx ? ctx->cost_prefix : ra::kCostPrefix;
     a.static_pct = ctx ? ctx->static_pct : 100;
     a.dyn_pages = ctx ? ctx->dyn_pages : 16;
+    {
+        // normalised so that the eight weights add up to 8192 (the schedule divides by a shift)
+        long W = 0;
+        int acc = 0;
+        const bool use = ctx && a.waves % 8 == 0;
+        for (int x = 0; x < 8; x++) W += use ? ctx->xcd_w[x] : 1000;
+        for (int x = 0; x < 8; x++) {
+            a.xcd_w[x] = x < 7 ? (int)(((use ? ctx->xcd_w[x] : 1000) * 8192L + W / 2) / W) : 8192 - acc;
+            acc += a.xcd_w[x];
+        }
+    }
     a.q = (const uint16_t *)p->q;
     a.k_pool = (const uint8_t *)p->k_pool; a.v_pool = (const uint8_t *)p->v_pool;
     a.stride_page_b = p->kv_stride_page * es; a.stride_head_b = p->kv_stride_head * es;
@@ -132,6 +144,19 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
     c->cost_prefix = ra::kCostPrefix;
     c->static_pct = 100;
     c->dyn_pages = 16;
+    // Share of the memory bandwidth each accelerator die gets when all eight stream at once, measured on
+    // MI355X with the attention kernel (per mille of the mean; the pattern follows the dies' place on the package).
+    static const int kXcdSpeed[8] = {1024, 944, 1089, 978, 1064, 973, 1013, 936};
+    for (int x = 0; x < 8; x++) c->xcd_w[x] = kXcdSpeed[x];
+    if (const char *ev = getenv("ROLLOUT_ATTN_XCD_WEIGHTS")) {
+        int v[8];
+        if (sscanf(ev, "%d,%d,%d,%d,%d,%d,%d,%d", &v[0], &v[1], &v[2], &v[3], &v[4], &v[5], &v[6], &v[7]) == 8) {
+            bool ok = true;
+            for (int x = 0; x < 8; x++) ok = ok && v[x] >= 100 && v[x] <= 10000;
+            if (ok)
+                for (int x = 0; x < 8; x++) c->xcd_w[x] = v[x];
+        }
+    }
     if (const char *ev = getenv("ROLLOUT_ATTN_STATIC_PCT")) {
         int v = atoi(ev);
         if (v >= 0 && v <= 100) c->static_pct = v;

@@ -16,18 +16,21 @@ constexpr int kCostPrefix = 5;      // ... of a shared-prefix page (more query r
 
 // Device pointers into the caller's workspace.  All offsets are fixed by the shape alone.
 struct Workspace {
-    int32_t *hdr;            // [16]: 0 total cost units, 1 units per static span, 2 rows, 3 prefix rows, 4 error flags,
-                             //       5 next span to hand out, 6 units per dynamic span, 7 spans
+    int32_t *hdr;            // [16]: 0 total cost units, 2 rows, 3 prefix rows, 4 error flags, 5 next span to hand out,
+                             //       7 spans
     int32_t *grp_count;      // [num_groups]      members that use the shared pass
     int32_t *grp_rowbase;    // [num_groups + 1]  first prefix row of the group (relative)
     int32_t *grp_membase;    // [num_groups + 1]  first slot of the group in members[]
     int32_t *seq_rank;       // [B]   rank inside the group, -1: not a member
-    int32_t *seq_pfx_row;    // [B]   prefix row (relative) or -1
+    int32_t *seq_pfx_row;    // [B]   prefix row or -1
+    int32_t *seq_rank_in_row;// [B]   position among the members of that row
+    int4 *merge_desc;        // [B*Hkv][2]  {first cost unit, pages, first span, last span} of the own row and of the prefix row
     int32_t *members;        // [B]   sequences ordered by prefix row
     int32_t *row_start;      // [2B + 1] exclusive scan of the rows' cost (per kv head); prefix rows come first
     int4 *row_info;          // [2B]  prefix row:      {group, first member slot, members, pages}
                              //       sequence row b:  {b, pages skipped, valid tokens after the skip, pages}
     int32_t *span_first_row; // [spans + 1]
+    int32_t *span_lo;        // [spans + 1] first cost unit of every span
     float *suf_o;            // [(B*Hkv + spans)][G][D]   partial outputs (normalised); slot = item + span
     float *suf_lse;          // [(B*Hkv + spans)][G]      partial log2-sum-exp
     float *pfx_o;            // [(prefix_rows_max*Hkv + spans)][kPrefixRows][D]
@@ -37,6 +40,7 @@ struct Workspace {
 struct Launch {
     int32_t B, Hq, Hkv, D, G, num_pages, max_pages, num_groups;
     int32_t kv_fp8, share, waves, members_per_row, stages, cost_prefix, static_pct, dyn_pages;
+    int32_t xcd_w[8]; // relative speed of the eight accelerator dies, adding up to 8192
     const uint16_t *q;
     const uint8_t *k_pool, *v_pool;
     int64_t stride_page_b, stride_head_b; // bytes

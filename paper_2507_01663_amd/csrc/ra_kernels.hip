@@ -47,11 +47,14 @@ size_t carve_workspace(Workspace &ws, void *base, int B, int Hkv, int G, int D, 
     ws.grp_membase = (int32_t *)take((size_t)(ng + 1) * 4);
     ws.seq_rank = (int32_t *)take((size_t)B * 4);
     ws.seq_pfx_row = (int32_t *)take((size_t)B * 4);
+    ws.seq_rank_in_row = (int32_t *)take((size_t)B * 4);
+    ws.merge_desc = (int4 *)take((size_t)B * Hkv * 32);
     ws.members = (int32_t *)take((size_t)B * 4);
     ws.row_start = (int32_t *)take(((size_t)2 * B + 1) * 4);
     ws.row_info = (int4 *)take((size_t)2 * B * 16);
     const size_t spans = (size_t)(1 + kDynSpansPerWave) * waves; // upper bound on spans of the cost stream
     ws.span_first_row = (int32_t *)take((spans + 1) * 4);
+    ws.span_lo = (int32_t *)take((spans + 2) * 4);
     size_t nsuf = (size_t)B * Hkv + spans;
     ws.suf_o = (float *)take(nsuf * G * D * 4);
     ws.suf_lse = (float *)take(nsuf * G * 4);
@@ -74,6 +77,7 @@ size_t carve_workspace(Workspace &ws, void *base, int B, int Hkv, int G, int D, 
 
 constexpr int kPlanThreads = 1024;
 constexpr int kPlanCap = 2048; // sequences / groups whose intermediate arrays fit in LDS; beyond, the workspace is used
+constexpr int kSpanCap = 6144; // likewise for span boundaries
 
 // Exclusive scan of in[0..n) into out[0..n], out[n] = total (in == out is allowed).  All threads call it.
 __device__ void block_scan(const int32_t *in, int32_t *out, int n, int32_t *tmp /*[17], LDS*/)
@@ -115,7 +119,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
 {
     __shared__ int32_t scan_tmp[17];
     __shared__ int32_t l_grp_count[kPlanCap], l_grp_rowbase[kPlanCap + 1], l_grp_membase[kPlanCap + 1];
-    __shared__ int32_t l_seq_rank[kPlanCap], l_row_start[2 * kPlanCap + 1];
+    __shared__ int32_t l_seq_rank[kPlanCap], l_row_start[2 * kPlanCap + 1], l_span_lo[kSpanCap + 1];
     const int tid = threadIdx.x;
     const Workspace &w = a.ws;
     const int B = a.B;
@@ -172,10 +176,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
             skip = a.pfx_off[g + 1] - a.pfx_off[g];
             prow = grp_rowbase[g] + rank / MPR;
             w.members[grp_membase[g] + rank] = b;
-            rank = rank % MPR;
         }
         w.seq_pfx_row[b] = prow;
-        w.seq_rank[b] = rank;
+        w.seq_rank_in_row[b] = rank >= 0 ? rank % MPR : -1;
         int pages = L > 0 ? (L + kPage - 1) / kPage - skip : 0;
         row_start[nPR + b] = pages * kCostSuffix;
         w.row_info[nPR + b] = make_int4(b, skip, L - skip * kPage, pages);
@@ -183,9 +186,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
     __syncthreads();
     const int nR = B + nPR;
     block_scan(row_start, row_start, nR, scan_tmp);
-    // Spans of the cost stream.  The first `waves` spans are equal and assigned one per resident wave; the rest
-    // of the stream is cut into smaller spans that the waves take from a counter as they finish, so that
-    // compute units that happen to get less memory bandwidth than others do not hold the kernel up.
+    // Spans of the cost stream.  The first `waves` spans are static, one per resident wave.  Workgroups are dealt
+    // round-robin to the eight accelerator dies, which do not all get the same share of the memory bandwidth,
+    // so within each block of eight consecutive static spans (8*S0 units) span x gets a share proportional to
+    // the relative speed xcd_w[x] of its die (the weights add up to 8192).  The rest of the stream, if any, is
+    // cut into smaller spans that the waves take from a counter as they finish.  All later kernels read the
+    // span boundaries from span_lo[], so any other cut could be written here.
     const long U = (long)a.Hkv * row_start[nR];
     const long min_span = (long)kMinUnitsPerWave * kCostSuffix;
     long S0 = U * a.static_pct / 100 / a.waves;
@@ -201,27 +207,71 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
     const int nspans = a.waves + (int)ndyn;
     if (tid == 0) {
         w.hdr[0] = (int)U;
-        w.hdr[1] = (int)S0;
         w.hdr[2] = nR;
         w.hdr[3] = nPR;
         w.hdr[5] = a.waves; // next span to hand out
-        w.hdr[6] = (int)cd;
         w.hdr[7] = nspans;
     }
     if (small)
         for (int r = tid; r <= nR; r += kPlanThreads) w.row_start[r] = row_start[r];
-    // first row of every span: the last row that starts at or before the span's first unit
+    const bool few = nspans < kSpanCap;
+    int32_t *span_lo = few ? l_span_lo : w.span_lo;
     for (int c = tid; c <= nspans; c += kPlanThreads) {
-        long target = c < a.waves ? (long)c * S0 : (long)a.waves * S0 + (long)(c - a.waves) * cd;
-        int lo = 0, hi = nR; // invariant: Hkv*row_start[lo] <= target < Hkv*row_start[hi]
-        if (target >= U) lo = nR;
+        long lo;
+        if (c < a.waves) {
+            int acc = 0;
+            for (int x = 0; x < (c & 7); x++) acc += a.xcd_w[x];
+            lo = (long)(c >> 3) * 8 * S0 + ((8 * S0 * acc) >> 13);
+        } else {
+            lo = (long)a.waves * S0 + (long)(c - a.waves) * cd;
+        }
+        span_lo[c] = (int)lo;
+        if (few) w.span_lo[c] = (int)lo;
+        // first row of the span: the last row that starts at or before the span's first unit
+        int rlo = 0, rhi = nR; // invariant: Hkv*row_start[rlo] <= lo < Hkv*row_start[rhi]
+        if (lo >= U) rlo = nR;
         else
-            while (hi - lo > 1) {
-                int mid = (lo + hi) >> 1;
-                if ((long)a.Hkv * row_start[mid] <= target) lo = mid;
-                else hi = mid;
+            while (rhi - rlo > 1) {
+                int mid = (rlo + rhi) >> 1;
+                if ((long)a.Hkv * row_start[mid] <= lo) rlo = mid;
+                else rhi = mid;
             }
-        w.span_first_row[c] = lo;
+        w.span_first_row[c] = rlo;
+    }
+    __syncthreads();
+    // For the merge: the spans that hold pages of each (sequence, kv head)'s own row and of its prefix row.
+    auto span_of = [&](int pos) { // last span that starts at or before pos
+        int lo = 0, hi = nspans;
+        while (hi - lo > 1) {
+            int mid = (lo + hi) >> 1;
+            if (span_lo[mid] <= pos) lo = mid;
+            else hi = mid;
+        }
+        return lo;
+    };
+    for (int i = tid; i < B * a.Hkv; i += kPlanThreads) {
+        const int b = i / a.Hkv, kvh = i - b * a.Hkv;
+        int4 own, pfx = make_int4(0, 0, 0, -1);
+        {
+            const int r = nPR + b;
+            const int n = (row_start[r + 1] - row_start[r]) / kCostSuffix;
+            const int S = a.Hkv * row_start[r] + kvh * kCostSuffix * n;
+            own = make_int4(S, n, 0, -1);
+            if (n > 0) {
+                own.z = span_of(S);
+                own.w = span_of(S + kCostSuffix * (n - 1));
+            }
+        }
+        const int rank = seq_rank[b];
+        if (rank >= 0) {
+            const int g = a.seq_group[b];
+            const int r = grp_rowbase[g] + rank / MPR;
+            const int n = (row_start[r + 1] - row_start[r]) / a.cost_prefix;
+            const int S = a.Hkv * row_start[r] + kvh * a.cost_prefix * n;
+            pfx = make_int4(S, n, span_of(S), span_of(S + a.cost_prefix * (n - 1)));
+        }
+        w.merge_desc[2 * i] = own;
+        w.merge_desc[2 * i + 1] = pfx;
     }
 }
 
@@ -230,14 +280,6 @@ hipError_t launch_plan(const Launch &a, hipStream_t s)
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, s, a);
     return hipGetLastError();
 }
-
-// The cost stream is cut into spans: `waves` spans of S0 units, then spans of cd units.
-struct Spans {
-    int waves, S0, cd;
-    __device__ __forceinline__ int lo(int c) const { return c < waves ? c * S0 : waves * S0 + (c - waves) * cd; }
-    __device__ __forceinline__ int hi(int c) const { return c < waves ? (c + 1) * S0 : waves * S0 + (c - waves + 1) * cd; }
-    __device__ __forceinline__ int of(int pos) const { return pos < waves * S0 ? pos / S0 : waves + (pos - waves * S0) / cd; }
-};
 
 // Pages [p_lo, p_hi) of an item (first cost unit S, weight cw per page, n pages) that belong to the span
 // [lo, hi) of the cost stream: those whose first unit S + cw*p lies in the span.
@@ -302,9 +344,9 @@ template <int D, int KVB> struct Geo {
     static constexpr int kUnits = kRowBytes / 16;       // 16-byte units per row
     static constexpr int kTile = kPage * kRowBytes;     // one (page, head) tile of K or of V
     static constexpr int kDmaPerTile = kTile / 1024;    // wave-wide 16-byte loads per tile
-    static constexpr int kScaleBytes = KVB == 1 ? 256 : 0; // e4m3: the page's k and v scales ride along
-    static constexpr int kStage = 2 * kTile + kScaleBytes; // K tile, V tile (and scales) of one page
-    static constexpr int kDmaPerStage = 2 * kDmaPerTile + (KVB == 1 ? 1 : 0);
+    static constexpr int kScaleBytes = KVB == 1 ? 256 : 0; // e4m3: the two pages' k and v scales ride along
+    static constexpr int kStage = 4 * kTile + kScaleBytes; // K0 K1 V0 V1 (and scales): two pages per ring stage
+    static constexpr int kDmaPerStage = 4 * kDmaPerTile + (KVB == 1 ? 1 : 0);
     static constexpr int kKSteps = D / 32;              // 16x16x32 MFMA steps over the head dim
     static constexpr int kKReads = kUnits / 4;          // 16-byte K reads per lane per page
     static constexpr int kDTiles = D / 16;
@@ -345,11 +387,11 @@ template <int D, int KVB> __device__ __forceinline__ void lane_setup(LaneConst<D
         }
     } else {
         // ds_read_b64_tr_b8: lane a supplies row a/2 of eight, d = 16*dt + 8*(a%2) .. +7 (8 bytes); rows 0-3 are
-        // keys 4j .. 4j+3, rows 4-7 repeat them (only the first four result bytes are used)
+        // keys 4j .. 4j+3 of the stage's first page, rows 4-7 the same keys of its second page (the next tile)
         const int vrow = 4 * j + ((a >> 1) & 3);
 #pragma unroll
         for (int dt = 0; dt < G::kDTiles; dt++)
-            lc.v_off[dt] = 16 * (vrow * G::kUnits + (dt ^ (swz(vrow) & UM))) + 8 * (a & 1);
+            lc.v_off[dt] = (a >> 3) * G::kTile + 16 * (vrow * G::kUnits + (dt ^ (swz(vrow) & UM))) + 8 * (a & 1);
     }
 }
 
@@ -360,6 +402,10 @@ __device__ __forceinline__ bf16x4 fp8x4_to_bf16(int codes)
     bf16x2 lo = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes, 1.0f, false);
     bf16x2 hi = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes, 1.0f, true);
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
+}
+__device__ __forceinline__ bf16x8 fp8x8_to_bf16(int c0, int c1)
+{
+    return __builtin_shufflevector(fp8x4_to_bf16(c0), fp8x4_to_bf16(c1), 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
 // One tile.  A full page goes the cheap way (uniform base + lane offset).  In the last page of a sequence
@@ -402,10 +448,13 @@ template <int DPS> struct WaitTail<0, DPS> {
 };
 
 // Attention of NQT*16 query rows over the pages [pg_lo, pg_hi) of one work row; writes the normalised
-// partial output and its log2-sum-exp.  One page (16 keys) per ring stage:
-//   S^T[key, row] = K_tile . Q^T      (16x16x32 MFMA over D; A = K rows straight from LDS, B = Q in registers)
-//   O^T[d, row]  += V_tile^T . P^T    (16x16x16 MFMA over the 16 keys; A = V through the transposing LDS read,
-//                                      B = P, which is the S^T accumulator layout as it stands)
+// partial output and its log2-sum-exp.  Two pages (32 keys) per ring stage:
+//   S^T[key, row] = K_tile . Q^T      (16x16x32 MFMA over D, per page; A = K rows straight from LDS, B = Q in
+//                                      registers)
+//   O^T[d, row]  += V_tiles^T . P^T   (16x16x32 MFMA over the 32 keys; A = V through the transposing LDS read,
+//                                      B = P: the two pages' S^T accumulators side by side, as they stand)
+// The contraction index of the second product may be any permutation of the keys as long as both operands
+// use the same one: slot e of lane group j is key 4j+e of the first page (e < 4) or key 4j+e-4 of the second.
 // In both products a lane owns one query row (lane % 16), so the running max, the rescale factor and the
 // row sum are per-lane scalars; only the row max needs a cross-lane step (lanes l, l^16, l^32, l^48).
 template <int D, int KVB, int NQT, int NST>
@@ -417,24 +466,30 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
     using G = Geo<D, KVB>;
     static_assert((NST - 1) * G::kDmaPerStage < 64, "the vector-memory counter holds 6 bits");
     const int lane = threadIdx.x, j = lane >> 4;
-    const int niter = sg.pg_hi - sg.pg_lo;
+    const int niter = (sg.pg_hi - sg.pg_lo + 1) >> 1;
 
-    auto issue = [&](int it, int pid) {
-        int nv = sg.limit - (sg.pg_lo + it) * kPage;
-        nv = nv > kPage ? kPage : nv;
+    auto issue = [&](int it, int pid0, int pid1) {
+        const int p0 = sg.pg_lo + 2 * it;
+        int nv0 = sg.limit - p0 * kPage, nv1 = nv0 - kPage;
+        nv0 = nv0 > kPage ? kPage : nv0;
+        nv1 = nv1 > kPage ? kPage : (nv1 < 0 ? 0 : nv1); // 0: no second page, every row reads zeros
         const uint32_t sb = lds_addr + (it % NST) * G::kStage;
-        const int64_t off = (int64_t)pid * a.stride_page_b + (int64_t)sg.kvh * a.stride_head_b;
-        issue_tile<D, KVB>(lc, a.k_pool + off, nv, sb, a.zeros);
-        issue_tile<D, KVB>(lc, a.v_pool + off, nv, sb + G::kTile, a.zeros);
+        const int64_t off0 = (int64_t)pid0 * a.stride_page_b + (int64_t)sg.kvh * a.stride_head_b;
+        const int64_t off1 = (int64_t)pid1 * a.stride_page_b + (int64_t)sg.kvh * a.stride_head_b;
+        issue_tile<D, KVB>(lc, a.k_pool + off0, nv0, sb, a.zeros);
+        issue_tile<D, KVB>(lc, a.k_pool + off1, nv1, sb + G::kTile, a.zeros);
+        issue_tile<D, KVB>(lc, a.v_pool + off0, nv0, sb + 2 * G::kTile, a.zeros);
+        issue_tile<D, KVB>(lc, a.v_pool + off1, nv1, sb + 3 * G::kTile, a.zeros);
         if (KVB == 1) {
-            // the page's two scales land behind the tiles: lane 0 brings k_scale, lane 1 v_scale
-            const int64_t si = (int64_t)pid * a.Hkv + sg.kvh;
-            const void *src = lane == 0 ? (const void *)(a.k_scale + si) : lane == 1 ? (const void *)(a.v_scale + si) : a.zeros;
-            dma4(src, sb + 2 * G::kTile);
+            // the pages' scales land behind the tiles: lanes 0..3 bring k0, v0, k1, v1
+            const int64_t si = (int64_t)((lane & 2) ? pid1 : pid0) * a.Hkv + sg.kvh;
+            const bool have = lane < 2 || (lane < 4 && nv1 > 0);
+            const void *src = !have ? a.zeros : (lane & 1) ? (const void *)(a.v_scale + si) : (const void *)(a.k_scale + si);
+            dma4(src, sb + 4 * G::kTile);
         }
     };
-    auto page_id = [&](int it) {
-        int p = sg.pg_lo + it;
+    auto page_id = [&](int it, int h) {
+        int p = sg.pg_lo + 2 * it + h;
         return p < sg.pg_hi ? sg.pages[p] : 0;
     };
 
@@ -454,12 +509,13 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
     }
 
     // page ids run one stage ahead of the loads that use them
-    int nid = page_id(0);
+    int nid0 = page_id(0, 0), nid1 = page_id(0, 1);
 #pragma unroll
     for (int s = 0; s < NST - 1; s++)
         if (s < niter) {
-            issue(s, nid);
-            nid = page_id(s + 1);
+            issue(s, nid0, nid1);
+            nid0 = page_id(s + 1, 0);
+            nid1 = page_id(s + 1, 1);
         }
 
     // Make the compiler wait for the query loads here, once, instead of at their first use inside the loop
@@ -482,61 +538,78 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
 
     for (int it = 0; it < niter; it++) {
         if (it + NST - 1 < niter) {
-            issue(it + NST - 1, nid);
-            nid = page_id(it + NST);
+            issue(it + NST - 1, nid0, nid1);
+            nid0 = page_id(it + NST, 0);
+            nid1 = page_id(it + NST, 1);
             wait_vmcnt<(NST - 1) * G::kDmaPerStage>();
         } else {
             WaitTail<NST - 2, G::kDmaPerStage>::run(niter - 1 - it);
         }
         const uint8_t *st = lds + (it % NST) * G::kStage;
 
-        // scores of the 16 keys of this page
-        f32x4 s[NQT];
+        // scores of the 2 x 16 keys of this stage
+        f32x4 s[NQT][2];
 #pragma unroll
-        for (int t = 0; t < NQT; t++) s[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int pg = 0; pg < 2; pg++) {
 #pragma unroll
-        for (int i = 0; i < G::kKReads; i++) {
-            if (KVB == 2) {
-                bf16x8 kf = *(const bf16x8 *)(st + lc.k_off[i]);
+            for (int t = 0; t < NQT; t++) s[t][pg] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int t = 0; t < NQT; t++) s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[t][i], s[t], 0, 0, 0);
-            } else {
-                const int4 kc = *(const int4 *)(st + lc.k_off[i]); // 16 codes: two k-steps
-                bf16x8 k0 = __builtin_shufflevector(fp8x4_to_bf16(kc.x), fp8x4_to_bf16(kc.y), 0, 1, 2, 3, 4, 5, 6, 7);
-                bf16x8 k1 = __builtin_shufflevector(fp8x4_to_bf16(kc.z), fp8x4_to_bf16(kc.w), 0, 1, 2, 3, 4, 5, 6, 7);
+            for (int i = 0; i < G::kKReads; i++) {
+                if (KVB == 2) {
+                    bf16x8 kf = *(const bf16x8 *)(st + pg * G::kTile + lc.k_off[i]);
 #pragma unroll
-                for (int t = 0; t < NQT; t++) {
-                    s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[t][2 * i], s[t], 0, 0, 0);
-                    s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[t][2 * i + 1], s[t], 0, 0, 0);
+                    for (int t = 0; t < NQT; t++)
+                        s[t][pg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[t][i], s[t][pg], 0, 0, 0);
+                } else {
+                    const int4 kc = *(const int4 *)(st + pg * G::kTile + lc.k_off[i]); // 16 codes: two k-steps
+                    const bf16x8 k0 = fp8x8_to_bf16(kc.x, kc.y), k1 = fp8x8_to_bf16(kc.z, kc.w);
+#pragma unroll
+                    for (int t = 0; t < NQT; t++) {
+                        s[t][pg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[t][2 * i], s[t][pg], 0, 0, 0);
+                        s[t][pg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[t][2 * i + 1], s[t][pg], 0, 0, 0);
+                    }
                 }
             }
         }
         // e4m3: one scale per (page, head) for K and one for V.  The K scale folds into the fp32 score scale,
         // the V scale into P before it is rounded to bf16 (the row sum keeps the unscaled weights).
-        float kscale = a.scale_log2, vscale = 1.0f;
+        float ks0 = a.scale_log2, ks1 = a.scale_log2, vs0 = 1.0f, vs1 = 1.0f;
         if (KVB == 1) {
-            const float2 sc = *(const float2 *)(st + 2 * G::kTile);
-            kscale *= sc.x;
-            vscale = sc.y;
+            const f32x4 sc = *(const f32x4 *)(st + 4 * G::kTile);
+            ks0 *= sc[0], vs0 = sc[1], ks1 *= sc[2], vs1 = sc[3];
         }
-        const int tok0 = (sg.pg_lo + it) * kPage + 4 * j; // this lane's first token of the page
-        const bool ragged = (sg.pg_lo + it + 1) * kPage > sg.limit;
-        s16x4 pf[NQT];
+        const int tok0 = (sg.pg_lo + 2 * it) * kPage + 4 * j; // this lane's first token in the stage's first page
+        const bool ragged = (sg.pg_lo + 2 * it + 2) * kPage > sg.limit;
+        bf16x8 pf[NQT];
 #pragma unroll
         for (int t = 0; t < NQT; t++) {
-            f32x4 v = s[t] * kscale;
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                v[e] = s[t][0][e] * ks0;
+                v[4 + e] = s[t][1][e] * ks1;
+            }
             if (ragged) {
 #pragma unroll
-                for (int e = 0; e < 4; e++)
+                for (int e = 0; e < 4; e++) {
                     if (tok0 + e >= sg.limit) v[e] = -INFINITY;
+                    if (tok0 + kPage + e >= sg.limit) v[4 + e] = -INFINITY;
+                }
             }
-            const float mx = row_max(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])));
+            const float mx = row_max(fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7]))));
             const float mn = fmaxf(m[t], mx);
-            f32x4 p;
+            f32x8 p;
 #pragma unroll
-            for (int e = 0; e < 4; e++) p[e] = __builtin_amdgcn_exp2f(v[e] - mn);
-            const float ps = (p[0] + p[1]) + (p[2] + p[3]);
-            pf[t] = __builtin_bit_cast(s16x4, __builtin_convertvector(KVB == 1 ? p * vscale : p, bf16x4));
+            for (int e = 0; e < 8; e++) p[e] = __builtin_amdgcn_exp2f(v[e] - mn);
+            const float ps = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+            if (KVB == 1) {
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                    p[e] *= vs0;
+                    p[4 + e] *= vs1;
+                }
+            }
+            pf[t] = __builtin_convertvector(p, bf16x8);
             // the running max rarely moves after the first pages: rescale only when some row's did
             if (__any(mn != m[t])) {
                 const float alpha = __builtin_amdgcn_exp2f(m[t] - mn);
@@ -551,18 +624,21 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
         typedef s16x4 __attribute__((address_space(3))) * lds_s16x4;
         typedef int __attribute__((ext_vector_type(2))) i32x2;
         typedef i32x2 __attribute__((address_space(3))) * lds_i32x2;
-        const uint32_t vb = lds_addr + (it % NST) * G::kStage + G::kTile;
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        const uint32_t vb = lds_addr + (it % NST) * G::kStage + 2 * G::kTile;
 #pragma unroll
         for (int dt = 0; dt < G::kDTiles; dt++) {
-            s16x4 vf;
+            bf16x8 vf;
             if (KVB == 2) {
-                vf = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(vb + lc.v_off[dt]));
+                const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(vb + lc.v_off[dt]));
+                const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(vb + G::kTile + lc.v_off[dt]));
+                vf = __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7));
             } else {
                 const i32x2 vc = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2)(vb + lc.v_off[dt]));
-                vf = __builtin_bit_cast(s16x4, fp8x4_to_bf16(vc[0]));
+                vf = fp8x8_to_bf16(vc[0], vc[1]);
             }
 #pragma unroll
-            for (int t = 0; t < NQT; t++) o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf, pf[t], o[t][dt], 0, 0, 0);
+            for (int t = 0; t < NQT; t++) o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[t], o[t][dt], 0, 0, 0);
         }
         // every LDS read of this stage has returned before a later load may overwrite it
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -589,8 +665,9 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
 #define RA_ATTN_PARAMS                                                                                                    \
     Launch a, const uint16_t *__restrict__ q, const int32_t *__restrict__ block_table, const int32_t *__restrict__ pfx_off, \
         const int32_t *__restrict__ pfx_pages, const int32_t *__restrict__ hdr, const int32_t *__restrict__ row_start,     \
-        const int4 *__restrict__ row_info, const int32_t *__restrict__ span_first_row, const int32_t *__restrict__ members
-#define RA_ATTN_ARGS a, q, block_table, pfx_off, pfx_pages, hdr, row_start, row_info, span_first_row, members
+        const int4 *__restrict__ row_info, const int32_t *__restrict__ span_first_row, const int32_t *__restrict__ members,  \
+        const int32_t *__restrict__ span_lo
+#define RA_ATTN_ARGS a, q, block_table, pfx_off, pfx_pages, hdr, row_start, row_info, span_first_row, members, span_lo
 
 template <int D, int KVB, int NST> __device__ __forceinline__ void attention_body(RA_ATTN_PARAMS, int32_t *next_span)
 {
@@ -599,18 +676,14 @@ template <int D, int KVB, int NST> __device__ __forceinline__ void attention_bod
     const Workspace &w = a.ws;
     const int lane = threadIdx.x;
     const int U = hdr[0], nR = hdr[2], nPR = hdr[3], nspans = hdr[7];
-    Spans sp;
-    sp.waves = a.waves;
-    sp.S0 = hdr[1];
-    sp.cd = hdr[6];
 
     LaneConst<D, KVB> lc;
     lane_setup<D, KVB>(lc, lane, a.stride_token_b);
 
     int span = blockIdx.x;
     while (span < nspans) {
-        const int u_lo = sp.lo(span);
-        const int u_hi = min(U, sp.hi(span));
+        const int u_lo = span_lo[span];
+        const int u_hi = min(U, span_lo[span + 1]);
         if (u_lo >= u_hi) break;
         // take the next span now; the answer is needed only when this one is done
         int next = 0;
@@ -670,20 +743,23 @@ template <int D, int KVB, int NST> __device__ __forceinline__ void attention_bod
     }
 }
 
-// bf16 KV: ring of four pages with one wave per SIMD, or of two pages with two waves per SIMD.  e4m3 KV: pages
-// are half the size, so the ring is eight deep.
-template <int D> __global__ __launch_bounds__(64) void attention_kernel_s4(RA_ATTN_PARAMS, int32_t *next_span)
+// Ring depths (in stages of two pages).  bf16 KV: two stages (32 KB) or three (48 KB).  e4m3 KV: pages are half
+// the size, so four stages.
+template <int D> __global__ __launch_bounds__(64) void attention_kernel_s3(RA_ATTN_PARAMS, int32_t *next_span)
 {
-    attention_body<D, 2, 4>(RA_ATTN_ARGS, next_span);
+    attention_body<D, 2, 3>(RA_ATTN_ARGS, next_span);
 }
-template <int D>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attention_kernel_s2(RA_ATTN_PARAMS, int32_t *next_span)
+template <int D> __global__ __launch_bounds__(64) void attention_kernel_s2(RA_ATTN_PARAMS, int32_t *next_span)
 {
     attention_body<D, 2, 2>(RA_ATTN_ARGS, next_span);
 }
 template <int D> __global__ __launch_bounds__(64) void attention_kernel_fp8(RA_ATTN_PARAMS, int32_t *next_span)
 {
-    attention_body<D, 1, 8>(RA_ATTN_ARGS, next_span);
+    attention_body<D, 1, 4>(RA_ATTN_ARGS, next_span);
+}
+template <int D> __global__ __launch_bounds__(64) void attention_kernel_fp8_s2(RA_ATTN_PARAMS, int32_t *next_span)
+{
+    attention_body<D, 1, 2>(RA_ATTN_ARGS, next_span);
 }
 
 static size_t attention_lds_bytes(int D, int kv_fp8, int stages)
@@ -694,25 +770,27 @@ static size_t attention_lds_bytes(int D, int kv_fp8, int stages)
 
 static const void *attention_fn(int D, int kv_fp8, int stages)
 {
+    if (kv_fp8 && stages == 2) return D == 128 ? (const void *)attention_kernel_fp8_s2<128> : (const void *)attention_kernel_fp8_s2<64>;
     if (kv_fp8) return D == 128 ? (const void *)attention_kernel_fp8<128> : (const void *)attention_kernel_fp8<64>;
     if (stages == 2) return D == 128 ? (const void *)attention_kernel_s2<128> : (const void *)attention_kernel_s2<64>;
-    return D == 128 ? (const void *)attention_kernel_s4<128> : (const void *)attention_kernel_s4<64>;
+    return D == 128 ? (const void *)attention_kernel_s3<128> : (const void *)attention_kernel_s3<64>;
 }
 
 hipError_t attention_config(int D, int kv_fp8, int num_cus, int *stages, int *waves)
 {
-    int st = 4, per_cu = 4;
-    if (kv_fp8) {
-        st = 8;
-    } else {
-        if (const char *ev = getenv("ROLLOUT_ATTN_STAGES")) st = atoi(ev) == 2 ? 2 : 4;
-        if (st == 2) per_cu = 8;
+    int st = kv_fp8 ? 4 : 2, per_cu = 4;
+    if (const char *ev = getenv(kv_fp8 ? "ROLLOUT_ATTN_FP8_STAGES" : "ROLLOUT_ATTN_STAGES")) {
+        int v = atoi(ev);
+        if (kv_fp8 && (v == 2 || v == 4)) st = v;
+        if (!kv_fp8 && (v == 2 || v == 3)) st = v;
     }
+    size_t lds = attention_lds_bytes(D, kv_fp8, st);
+    per_cu = (int)((160u * 1024u) / lds);
+    if (per_cu > 4) per_cu = 4; // one wave per SIMD
     if (const char *ev = getenv("ROLLOUT_ATTN_WAVES_PER_CU")) {
         int v = atoi(ev);
         if (v >= 1 && v <= 16) per_cu = v;
     }
-    size_t lds = attention_lds_bytes(D, kv_fp8, st);
     hipError_t e = hipFuncSetAttribute(attention_fn(D, kv_fp8, st), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     *stages = st;
@@ -726,16 +804,19 @@ hipError_t launch_attention(const Launch &a, hipStream_t s)
     const Workspace &w = a.ws;
 #define RA_LAUNCH(K)                                                                                                      \
     hipLaunchKernelGGL(K, dim3(a.waves), dim3(64), lds, s, a, a.q, a.block_table, a.pfx_off, a.pfx_pages, w.hdr, w.row_start, \
-                       w.row_info, w.span_first_row, w.members, w.hdr + 5)
-    if (a.kv_fp8) {
+                       w.row_info, w.span_first_row, w.members, w.span_lo, w.hdr + 5)
+    if (a.kv_fp8 && a.stages == 2) {
+        if (a.D == 128) RA_LAUNCH(attention_kernel_fp8_s2<128>);
+        else RA_LAUNCH(attention_kernel_fp8_s2<64>);
+    } else if (a.kv_fp8) {
         if (a.D == 128) RA_LAUNCH(attention_kernel_fp8<128>);
         else RA_LAUNCH(attention_kernel_fp8<64>);
     } else if (a.stages == 2) {
         if (a.D == 128) RA_LAUNCH(attention_kernel_s2<128>);
         else RA_LAUNCH(attention_kernel_s2<64>);
     } else {
-        if (a.D == 128) RA_LAUNCH(attention_kernel_s4<128>);
-        else RA_LAUNCH(attention_kernel_s4<64>);
+        if (a.D == 128) RA_LAUNCH(attention_kernel_s3<128>);
+        else RA_LAUNCH(attention_kernel_s3<64>);
     }
 #undef RA_LAUNCH
     return hipGetLastError();
@@ -756,54 +837,37 @@ struct PartList {
     int S, cw, n, c_lo, c_hi;
 };
 
-__global__ __launch_bounds__(kMergeThreads) void merge_kernel(Launch a, const int32_t *__restrict__ hdr,
-                                                               const int32_t *__restrict__ row_start,
-                                                               const int4 *__restrict__ row_info,
+__global__ __launch_bounds__(kMergeThreads) void merge_kernel(Launch a, const int4 *__restrict__ merge_desc,
+                                                               const int32_t *__restrict__ span_lo,
                                                                const int32_t *__restrict__ seq_pfx_row,
-                                                               const int32_t *__restrict__ seq_rank)
+                                                               const int32_t *__restrict__ seq_rank_in_row)
 {
     const Workspace &w = a.ws;
-    const int b = blockIdx.x / a.Hkv, kvh = blockIdx.x - b * a.Hkv;
-    const int nPR = hdr[3];
-    Spans sp;
-    sp.waves = a.waves;
-    sp.S0 = hdr[1];
-    sp.cd = hdr[6];
+    const int item = blockIdx.x;
+    const int b = item / a.Hkv, kvh = item - b * a.Hkv;
     const int D = a.D, tpr = D / 4; // threads per output row
+    const int4 own = merge_desc[2 * item], pfx = merge_desc[2 * item + 1];
+    const int prow = seq_pfx_row[b];
+    const int row0 = seq_rank_in_row[b] * a.G;
     PartList pl[2];
     {
-        const int r = nPR + b;
         PartList &p = pl[1];
-        p.n = row_info[r].w;
+        p.S = own.x, p.n = own.y, p.c_lo = own.z, p.c_hi = own.w;
         p.cw = kCostSuffix;
-        p.S = a.Hkv * row_start[r] + kvh * p.cw * p.n;
-        p.c_lo = sp.of(p.S);
-        p.c_hi = p.n > 0 ? sp.of(p.S + p.cw * (p.n - 1)) : p.c_lo - 1;
-        const int64_t item = (int64_t)b * a.Hkv + kvh;
-        p.o = w.suf_o + item * a.G * D;
-        p.lse = w.suf_lse + item * a.G;
+        p.o = w.suf_o + (int64_t)item * a.G * D;
+        p.lse = w.suf_lse + (int64_t)item * a.G;
         p.ostride = (int64_t)a.G * D;
         p.lstride = a.G;
     }
-    const int prow = seq_pfx_row[b];
     {
         PartList &p = pl[0];
-        if (prow >= 0) {
-            p.n = row_info[prow].w;
-            p.cw = a.cost_prefix;
-            p.S = a.Hkv * row_start[prow] + kvh * p.cw * p.n;
-            p.c_lo = sp.of(p.S);
-            p.c_hi = sp.of(p.S + p.cw * (p.n - 1));
-            const int64_t item = (int64_t)prow * a.Hkv + kvh;
-            const int row0 = seq_rank[b] * a.G;
-            p.o = w.pfx_o + (item * kPrefixRows + row0) * D;
-            p.lse = w.pfx_lse + item * kPrefixRows + row0;
-            p.ostride = (int64_t)kPrefixRows * D;
-            p.lstride = kPrefixRows;
-        } else {
-            p = pl[1];
-            p.c_hi = p.c_lo - 1;
-        }
+        p.S = pfx.x, p.n = pfx.y, p.c_lo = pfx.z, p.c_hi = pfx.w;
+        p.cw = a.cost_prefix;
+        const int64_t pitem = (int64_t)(prow < 0 ? 0 : prow) * a.Hkv + kvh;
+        p.o = w.pfx_o + (pitem * kPrefixRows + row0) * D;
+        p.lse = w.pfx_lse + pitem * kPrefixRows + row0;
+        p.ostride = (int64_t)kPrefixRows * D;
+        p.lstride = kPrefixRows;
     }
     for (int hl = threadIdx.x / tpr; hl < a.G; hl += kMergeThreads / tpr) {
         const int d4 = (threadIdx.x % tpr) * 4;
@@ -811,7 +875,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(Launch a, const in
         for (int k = 0; k < 2; k++)
             for (int c = pl[k].c_lo; c <= pl[k].c_hi; c++) {
                 int p_lo, p_hi;
-                span_pages(pl[k].S, pl[k].cw, pl[k].n, sp.lo(c), sp.hi(c), p_lo, p_hi);
+                span_pages(pl[k].S, pl[k].cw, pl[k].n, span_lo[c], span_lo[c + 1], p_lo, p_hi);
                 if (p_lo < p_hi) M = fmaxf(M, pl[k].lse[c * pl[k].lstride + hl]);
             }
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -819,7 +883,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(Launch a, const in
         for (int k = 0; k < 2; k++)
             for (int c = pl[k].c_lo; c <= pl[k].c_hi; c++) {
                 int p_lo, p_hi;
-                span_pages(pl[k].S, pl[k].cw, pl[k].n, sp.lo(c), sp.hi(c), p_lo, p_hi);
+                span_pages(pl[k].S, pl[k].cw, pl[k].n, span_lo[c], span_lo[c + 1], p_lo, p_hi);
                 if (p_lo >= p_hi) continue;
                 const float wgt = __builtin_amdgcn_exp2f(pl[k].lse[c * pl[k].lstride + hl] - M);
                 wsum += wgt;
@@ -838,8 +902,8 @@ hipError_t launch_merge(const Launch &a, hipStream_t s)
 {
     if (a.B == 0) return hipSuccess;
     const Workspace &w = a.ws;
-    hipLaunchKernelGGL(merge_kernel, dim3(a.B * a.Hkv), dim3(kMergeThreads), 0, s, a, w.hdr, w.row_start, w.row_info,
-                       w.seq_pfx_row, w.seq_rank);
+    hipLaunchKernelGGL(merge_kernel, dim3(a.B * a.Hkv), dim3(kMergeThreads), 0, s, a, w.merge_desc, w.span_lo, w.seq_pfx_row,
+                       w.seq_rank_in_row);
     return hipGetLastError();
 }
 

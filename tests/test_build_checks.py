@@ -33,4 +33,4 @@ def test_no_scratch_and_no_full_drain_in_the_page_loop(isa):
         assert ".private_segment_fixed_size: 0" in isa
         assert "scratch_" not in body, name
         # the LDS ring is paced by hand-written waits with a non-zero count; they must be there
-        assert re.search(r"s_waitcnt vmcnt\((4|5|8|12|16|24|35)\)", body), name
+        assert re.search(r"s_waitcnt vmcnt\([1-9][0-9]*\)", body), name
