@@ -301,21 +301,26 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 // 16 bytes per lane from global memory straight into LDS at lds_addr + lane*16 (no registers in between).
 // The compiler does not see these as loads, so their completion is tracked by hand with wait_vmcnt().
 // Two address forms: a full 64-bit address per lane, or a wave-uniform base plus a 32-bit lane offset.
+// (The LDS address and the base are wave-uniform by construction; readfirstlane says so to the compiler, which
+// may have computed them on the vector unit.)
 __device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_addr)
 {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr)
-                 : "memory", "m0");
+    const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_addr);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(m0) : "memory", "m0");
 }
 __device__ __forceinline__ void dma16_base(uint32_t lane_off, const void *uniform_base, uint32_t lds_addr)
 {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(uniform_base),
-                 "s"(lds_addr)
+    const uint64_t u = (uint64_t)(uintptr_t)uniform_base;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u), hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
+    const uint64_t sbase = ((uint64_t)hi << 32) | lo;
+    const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_addr);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(sbase), "s"(m0)
                  : "memory", "m0");
 }
-
 __device__ __forceinline__ void dma4(const void *gptr, uint32_t lds_addr) // 4 bytes per lane, to lds_addr + lane*4
 {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(gptr), "s"(lds_addr) : "memory", "m0");
+    const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_addr);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(gptr), "s"(m0) : "memory", "m0");
 }
 
 // Reductions over the four lanes that own one query row (l, l^16, l^32, l^48), on the VALU (no LDS trip).
@@ -355,6 +360,8 @@ template <int D, int KVB> struct Geo {
 template <int D, int KVB> struct LaneConst {
     int dma_row[Geo<D, KVB>::kDmaPerTile];
     int dma_off[Geo<D, KVB>::kDmaPerTile];
+    int q_row[D * 2 / 64], q_off[D * 2 / 64]; // placement of a tile of 16 contiguous bf16 query rows
+    int kq_off[D / 32];                       // where lane (row, j) finds its Q operand of k-step i in that tile
     int k_off[Geo<D, KVB>::kKReads];
     int v_off[Geo<D, KVB>::kDTiles];
 };
@@ -370,6 +377,24 @@ template <int D, int KVB> __device__ __forceinline__ void lane_setup(LaneConst<D
         int c = cp ^ (swz(r) & UM);
         lc.dma_row[n] = r;
         lc.dma_off[n] = r * stride_token_b + c * 16;
+    }
+    {
+        // query tile: 16 rows of D bf16, 16-byte units swizzled inside the row like a bf16 K tile
+        constexpr int QU = D * 2 / 16, QM = QU - 1;
+#pragma unroll
+        for (int n = 0; n < D * 2 / 64; n++) {
+            int slot = 64 * n + lane;
+            int r = slot / QU, cp = slot % QU;
+            lc.q_row[n] = r;
+            lc.q_off[n] = r * (D * 2) + (cp ^ (swz(r) & QM)) * 16;
+        }
+        const int r = lane & 15, j = lane >> 4;
+#pragma unroll
+        for (int i = 0; i < D / 32; i++) {
+            // the eight d values of k-step i that this lane's K operand holds start at d0 (see run_segment)
+            const int d0 = KVB == 2 ? 32 * i + 8 * j : 16 * (4 * (i / 2) + j) + 8 * (i % 2);
+            lc.kq_off[i] = 16 * (r * QU + ((d0 / 8) ^ (swz(r) & QM)));
+        }
     }
     // K operand: lane (key = lane%16, j = lane/16) reads unit 4*i + j of its key's row
     const int r = lane & 15, j = lane >> 4;
@@ -428,12 +453,57 @@ __device__ __forceinline__ void issue_tile(const LaneConst<D, KVB> &lc, const ui
     }
 }
 
+// Wave-uniform lookups in read-only tables (block table, schedule): read through the constant address space
+// so that they are scalar loads, which leave the vector-memory counter that paces the ring alone.
+typedef const int32_t __attribute__((address_space(4))) *const_i32_ptr;
+__device__ __forceinline__ int32_t uniform_load(const int32_t *p, int64_t i) { return ((const_i32_ptr)(uintptr_t)p)[i]; }
+
+// One unit of work of a wave: pages [pg_lo, pg_hi) of one (work row, kv head) item.  All fields are wave-uniform.
 struct Segment {
-    const int32_t *__restrict__ pages; // page ids of the work row (uniform)
-    int pg_lo, pg_hi;                  // pages of the row this wave covers
-    int limit;                         // tokens of the row that exist and belong to this span: min(valid, 16*pg_hi)
+    const int32_t *pages; // page ids of the work row (read with uniform_load)
+    int pg_lo, pg_hi;
+    int limit;            // tokens of the row that exist and belong to this piece: min(valid, 16*pg_hi)
     int kvh;
+    int prefix;           // 1: shared prompt pages of a group, 0: a sequence's own pages
+    int b;                // the sequence (own pages)
+    int moff, nrows;      // shared pages: first slot in members[], query rows in use
+    int64_t slot;         // partial-result slot
+    __device__ __forceinline__ int stages() const { return (pg_hi - pg_lo + 1) >> 1; }
 };
+
+// The wave's LDS ring: stages (two pages each) are numbered in the order the wave streams them, across
+// segments; stage n lives in ring slot n % NST.
+struct Ring {
+    int issued; // stages whose loads have been issued
+    int waited; // stages whose loads have been waited for (and consumed)
+    int qslot;  // the query slot of the current segment; alternates with every segment
+};
+
+template <int D, int KVB, int NST> struct LdsMap {
+    using G = Geo<D, KVB>;
+    static constexpr int kQTile = kPage * D * 2;   // 16 query rows of bf16
+    static constexpr int kQBase = NST * G::kStage; // two query slots follow the ring
+    static constexpr int kBytes = NST * G::kStage + 2 * kQTile;
+};
+
+// A finished partial of an own-pages segment, kept in registers.  Stores share the vector-memory counter with the
+// ring's loads and take a full loaded-memory round trip to drain, so a wave keeps its partials (it rarely has
+// more than three) and writes them when it has nothing left to stream.
+template <int D> struct Pending {
+    f32x4 o[D / 16];
+    float lse2;
+    int64_t slot; // wave-uniform
+};
+template <int D> __device__ __forceinline__ void store_pending(const Launch &a, const Pending<D> &p, int lane)
+{
+    const int row = lane & 15, j = lane >> 4;
+    if (row < a.G) {
+        float *dst = a.ws.suf_o + (p.slot * a.G + row) * D + 4 * j;
+#pragma unroll
+        for (int dt = 0; dt < D / 16; dt++) *(f32x4 *)(dst + 16 * dt) = p.o[dt];
+        if (j == 0) a.ws.suf_lse[p.slot * a.G + row] = p.lse2;
+    }
+}
 
 // Waits until at most min(stages_after, N) younger stages of DPS loads each are still in flight.
 template <int N, int DPS> struct WaitTail {
@@ -447,8 +517,49 @@ template <int DPS> struct WaitTail<0, DPS> {
     static __device__ __forceinline__ void run(int) { wait_vmcnt<0>(); }
 };
 
-// Attention of NQT*16 query rows over the pages [pg_lo, pg_hi) of one work row; writes the normalised
-// partial output and its log2-sum-exp.  Two pages (32 keys) per ring stage:
+// Loads of one stage (two pages: K0 K1 V0 V1, and for e4m3 the four scales) of a segment into a ring slot.
+template <int D, int KVB, int NST>
+__device__ __forceinline__ void issue_stage(const Launch &a, const LaneConst<D, KVB> &lc, const Segment &sg, int st, int pid0,
+                                            int pid1, int ring_slot, uint32_t lds_addr)
+{
+    using G = Geo<D, KVB>;
+    const int lane = threadIdx.x;
+    const int p0 = sg.pg_lo + 2 * st;
+    int nv0 = sg.limit - p0 * kPage, nv1 = nv0 - kPage;
+    nv0 = nv0 > kPage ? kPage : nv0;
+    nv1 = nv1 > kPage ? kPage : (nv1 < 0 ? 0 : nv1); // 0: no second page, every row reads zeros
+    const uint32_t sb = lds_addr + ring_slot * G::kStage;
+    const int64_t off0 = (int64_t)pid0 * a.stride_page_b + (int64_t)sg.kvh * a.stride_head_b;
+    const int64_t off1 = (int64_t)pid1 * a.stride_page_b + (int64_t)sg.kvh * a.stride_head_b;
+    issue_tile<D, KVB>(lc, a.k_pool + off0, nv0, sb, a.zeros);
+    issue_tile<D, KVB>(lc, a.k_pool + off1, nv1, sb + G::kTile, a.zeros);
+    issue_tile<D, KVB>(lc, a.v_pool + off0, nv0, sb + 2 * G::kTile, a.zeros);
+    issue_tile<D, KVB>(lc, a.v_pool + off1, nv1, sb + 3 * G::kTile, a.zeros);
+    if (KVB == 1) {
+        // the pages' scales land behind the tiles: lanes 0..3 bring k0, v0, k1, v1
+        const int64_t si = (int64_t)((lane & 2) ? pid1 : pid0) * a.Hkv + sg.kvh;
+        const bool have = lane < 2 || (lane < 4 && nv1 > 0);
+        const void *src = !have ? a.zeros : (lane & 1) ? (const void *)(a.v_scale + si) : (const void *)(a.k_scale + si);
+        dma4(src, sb + 4 * G::kTile);
+    }
+}
+
+// Query rows of an own-pages segment: the G heads of (b, kvh) are contiguous in q; rows G..15 read zeros.
+template <int D, int KVB, int NST>
+__device__ __forceinline__ void issue_q(const Launch &a, const uint16_t *__restrict__ q, const LaneConst<D, KVB> &lc,
+                                        const Segment &sg, int qslot, uint32_t lds_addr)
+{
+    using M = LdsMap<D, KVB, NST>;
+    const uint8_t *src = (const uint8_t *)(q + ((int64_t)sg.b * a.Hq + (int64_t)sg.kvh * a.G) * D);
+    const uint32_t dst = lds_addr + M::kQBase + qslot * M::kQTile;
+#pragma unroll
+    for (int n = 0; n < D * 2 / 64; n++) {
+        const void *p = lc.q_row[n] < a.G ? (const void *)(src + lc.q_off[n]) : a.zeros;
+        dma16(p, dst + 1024 * n);
+    }
+}
+
+// Attention of NQT*16 query rows over one segment.  Two pages (32 keys) per ring stage:
 //   S^T[key, row] = K_tile . Q^T      (16x16x32 MFMA over D, per page; A = K rows straight from LDS, B = Q in
 //                                      registers)
 //   O^T[d, row]  += V_tiles^T . P^T   (16x16x32 MFMA over the 32 keys; A = V through the transposing LDS read,
@@ -457,73 +568,69 @@ template <int DPS> struct WaitTail<0, DPS> {
 // use the same one: slot e of lane group j is key 4j+e of the first page (e < 4) or key 4j+e-4 of the second.
 // In both products a lane owns one query row (lane % 16), so the running max, the rescale factor and the
 // row sum are per-lane scalars; only the row max needs a cross-lane step (lanes l, l^16, l^32, l^48).
+//
+// The ring does not run dry at a segment boundary: while the last stages of this segment are consumed, the
+// first stages (and the query rows) of the next one are already being loaded.  On entry, the first
+// min(NST-1, stages) stages of this segment are in flight; on exit the same holds for `nxt`.
+// A one-tile partial goes back in `ret` (normalised, with its log2-sum-exp); a shared-prefix partial is stored.
 template <int D, int KVB, int NQT, int NST>
-__device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__restrict__ q, const Segment &sg,
-                                            const LaneConst<D, KVB> &lc, uint8_t *lds, uint32_t lds_addr,
-                                            const int (&qrow_seq)[NQT], const int (&qrow_head)[NQT], float *part_o,
-                                            float *part_lse, int part_rows)
+__device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__restrict__ q, const int32_t *__restrict__ members,
+                                            const Segment &cur, bool has_nxt, const Segment &nxt, Ring &ring,
+                                            const LaneConst<D, KVB> &lc, uint8_t *lds, uint32_t lds_addr, Pending<D> &ret)
 {
     using G = Geo<D, KVB>;
+    using M = LdsMap<D, KVB, NST>;
     static_assert((NST - 1) * G::kDmaPerStage < 64, "the vector-memory counter holds 6 bits");
     const int lane = threadIdx.x, j = lane >> 4;
-    const int niter = (sg.pg_hi - sg.pg_lo + 1) >> 1;
+    const int niter = cur.stages();
+    const int base = ring.waited; // ring number of this segment's first stage
+    int nxt_pre = 0;
+    if (has_nxt) {
+        nxt_pre = nxt.stages();
+        nxt_pre = nxt_pre < NST - 1 ? nxt_pre : NST - 1;
+    }
+    const int total = niter + nxt_pre;
 
-    auto issue = [&](int it, int pid0, int pid1) {
-        const int p0 = sg.pg_lo + 2 * it;
-        int nv0 = sg.limit - p0 * kPage, nv1 = nv0 - kPage;
-        nv0 = nv0 > kPage ? kPage : nv0;
-        nv1 = nv1 > kPage ? kPage : (nv1 < 0 ? 0 : nv1); // 0: no second page, every row reads zeros
-        const uint32_t sb = lds_addr + (it % NST) * G::kStage;
-        const int64_t off0 = (int64_t)pid0 * a.stride_page_b + (int64_t)sg.kvh * a.stride_head_b;
-        const int64_t off1 = (int64_t)pid1 * a.stride_page_b + (int64_t)sg.kvh * a.stride_head_b;
-        issue_tile<D, KVB>(lc, a.k_pool + off0, nv0, sb, a.zeros);
-        issue_tile<D, KVB>(lc, a.k_pool + off1, nv1, sb + G::kTile, a.zeros);
-        issue_tile<D, KVB>(lc, a.v_pool + off0, nv0, sb + 2 * G::kTile, a.zeros);
-        issue_tile<D, KVB>(lc, a.v_pool + off1, nv1, sb + 3 * G::kTile, a.zeros);
-        if (KVB == 1) {
-            // the pages' scales land behind the tiles: lanes 0..3 bring k0, v0, k1, v1
-            const int64_t si = (int64_t)((lane & 2) ? pid1 : pid0) * a.Hkv + sg.kvh;
-            const bool have = lane < 2 || (lane < 4 && nv1 > 0);
-            const void *src = !have ? a.zeros : (lane & 1) ? (const void *)(a.v_scale + si) : (const void *)(a.k_scale + si);
-            dma4(src, sb + 4 * G::kTile);
+    // page id of page h of the stage with number base + rel (this segment's stages first, then the next one's)
+    auto page_id = [&](int rel, int h) {
+        int id = 0;
+        if (rel < niter) {
+            const int p = cur.pg_lo + 2 * rel + h;
+            if (p < cur.pg_hi) id = uniform_load(cur.pages, p);
+        } else if (rel < total) {
+            const int p = nxt.pg_lo + 2 * (rel - niter) + h;
+            if (p < nxt.pg_hi) id = uniform_load(nxt.pages, p);
         }
+        return id;
     };
-    auto page_id = [&](int it, int h) {
-        int p = sg.pg_lo + 2 * it + h;
-        return p < sg.pg_hi ? sg.pages[p] : 0;
-    };
+    int nid0 = page_id(ring.issued - base, 0), nid1 = page_id(ring.issued - base, 1); // one stage ahead of their use
 
     // Q^T operand: for k-step i, lane (row = lane%16, j) holds the eight d values that its K operand holds.
     // bf16 K: d = 32*i + 8*j .. +7.  e4m3 K: one 16-byte K read carries 16 d values and feeds two k-steps, so
     // d = 16*(4*(i/2) + j) + 8*(i%2) .. +7 (the sum over d does not care about the order).
     bf16x8 qf[NQT][G::kKSteps];
+    if (NQT > 1) {
+        // shared pages: rows = members x G packed densely, gathered straight from global memory; the compiler's
+        // wait for these loads drains the ring once per such segment, and they are few
 #pragma unroll
-    for (int t = 0; t < NQT; t++) {
+        for (int t = 0; t < NQT; t++) {
+            const int row = 16 * t + (lane & 15);
+            const int mi = row / a.G;
+            const int seq = row < cur.nrows ? members[cur.moff + mi] : -1;
+            const int head = cur.kvh * a.G + (row - mi * a.G);
 #pragma unroll
-        for (int i = 0; i < G::kKSteps; i++) {
-            const int d0 = KVB == 2 ? 32 * i + 8 * j : 16 * (4 * (i / 2) + j) + 8 * (i % 2);
-            bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (qrow_seq[t] >= 0) v = *(const bf16x8 *)(q + ((int64_t)qrow_seq[t] * a.Hq + qrow_head[t]) * D + d0);
-            qf[t][i] = v;
+            for (int i = 0; i < G::kKSteps; i++) {
+                const int d0 = KVB == 2 ? 32 * i + 8 * j : 16 * (4 * (i / 2) + j) + 8 * (i % 2);
+                bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+                if (seq >= 0) v = *(const bf16x8 *)(q + ((int64_t)seq * a.Hq + head) * D + d0);
+                qf[t][i] = v;
+            }
         }
-    }
-
-    // page ids run one stage ahead of the loads that use them
-    int nid0 = page_id(0, 0), nid1 = page_id(0, 1);
 #pragma unroll
-    for (int s = 0; s < NST - 1; s++)
-        if (s < niter) {
-            issue(s, nid0, nid1);
-            nid0 = page_id(s + 1, 0);
-            nid1 = page_id(s + 1, 1);
+        for (int t = 0; t < NQT; t++) {
+#pragma unroll
+            for (int i = 0; i < G::kKSteps; i++) asm volatile("" ::"v"(qf[t][i]));
         }
-
-    // Make the compiler wait for the query loads here, once, instead of at their first use inside the loop
-    // (where a full vector-memory wait would drain the ring every iteration).
-#pragma unroll
-    for (int t = 0; t < NQT; t++) {
-#pragma unroll
-        for (int i = 0; i < G::kKSteps; i++) asm volatile("" ::"v"(qf[t][i]));
     }
 
     f32x4 o[NQT][G::kDTiles];
@@ -537,15 +644,32 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
     }
 
     for (int it = 0; it < niter; it++) {
-        if (it + NST - 1 < niter) {
-            issue(it + NST - 1, nid0, nid1);
-            nid0 = page_id(it + NST, 0);
-            nid1 = page_id(it + NST, 1);
-            wait_vmcnt<(NST - 1) * G::kDmaPerStage>();
-        } else {
-            WaitTail<NST - 2, G::kDmaPerStage>::run(niter - 1 - it);
+        // keep NST-1 stages in flight beyond this one
+        int want = it + NST;
+        want = want < total ? want : total;
+        while (ring.issued - base < want) {
+            const int rel = ring.issued - base;
+            if (rel < niter) {
+                issue_stage<D, KVB, NST>(a, lc, cur, rel, nid0, nid1, ring.issued % NST, lds_addr);
+            } else {
+                if (rel == niter && !nxt.prefix) issue_q<D, KVB, NST>(a, q, lc, nxt, ring.qslot ^ 1, lds_addr);
+                issue_stage<D, KVB, NST>(a, lc, nxt, rel - niter, nid0, nid1, ring.issued % NST, lds_addr);
+            }
+            ring.issued++;
+            nid0 = page_id(ring.issued - base, 0);
+            nid1 = page_id(ring.issued - base, 1);
         }
-        const uint8_t *st = lds + (it % NST) * G::kStage;
+        // Loads complete in order.  Anything else issued after this stage (query rows, partial stores) only
+        // makes the wait stricter than needed.
+        WaitTail<NST - 1, G::kDmaPerStage>::run(ring.issued - base - 1 - it);
+        const int rslot = (base + it) % NST;
+        const uint8_t *st = lds + rslot * G::kStage;
+        if (NQT == 1 && it == 0) {
+            // the query rows were loaded ahead of this segment's first stage, so they have landed too
+#pragma unroll
+            for (int i = 0; i < G::kKSteps; i++)
+                qf[0][i] = *(const bf16x8 *)(lds + M::kQBase + ring.qslot * M::kQTile + lc.kq_off[i]);
+        }
 
         // scores of the 2 x 16 keys of this stage
         f32x4 s[NQT][2];
@@ -578,8 +702,8 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
             const f32x4 sc = *(const f32x4 *)(st + 4 * G::kTile);
             ks0 *= sc[0], vs0 = sc[1], ks1 *= sc[2], vs1 = sc[3];
         }
-        const int tok0 = (sg.pg_lo + 2 * it) * kPage + 4 * j; // this lane's first token in the stage's first page
-        const bool ragged = (sg.pg_lo + 2 * it + 2) * kPage > sg.limit;
+        const int tok0 = (cur.pg_lo + 2 * it) * kPage + 4 * j; // this lane's first token in the stage's first page
+        const bool ragged = (cur.pg_lo + 2 * it + 2) * kPage > cur.limit;
         bf16x8 pf[NQT];
 #pragma unroll
         for (int t = 0; t < NQT; t++) {
@@ -592,8 +716,8 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
             if (ragged) {
 #pragma unroll
                 for (int e = 0; e < 4; e++) {
-                    if (tok0 + e >= sg.limit) v[e] = -INFINITY;
-                    if (tok0 + kPage + e >= sg.limit) v[4 + e] = -INFINITY;
+                    if (tok0 + e >= cur.limit) v[e] = -INFINITY;
+                    if (tok0 + kPage + e >= cur.limit) v[4 + e] = -INFINITY;
                 }
             }
             const float mx = row_max(fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7]))));
@@ -625,7 +749,7 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
         typedef int __attribute__((ext_vector_type(2))) i32x2;
         typedef i32x2 __attribute__((address_space(3))) * lds_i32x2;
         typedef short s16x8 __attribute__((ext_vector_type(8)));
-        const uint32_t vb = lds_addr + (it % NST) * G::kStage + 2 * G::kTile;
+        const uint32_t vb = lds_addr + rslot * G::kStage + 2 * G::kTile;
 #pragma unroll
         for (int dt = 0; dt < G::kDTiles; dt++) {
             bf16x8 vf;
@@ -642,26 +766,33 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
         }
         // every LDS read of this stage has returned before a later load may overwrite it
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        ring.waited++;
     }
+    ring.qslot ^= 1; // the next segment's query rows, if it keeps them in LDS, went to the other slot
 
-    // normalise and store the partial
 #pragma unroll
     for (int t = 0; t < NQT; t++) {
         const float l = row_sum(lsum[t]);
-        const int row = 16 * t + (lane & 15);
-        if (row < part_rows) {
-            const float inv = 1.0f / l;
-            float *dst = part_o + (int64_t)row * D + 4 * j;
+        const float inv = 1.0f / l;
+        const float lse2 = m[t] + __builtin_amdgcn_logf(l);
+        if (NQT == 1) {
 #pragma unroll
-            for (int dt = 0; dt < G::kDTiles; dt++) *(f32x4 *)(dst + 16 * dt) = o[t][dt] * inv;
-            if (j == 0) part_lse[row] = m[t] + __builtin_amdgcn_logf(l);
+            for (int dt = 0; dt < G::kDTiles; dt++) ret.o[dt] = o[t][dt] * inv;
+            ret.lse2 = lse2;
+        } else {
+            const int row = 16 * t + (lane & 15);
+            if (row < cur.nrows) {
+                float *dst = a.ws.pfx_o + (cur.slot * kPrefixRows + row) * D + 4 * j;
+#pragma unroll
+                for (int dt = 0; dt < G::kDTiles; dt++) *(f32x4 *)(dst + 16 * dt) = o[t][dt] * inv;
+                if (j == 0) a.ws.pfx_lse[cur.slot * kPrefixRows + row] = lse2;
+            }
         }
     }
 }
 
 // The read-only inputs and the schedule come in as separate restrict pointers so that the compiler can keep
-// every wave-uniform lookup (page ids, row bounds) on the scalar unit, away from the vector-memory counter
-// that paces the LDS ring.
+// every wave-uniform lookup on the scalar unit, away from the vector-memory counter that paces the LDS ring.
 #define RA_ATTN_PARAMS                                                                                                    \
     Launch a, const uint16_t *__restrict__ q, const int32_t *__restrict__ block_table, const int32_t *__restrict__ pfx_off, \
         const int32_t *__restrict__ pfx_pages, const int32_t *__restrict__ hdr, const int32_t *__restrict__ row_start,     \
@@ -673,78 +804,134 @@ template <int D, int KVB, int NST> __device__ __forceinline__ void attention_bod
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     const uint32_t lds_addr = (uint32_t)(uintptr_t)lds;
-    const Workspace &w = a.ws;
     const int lane = threadIdx.x;
-    const int U = hdr[0], nR = hdr[2], nPR = hdr[3], nspans = hdr[7];
+    const int U = uniform_load(hdr, 0), nR = uniform_load(hdr, 2), nPR = uniform_load(hdr, 3), nspans = uniform_load(hdr, 7);
 
     LaneConst<D, KVB> lc;
     lane_setup<D, KVB>(lc, lane, a.stride_token_b);
+    Ring ring = {0, 0, 0};
+    Pending<D> pend[3], fresh;
+    int npend = 0;
 
-    int span = blockIdx.x;
-    while (span < nspans) {
-        const int u_lo = span_lo[span];
-        const int u_hi = min(U, span_lo[span + 1]);
-        if (u_lo >= u_hi) break;
-        // take the next span now; the answer is needed only when this one is done
-        int next = 0;
-        if (lane == 0) next = atomicAdd(next_span, 1);
-
-        for (int r = span_first_row[span]; r < nR; r++) {
-            const int rs = a.Hkv * row_start[r];
-            if (rs >= u_hi) break;
-            const int4 info = row_info[r];
-            const int units = info.w;
-            if (units == 0) continue;
-            const bool prefix = r < nPR;
-            const int cw = prefix ? a.cost_prefix : kCostSuffix;
-            const int ic = cw * units; // cost of one (row, kv head) item
-            int kvh = u_lo > rs ? (u_lo - rs) / ic : 0;
-            for (; kvh < a.Hkv; kvh++) {
-                const int S = rs + kvh * ic;
-                if (S >= u_hi) break;
-                Segment sg;
-                sg.kvh = kvh;
-                span_pages(S, cw, units, u_lo, u_hi, sg.pg_lo, sg.pg_hi);
-                if (sg.pg_lo >= sg.pg_hi) continue;
-                if (!prefix) {
-                    // a sequence's own pages: the G query heads of this kv head form one 16-row tile
-                    const int b = info.x;
-                    sg.pages = block_table + (int64_t)b * a.max_pages + info.y;
-                    sg.limit = min(info.z, sg.pg_hi * kPage);
-                    const int slot = b * a.Hkv + kvh + span;
-                    int qs[1], qh[1];
-                    const int row = lane & 15;
-                    qs[0] = row < a.G ? b : -1;
-                    qh[0] = kvh * a.G + row;
-                    run_segment<D, KVB, 1, NST>(a, q, sg, lc, lds, lds_addr, qs, qh, w.suf_o + (int64_t)slot * a.G * D,
-                                           w.suf_lse + (int64_t)slot * a.G, a.G);
-                } else {
-                    // shared prompt pages of a group: rows = members x G, packed densely into 16-row tiles
-                    const int g = info.x;
-                    sg.pages = pfx_pages + pfx_off[g];
-                    sg.limit = sg.pg_hi * kPage;
-                    const int slot = r * a.Hkv + kvh + span;
-                    const int nrows = info.z * a.G;
-                    int qs[kPrefixTiles], qh[kPrefixTiles];
-#pragma unroll
-                    for (int t = 0; t < kPrefixTiles; t++) {
-                        const int row = 16 * t + (lane & 15);
-                        const int mi = row / a.G;
-                        qs[t] = row < nrows ? members[info.y + mi] : -1;
-                        qh[t] = kvh * a.G + (row - mi * a.G);
-                    }
-                    run_segment<D, KVB, kPrefixTiles, NST>(a, q, sg, lc, lds, lds_addr, qs, qh,
-                                                      w.pfx_o + (int64_t)slot * kPrefixRows * D,
-                                                      w.pfx_lse + (int64_t)slot * kPrefixRows, nrows);
+    // ---- walker: yields this wave's segments in stream order, span after span ----
+    int wk_span = blockIdx.x, wk_lo = 0, wk_hi = 0, wk_r = 0, wk_kvh = -1, wk_rs = 0, wk_units = 0, wk_cw = 1;
+    int wk_x = 0, wk_y = 0, wk_z = 0; // row_info of the current row
+    int wk_next = 0;                  // lane 0: the span taken from the counter
+    bool wk_done = false;
+    const bool dynamic = nspans > a.waves;
+    auto enter_span = [&](int c) {
+        wk_span = c;
+        wk_lo = uniform_load(span_lo, c);
+        wk_hi = min(U, uniform_load(span_lo, c + 1));
+        wk_r = uniform_load(span_first_row, c);
+        wk_kvh = -1;
+        // take the span after this one now; the answer is needed only when this one is exhausted
+        if (dynamic && lane == 0) wk_next = atomicAdd(next_span, 1);
+    };
+    auto advance = [&](Segment &out) -> bool {
+        for (;;) {
+            if (wk_done) return false;
+            if (wk_kvh < 0) { // need a row
+                bool exhausted = wk_r >= nR;
+                if (!exhausted) {
+                    wk_rs = a.Hkv * uniform_load(row_start, wk_r);
+                    exhausted = wk_rs >= wk_hi;
                 }
+                if (exhausted) {
+                    const int nx = dynamic ? __builtin_amdgcn_readfirstlane(wk_next) : nspans;
+                    if (nx >= nspans) {
+                        wk_done = true;
+                        return false;
+                    }
+                    enter_span(nx);
+                    continue;
+                }
+                const int32_t *ri = (const int32_t *)(row_info + wk_r);
+                wk_units = uniform_load(ri, 3);
+                if (wk_units == 0) {
+                    wk_r++;
+                    continue;
+                }
+                wk_x = uniform_load(ri, 0), wk_y = uniform_load(ri, 1), wk_z = uniform_load(ri, 2);
+                wk_cw = wk_r < nPR ? a.cost_prefix : kCostSuffix;
+                const int ic = wk_cw * wk_units;
+                wk_kvh = wk_lo > wk_rs ? (wk_lo - wk_rs) / ic : 0;
             }
+            const int S = wk_rs + wk_kvh * wk_cw * wk_units;
+            if (wk_kvh >= a.Hkv || S >= wk_hi) {
+                wk_r++;
+                wk_kvh = -1;
+                continue;
+            }
+            const int kvh = wk_kvh++;
+            span_pages(S, wk_cw, wk_units, wk_lo, wk_hi, out.pg_lo, out.pg_hi);
+            if (out.pg_lo >= out.pg_hi) continue;
+            out.kvh = kvh;
+            out.prefix = wk_r < nPR;
+            if (!out.prefix) {
+                // a sequence's own pages: the G query heads of this kv head form one 16-row tile
+                out.b = wk_x;
+                out.pages = block_table + (int64_t)wk_x * a.max_pages + wk_y;
+                out.limit = min(wk_z, out.pg_hi * kPage);
+                out.slot = (int64_t)wk_x * a.Hkv + kvh + wk_span;
+                out.moff = 0;
+                out.nrows = a.G;
+            } else {
+                // shared prompt pages of a group: rows = members x G, packed densely into 16-row tiles
+                out.b = 0;
+                out.pages = pfx_pages + uniform_load(pfx_off, wk_x);
+                out.limit = out.pg_hi * kPage;
+                out.slot = (int64_t)wk_r * a.Hkv + kvh + wk_span;
+                out.moff = wk_y;
+                out.nrows = wk_z * a.G;
+            }
+            return true;
         }
-        span = __builtin_amdgcn_readfirstlane(next);
+    };
+
+    if (wk_span >= nspans || uniform_load(span_lo, wk_span) >= U) return;
+    enter_span(wk_span);
+    Segment cur, nxt;
+    bool has_cur = advance(cur);
+    if (has_cur) {
+        // prime the ring with the first segment
+        if (!cur.prefix) issue_q<D, KVB, NST>(a, q, lc, cur, ring.qslot, lds_addr);
+        const int n = min(NST - 1, cur.stages());
+        for (int k = 0; k < n; k++) {
+            const int p = cur.pg_lo + 2 * k;
+            const int id0 = uniform_load(cur.pages, p), id1 = p + 1 < cur.pg_hi ? uniform_load(cur.pages, p + 1) : 0;
+            issue_stage<D, KVB, NST>(a, lc, cur, k, id0, id1, ring.issued % NST, lds_addr);
+            ring.issued++;
+        }
     }
+    while (has_cur) {
+        const bool has_nxt = advance(nxt);
+        if (!cur.prefix) {
+            run_segment<D, KVB, 1, NST>(a, q, members, cur, has_nxt, nxt, ring, lc, lds, lds_addr, fresh);
+            fresh.slot = cur.slot;
+            if (npend == 3) { // full: write the oldest out
+                store_pending<D>(a, pend[0], lane);
+                pend[0] = pend[1];
+                pend[1] = pend[2];
+                npend = 2;
+            }
+            if (npend == 0) pend[0] = fresh;
+            else if (npend == 1) pend[1] = fresh;
+            else pend[2] = fresh;
+            npend++;
+        } else {
+            run_segment<D, KVB, kPrefixTiles, NST>(a, q, members, cur, has_nxt, nxt, ring, lc, lds, lds_addr, fresh);
+        }
+        cur = nxt;
+        has_cur = has_nxt;
+    }
+    if (npend > 0) store_pending<D>(a, pend[0], lane);
+    if (npend > 1) store_pending<D>(a, pend[1], lane);
+    if (npend > 2) store_pending<D>(a, pend[2], lane);
 }
 
-// Ring depths (in stages of two pages).  bf16 KV: two stages (32 KB) or three (48 KB).  e4m3 KV: pages are half
-// the size, so four stages.
+// Ring depths (in stages of two pages).  bf16 KV: two stages (32 KB + 8 KB of query slots, four waves per
+// compute unit) or three.  e4m3 KV: pages are half the size: three stages, or two.
 template <int D> __global__ __launch_bounds__(64) void attention_kernel_s3(RA_ATTN_PARAMS, int32_t *next_span)
 {
     attention_body<D, 2, 3>(RA_ATTN_ARGS, next_span);
@@ -755,7 +942,7 @@ template <int D> __global__ __launch_bounds__(64) void attention_kernel_s2(RA_AT
 }
 template <int D> __global__ __launch_bounds__(64) void attention_kernel_fp8(RA_ATTN_PARAMS, int32_t *next_span)
 {
-    attention_body<D, 1, 4>(RA_ATTN_ARGS, next_span);
+    attention_body<D, 1, 3>(RA_ATTN_ARGS, next_span);
 }
 template <int D> __global__ __launch_bounds__(64) void attention_kernel_fp8_s2(RA_ATTN_PARAMS, int32_t *next_span)
 {
@@ -764,8 +951,12 @@ template <int D> __global__ __launch_bounds__(64) void attention_kernel_fp8_s2(R
 
 static size_t attention_lds_bytes(int D, int kv_fp8, int stages)
 {
-    if (kv_fp8) return (size_t)stages * (D == 128 ? Geo<128, 1>::kStage : Geo<64, 1>::kStage);
-    return (size_t)stages * (D == 128 ? Geo<128, 2>::kStage : Geo<64, 2>::kStage);
+    if (kv_fp8) {
+        if (D == 128) return stages == 2 ? LdsMap<128, 1, 2>::kBytes : LdsMap<128, 1, 3>::kBytes;
+        return stages == 2 ? LdsMap<64, 1, 2>::kBytes : LdsMap<64, 1, 3>::kBytes;
+    }
+    if (D == 128) return stages == 2 ? LdsMap<128, 2, 2>::kBytes : LdsMap<128, 2, 3>::kBytes;
+    return stages == 2 ? LdsMap<64, 2, 2>::kBytes : LdsMap<64, 2, 3>::kBytes;
 }
 
 static const void *attention_fn(int D, int kv_fp8, int stages)
@@ -778,10 +969,10 @@ static const void *attention_fn(int D, int kv_fp8, int stages)
 
 hipError_t attention_config(int D, int kv_fp8, int num_cus, int *stages, int *waves)
 {
-    int st = kv_fp8 ? 4 : 2, per_cu = 4;
+    int st = kv_fp8 ? 3 : 2, per_cu = 4;
     if (const char *ev = getenv(kv_fp8 ? "ROLLOUT_ATTN_FP8_STAGES" : "ROLLOUT_ATTN_STAGES")) {
         int v = atoi(ev);
-        if (kv_fp8 && (v == 2 || v == 4)) st = v;
+        if (kv_fp8 && (v == 2 || v == 3)) st = v;
         if (!kv_fp8 && (v == 2 || v == 3)) st = v;
     }
     size_t lds = attention_lds_bytes(D, kv_fp8, st);
