@@ -14,6 +14,7 @@ struct ra_ctx {
     int waves[2][2];  // resident attention waves, [e4m3 KV][D == 128]
     int stages[2][2]; // LDS ring depth, same indices
     int cost_prefix; // scheduling weight of a shared-prefix page
+    int cost_item;   // ... of a segment, on top of its pages
     int static_pct;  // share of the work that is assigned to waves up front
     int dyn_pages;   // pages per dynamically scheduled span
     int xcd_w[8];    // relative speed of the accelerator dies
@@ -98,6 +99,7 @@ void fill_launch(ra::Launch &a, const ra_ctx *ctx, const ra_problem *p)
     a.stages = ctx ? ctx->stages[a.kv_fp8][p->D == 128] : 4;
     a.members_per_row = ra::kPrefixRows / a.G;
     a.cost_prefix = ctx ? ctx->cost_prefix : ra::kCostPrefix;
+    a.cost_item = ctx ? ctx->cost_item : ra::kCostItem;
     a.static_pct = ctx ? ctx->static_pct : 100;
     a.dyn_pages = ctx ? ctx->dyn_pages : 16;
     {
@@ -142,6 +144,7 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
     memset(c, 0, sizeof *c);
     c->device = device;
     c->cost_prefix = ra::kCostPrefix;
+    c->cost_item = ra::kCostItem;
     c->static_pct = 100;
     c->dyn_pages = 16;
     // Share of the memory bandwidth each accelerator die gets when all eight stream at once, measured on
@@ -152,7 +155,7 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
         int v[8];
         if (sscanf(ev, "%d,%d,%d,%d,%d,%d,%d,%d", &v[0], &v[1], &v[2], &v[3], &v[4], &v[5], &v[6], &v[7]) == 8) {
             bool ok = true;
-            for (int x = 0; x < 8; x++) ok = ok && v[x] >= 100 && v[x] <= 10000;
+            for (int x = 0; x < 8; x++) ok = ok && v[x] >= 700 && v[x] <= 1400; // no span under half the mean
             if (ok)
                 for (int x = 0; x < 8; x++) c->xcd_w[x] = v[x];
         }
@@ -168,6 +171,10 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
     if (const char *ev = getenv("ROLLOUT_ATTN_COST_PREFIX")) {
         int v = atoi(ev);
         if (v >= 1 && v <= 64) c->cost_prefix = v;
+    }
+    if (const char *ev = getenv("ROLLOUT_ATTN_COST_ITEM")) {
+        int v = atoi(ev);
+        if (v >= 0 && v <= 256) c->cost_item = v;
     }
     hipDeviceProp_t prop;
     e = hipGetDeviceProperties(&prop, device);

@@ -12,7 +12,9 @@ constexpr int kPrefixRows = 16 * kPrefixTiles; // = members x heads-per-kv-head 
 constexpr int kMinUnitsPerWave = 8; // do not cut the page stream finer than this many pages
 constexpr int kDynSpansPerWave = 4; // at most this many dynamically scheduled spans per resident wave
 constexpr int kCostSuffix = 4;      // scheduling weight of a page of a sequence's own KV
+constexpr int kChunkSegs = 7;       // segment records per chunk of a span's work list (plus one header record)
 constexpr int kCostPrefix = 5;      // ... of a shared-prefix page (more query rows per byte, so more time per page)
+constexpr int kCostItem = 5;        // ... of a segment, on top of its pages
 
 // Device pointers into the caller's workspace.  All offsets are fixed by the shape alone.
 struct Workspace {
@@ -24,13 +26,12 @@ struct Workspace {
     int32_t *seq_rank;       // [B]   rank inside the group, -1: not a member
     int32_t *seq_pfx_row;    // [B]   prefix row or -1
     int32_t *seq_rank_in_row;// [B]   position among the members of that row
-    int4 *merge_desc;        // [B*Hkv][2]  {first cost unit, pages, first span, last span} of the own row and of the prefix row
+    int4 *merge_desc;        // [B*Hkv][2]  {pages, first span, last span, -} of the own row and of the prefix row
     int32_t *members;        // [B]   sequences ordered by prefix row
     int32_t *row_start;      // [2B + 1] exclusive scan of the rows' cost (per kv head); prefix rows come first
-    int4 *row_info;          // [2B]  prefix row:      {group, first member slot, members, pages}
-                             //       sequence row b:  {b, pages skipped, valid tokens after the skip, pages}
-    int32_t *span_first_row; // [spans + 1]
-    int32_t *span_lo;        // [spans + 1] first cost unit of every span
+    int32_t *prow_g;         // [B]   group of a prefix row
+    int4 *seg_rec;           // [chunks][8][2]  what each span's wave does: chunk c < spans belongs to span c; record 0 of a
+                             //       chunk is {segments in the chunk (<= 7), next chunk of the span or -1}, then the segments
     float *suf_o;            // [(B*Hkv + spans)][G][D]   partial outputs (normalised); slot = item + span
     float *suf_lse;          // [(B*Hkv + spans)][G]      partial log2-sum-exp
     float *pfx_o;            // [(prefix_rows_max*Hkv + spans)][kPrefixRows][D]
@@ -39,7 +40,7 @@ struct Workspace {
 
 struct Launch {
     int32_t B, Hq, Hkv, D, G, num_pages, max_pages, num_groups;
-    int32_t kv_fp8, share, waves, members_per_row, stages, cost_prefix, static_pct, dyn_pages;
+    int32_t kv_fp8, share, waves, members_per_row, stages, cost_prefix, cost_item, static_pct, dyn_pages;
     int32_t xcd_w[8]; // relative speed of the eight accelerator dies, adding up to 8192
     const uint16_t *q;
     const uint8_t *k_pool, *v_pool;

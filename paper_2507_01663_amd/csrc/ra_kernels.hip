@@ -51,10 +51,11 @@ size_t carve_workspace(Workspace &ws, void *base, int B, int Hkv, int G, int D, 
     ws.merge_desc = (int4 *)take((size_t)B * Hkv * 32);
     ws.members = (int32_t *)take((size_t)B * 4);
     ws.row_start = (int32_t *)take(((size_t)2 * B + 1) * 4);
-    ws.row_info = (int4 *)take((size_t)2 * B * 16);
+    ws.prow_g = (int32_t *)take((size_t)B * 4);
     const size_t spans = (size_t)(1 + kDynSpansPerWave) * waves; // upper bound on spans of the cost stream
-    ws.span_first_row = (int32_t *)take((spans + 1) * 4);
-    ws.span_lo = (int32_t *)take((spans + 2) * 4);
+    // every (item, span) pair that shares pages is one segment: at most items + spans of them
+    const size_t chunks = spans + ((size_t)2 * B * Hkv + spans) / kChunkSegs + 2;
+    ws.seg_rec = (int4 *)take(chunks * 16 * sizeof(int4));
     size_t nsuf = (size_t)B * Hkv + spans;
     ws.suf_o = (float *)take(nsuf * G * D * 4);
     ws.suf_lse = (float *)take(nsuf * G * 4);
@@ -65,19 +66,26 @@ size_t carve_workspace(Workspace &ws, void *base, int B, int Hkv, int G, int D, 
 }
 
 // ------------------------------------------------------------------------------------------------------
-// schedule (one workgroup): work rows, their cost, the scan, and each wave's first row
+// schedule (one workgroup): work rows, their cost, the scan, and each span's work list
 //
 // Work rows: first the shared-prefix rows (one per group and block of kPrefixRows/G members), then one row
-// per sequence for its own pages.  A row of n pages costs weight*n per kv head, and the rows, each repeated
-// for every kv head, form one stream of cost units that is cut into equal spans, one per resident wave: the
-// ragged lengths (paper Sec. 7.4) never leave a compute unit idle.  A page belongs to the wave whose span
-// holds the page's first cost unit.  Prefix pages weigh more because a wave spends more time on them (more
-// query rows per byte); the weights only balance time, they never change results.
+// per sequence for its own pages.  A row of n pages costs a fixed amount plus weight*n per kv head, and the
+// rows, each repeated for every kv head, form one stream of cost units that is cut into spans, one per
+// resident wave: the ragged lengths (paper Sec. 7.4) never leave a compute unit idle.  A page belongs to the
+// wave whose span holds the page's first cost unit.  Prefix pages weigh more because a wave spends more time
+// on them (more query rows per byte); the weights only balance time, they never change results.
 // ------------------------------------------------------------------------------------------------------
+
+// Pages [p_lo, p_hi) of an item (first cost unit S, weight cw per page, n pages) that belong to the span
+// [lo, hi) of the cost stream: those whose first unit S + cw*p lies in the span.
+__device__ __forceinline__ void span_pages(int S, int cw, int n, int lo, int hi, int &p_lo, int &p_hi)
+{
+    p_lo = lo <= S ? 0 : min(n, (lo - S + cw - 1) / cw);
+    p_hi = hi <= S ? 0 : min(n, (hi - S + cw - 1) / cw);
+}
 
 constexpr int kPlanThreads = 1024;
 constexpr int kPlanCap = 2048; // sequences / groups whose intermediate arrays fit in LDS; beyond, the workspace is used
-constexpr int kSpanCap = 6144; // likewise for span boundaries
 
 // Exclusive scan of in[0..n) into out[0..n], out[n] = total (in == out is allowed).  All threads call it.
 __device__ void block_scan(const int32_t *in, int32_t *out, int n, int32_t *tmp /*[17], LDS*/)
@@ -115,35 +123,80 @@ __device__ void block_scan(const int32_t *in, int32_t *out, int n, int32_t *tmp 
     __syncthreads();
 }
 
+// Where the cost stream is cut.  The first `waves` spans are static, one per resident wave.  Workgroups are
+// dealt round-robin to the eight accelerator dies, which do not all get the same share of the memory
+// bandwidth, so within each block of eight consecutive static spans (8*S0 units) span x gets a share
+// proportional to the relative speed xcd_w[x] of its die (the weights add up to 8192).  The rest of the
+// stream, if any, is cut into spans of cd units that the waves take from a counter as they finish.
+struct Cuts {
+    long U, S0, cd;
+    int waves, nspans;
+    int acc[9]; // running sums of the die weights
+    __device__ long lo(int c) const
+    {
+        long v = c < waves ? (long)(c >> 3) * 8 * S0 + ((8 * S0 * acc[c & 7]) >> 13) : (long)waves * S0 + (long)(c - waves) * cd;
+        return v < U ? v : U;
+    }
+    __device__ int span_of(long pos) const // the span that holds cost unit pos < U
+    {
+        if (pos >= (long)waves * S0) return waves + (int)((pos - (long)waves * S0) / cd);
+        const long blk = pos / (8 * S0), rem = pos - blk * 8 * S0;
+        int x = 0;
+#pragma unroll
+        for (int i = 1; i < 8; i++)
+            if (((8 * S0 * acc[i]) >> 13) <= rem) x = i;
+        return (int)blk * 8 + x;
+    }
+};
+
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
 {
     __shared__ int32_t scan_tmp[17];
+    __shared__ int32_t l_len[kPlanCap], l_grp[kPlanCap], l_poff[kPlanCap + 1];
     __shared__ int32_t l_grp_count[kPlanCap], l_grp_rowbase[kPlanCap + 1], l_grp_membase[kPlanCap + 1];
-    __shared__ int32_t l_seq_rank[kPlanCap], l_row_start[2 * kPlanCap + 1], l_span_lo[kSpanCap + 1];
+    __shared__ int32_t l_seq_rank[kPlanCap], l_prow_g[kPlanCap], l_row_start[2 * kPlanCap + 1];
+    __shared__ int32_t l_overflow;
     const int tid = threadIdx.x;
     const Workspace &w = a.ws;
     const int B = a.B;
     const int NG = a.share ? a.num_groups : 0;
     const int MPR = a.members_per_row;
-    // intermediates live in LDS when they fit (the usual case), else in the workspace
+    // inputs and intermediates live in LDS when they fit (the usual case), else in the workspace
     const bool small = B <= kPlanCap && NG <= kPlanCap;
     int32_t *grp_count = small ? l_grp_count : w.grp_count;
     int32_t *grp_rowbase = small ? l_grp_rowbase : w.grp_rowbase;
     int32_t *grp_membase = small ? l_grp_membase : w.grp_membase;
     int32_t *seq_rank = small ? l_seq_rank : w.seq_rank;
+    int32_t *prow_g = small ? l_prow_g : w.prow_g;
     int32_t *row_start = small ? l_row_start : w.row_start;
-
+    const int32_t *len_src = a.seq_lens, *grp_src = a.seq_group, *poff = a.pfx_off;
+    // one trip to memory for everything the schedule depends on
+    if (small) {
+        for (int b = tid; b < B; b += kPlanThreads) {
+            l_len[b] = a.seq_lens[b];
+            l_grp[b] = NG ? a.seq_group[b] : -1;
+        }
+        for (int g = tid; g <= NG; g += kPlanThreads) l_poff[g] = NG ? a.pfx_off[g] : 0;
+        len_src = l_len, grp_src = l_grp, poff = l_poff;
+    }
     for (int g = tid; g < NG; g += kPlanThreads) grp_count[g] = 0;
+    if (tid == 0) l_overflow = 0;
     __syncthreads();
+    auto len_of = [&](int b) { // never walk past the table row
+        const int L = len_src[b];
+        return L < 0 ? 0 : (L > a.max_pages * kPage ? a.max_pages * kPage : L);
+    };
+    auto grp_of = [&](int b) {
+        const int g = NG ? grp_src[b] : -1;
+        return g >= 0 && g < NG ? g : -1;
+    };
     // membership: a sequence uses the shared pass when its group has shared pages and it holds all of them
     for (int b = tid; b < B; b += kPlanThreads) {
         int rank = -1;
-        if (NG) {
-            int g = a.seq_group[b];
-            if (g >= 0 && g < NG) {
-                int np = a.pfx_off[g + 1] - a.pfx_off[g];
-                if (np > 0 && a.seq_lens[b] >= np * kPage) rank = atomicAdd(&grp_count[g], 1);
-            }
+        const int g = grp_of(b);
+        if (g >= 0) {
+            const int np = poff[g + 1] - poff[g];
+            if (np > 0 && len_of(b) >= np * kPage) rank = atomicAdd(&grp_count[g], 1);
         }
         seq_rank[b] = rank;
     }
@@ -156,119 +209,152 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
         block_scan(grp_rowbase, grp_rowbase, NG, scan_tmp);
         nPR = grp_rowbase[NG];
     }
-    // rows and their cost (staged in row_start, scanned in place)
+    // Rows and their cost per kv head (staged in row_start, scanned in place): an item of n > 0 pages costs
+    // cost_item + weight*n.  The fixed part stands for what every segment costs a wave on top of its pages
+    // (query rows, a partial result, a pipeline that restarts).
     for (int g = tid; g < NG; g += kPlanThreads) {
-        int cnt = grp_count[g], np = a.pfx_off[g + 1] - a.pfx_off[g];
-        int r0 = grp_rowbase[g], m0 = grp_membase[g];
+        const int cnt = grp_count[g], np = poff[g + 1] - poff[g];
+        const int r0 = grp_rowbase[g];
         for (int k = 0; k * MPR < cnt; k++) {
-            int left = cnt - k * MPR;
-            row_start[r0 + k] = np * a.cost_prefix;
-            w.row_info[r0 + k] = make_int4(g, m0 + k * MPR, left < MPR ? left : MPR, np);
+            row_start[r0 + k] = a.cost_item + np * a.cost_prefix;
+            prow_g[r0 + k] = g;
         }
     }
     for (int b = tid; b < B; b += kPlanThreads) {
-        int L = a.seq_lens[b];
-        if (L > a.max_pages * kPage) L = a.max_pages * kPage; // never walk past the table row
-        int rank = seq_rank[b];
+        const int L = len_of(b);
+        const int rank = seq_rank[b];
         int skip = 0, prow = -1;
         if (rank >= 0) {
-            int g = a.seq_group[b];
-            skip = a.pfx_off[g + 1] - a.pfx_off[g];
+            const int g = grp_of(b);
+            skip = poff[g + 1] - poff[g];
             prow = grp_rowbase[g] + rank / MPR;
             w.members[grp_membase[g] + rank] = b;
         }
         w.seq_pfx_row[b] = prow;
         w.seq_rank_in_row[b] = rank >= 0 ? rank % MPR : -1;
-        int pages = L > 0 ? (L + kPage - 1) / kPage - skip : 0;
-        row_start[nPR + b] = pages * kCostSuffix;
-        w.row_info[nPR + b] = make_int4(b, skip, L - skip * kPage, pages);
+        const int pages = L > 0 ? (L + kPage - 1) / kPage - skip : 0;
+        row_start[nPR + b] = pages > 0 ? a.cost_item + pages * kCostSuffix : 0;
     }
     __syncthreads();
     const int nR = B + nPR;
     block_scan(row_start, row_start, nR, scan_tmp);
-    // Spans of the cost stream.  The first `waves` spans are static, one per resident wave.  Workgroups are dealt
-    // round-robin to the eight accelerator dies, which do not all get the same share of the memory bandwidth,
-    // so within each block of eight consecutive static spans (8*S0 units) span x gets a share proportional to
-    // the relative speed xcd_w[x] of its die (the weights add up to 8192).  The rest of the stream, if any, is
-    // cut into smaller spans that the waves take from a counter as they finish.  All later kernels read the
-    // span boundaries from span_lo[], so any other cut could be written here.
-    const long U = (long)a.Hkv * row_start[nR];
-    const long min_span = (long)kMinUnitsPerWave * kCostSuffix;
-    long S0 = U * a.static_pct / 100 / a.waves;
-    if (S0 < min_span) S0 = min_span;
-    long cd = (long)a.dyn_pages * kCostSuffix;
+
+    Cuts cut;
+    cut.U = (long)a.Hkv * row_start[nR];
+    cut.waves = a.waves;
+    // no span is shorter than a few pages, and none is shorter than one page of either kind, so that every
+    // span between the first and the last one of an item holds at least one of its pages
+    long min_span = (long)kMinUnitsPerWave * kCostSuffix;
+    if (min_span < 4 * a.cost_prefix) min_span = 4 * a.cost_prefix; // (a die's share is at least half the mean)
+    cut.S0 = a.static_pct >= 100 ? (cut.U + a.waves - 1) / a.waves : cut.U * a.static_pct / 100 / a.waves;
+    if (cut.S0 < min_span) cut.S0 = min_span;
+    cut.cd = (long)a.dyn_pages * kCostSuffix;
+    if (cut.cd < min_span) cut.cd = min_span;
     long ndyn = 0;
-    const long Ud = U - S0 * a.waves;
+    const long Ud = cut.U - cut.S0 * a.waves;
     if (Ud > 0) {
         const long most = (long)kDynSpansPerWave * a.waves;
-        if ((Ud + cd - 1) / cd > most) cd = (Ud + most - 1) / most;
-        ndyn = (Ud + cd - 1) / cd;
+        if ((Ud + cut.cd - 1) / cut.cd > most) cut.cd = (Ud + most - 1) / most;
+        ndyn = (Ud + cut.cd - 1) / cut.cd;
     }
-    const int nspans = a.waves + (int)ndyn;
+    cut.nspans = a.waves + (int)ndyn;
+    cut.acc[0] = 0;
+#pragma unroll
+    for (int x = 0; x < 8; x++) cut.acc[x + 1] = cut.acc[x] + a.xcd_w[x];
+    const int nspans = cut.nspans;
     if (tid == 0) {
-        w.hdr[0] = (int)U;
+        w.hdr[0] = (int)cut.U;
         w.hdr[2] = nR;
         w.hdr[3] = nPR;
         w.hdr[5] = a.waves; // next span to hand out
         w.hdr[7] = nspans;
     }
-    if (small)
-        for (int r = tid; r <= nR; r += kPlanThreads) w.row_start[r] = row_start[r];
-    const bool few = nspans < kSpanCap;
-    int32_t *span_lo = few ? l_span_lo : w.span_lo;
-    for (int c = tid; c <= nspans; c += kPlanThreads) {
-        long lo;
-        if (c < a.waves) {
-            int acc = 0;
-            for (int x = 0; x < (c & 7); x++) acc += a.xcd_w[x];
-            lo = (long)(c >> 3) * 8 * S0 + ((8 * S0 * acc) >> 13);
-        } else {
-            lo = (long)a.waves * S0 + (long)(c - a.waves) * cd;
+    // what a row is: {group, first member slot, members, pages} or {sequence, pages skipped, tokens after, pages}
+    auto row_info = [&](int r) {
+        if (r < nPR) {
+            const int g = prow_g[r], k = r - grp_rowbase[g], left = grp_count[g] - k * MPR;
+            return make_int4(g, grp_membase[g] + k * MPR, left < MPR ? left : MPR, poff[g + 1] - poff[g]);
         }
-        span_lo[c] = (int)lo;
-        if (few) w.span_lo[c] = (int)lo;
-        // first row of the span: the last row that starts at or before the span's first unit
-        int rlo = 0, rhi = nR; // invariant: Hkv*row_start[rlo] <= lo < Hkv*row_start[rhi]
-        if (lo >= U) rlo = nR;
-        else
-            while (rhi - rlo > 1) {
-                int mid = (rlo + rhi) >> 1;
-                if ((long)a.Hkv * row_start[mid] <= lo) rlo = mid;
+        const int b = r - nPR, L = len_of(b);
+        int skip = 0;
+        if (seq_rank[b] >= 0) {
+            const int g = grp_of(b);
+            skip = poff[g + 1] - poff[g];
+        }
+        return make_int4(b, skip, L - skip * kPage, L > 0 ? (L + kPage - 1) / kPage - skip : 0);
+    };
+
+    // The work list of every span: one record per segment (the pages of one (row, kv head) item that lie in
+    // the span), so that the attention waves find their work with one load instead of walking these tables.
+    // A record is {index of the row's first page id in its table, first page, end page, token limit,
+    // kv head | prefix << 16, sequence (own pages) or first member slot (shared pages), query rows, partial slot}.
+    for (int c = tid; c < nspans; c += kPlanThreads) {
+        const int lo = (int)cut.lo(c), hi = (int)cut.lo(c + 1);
+        int chunk = c, n = 0;
+        if (lo < hi) {
+            // first row of the span: the last row that starts at or before the span's first unit
+            int r = 0, rhi = nR; // invariant: Hkv*row_start[r] <= lo < Hkv*row_start[rhi]
+            while (rhi - r > 1) {
+                const int mid = (r + rhi) >> 1;
+                if ((long)a.Hkv * row_start[mid] <= lo) r = mid;
                 else rhi = mid;
             }
-        w.span_first_row[c] = rlo;
-    }
-    __syncthreads();
-    // For the merge: the spans that hold pages of each (sequence, kv head)'s own row and of its prefix row.
-    auto span_of = [&](int pos) { // last span that starts at or before pos
-        int lo = 0, hi = nspans;
-        while (hi - lo > 1) {
-            int mid = (lo + hi) >> 1;
-            if (span_lo[mid] <= pos) lo = mid;
-            else hi = mid;
+            for (; r < nR; r++) {
+                const int rs = a.Hkv * row_start[r];
+                if (rs >= hi) break;
+                const int ic = row_start[r + 1] - row_start[r]; // cost of one item of the row
+                if (ic == 0) continue;
+                const int4 info = row_info(r);
+                const bool prefix = r < nPR;
+                const int cw = prefix ? a.cost_prefix : kCostSuffix;
+                for (int kvh = lo > rs ? (lo - rs) / ic : 0; kvh < a.Hkv; kvh++) {
+                    const int S = rs + kvh * ic;
+                    if (S >= hi) break;
+                    int p_lo, p_hi;
+                    span_pages(S + a.cost_item, cw, info.w, lo, hi, p_lo, p_hi);
+                    if (p_lo >= p_hi) continue;
+                    if (n == kChunkSegs) { // chain another chunk
+                        const int nc = nspans + atomicAdd(&l_overflow, 1);
+                        w.seg_rec[(size_t)chunk * 16] = make_int4(n, nc, 0, 0);
+                        chunk = nc;
+                        n = 0;
+                    }
+                    int4 *rec = w.seg_rec + (size_t)chunk * 16 + 2 * (1 + n);
+                    if (!prefix) {
+                        rec[0] = make_int4(info.x * a.max_pages + info.y, p_lo, p_hi, min(info.z, p_hi * kPage));
+                        rec[1] = make_int4(kvh, info.x, a.G, info.x * a.Hkv + kvh + c);
+                    } else {
+                        rec[0] = make_int4(poff[info.x], p_lo, p_hi, p_hi * kPage);
+                        rec[1] = make_int4(kvh | (1 << 16), info.y, info.z * a.G, r * a.Hkv + kvh + c);
+                    }
+                    n++;
+                }
+            }
         }
-        return lo;
-    };
+        w.seg_rec[(size_t)chunk * 16] = make_int4(n, -1, 0, 0);
+    }
+    // For the merge: the spans that hold pages of each (sequence, kv head)'s own row and of its prefix row,
+    // {pages, first span, last span, unused}.  Every span in that range holds at least one of the pages.
     for (int i = tid; i < B * a.Hkv; i += kPlanThreads) {
         const int b = i / a.Hkv, kvh = i - b * a.Hkv;
-        int4 own, pfx = make_int4(0, 0, 0, -1);
+        int4 own = make_int4(0, 0, -1, 0), pfx = make_int4(0, 0, -1, 0);
         {
             const int r = nPR + b;
-            const int n = (row_start[r + 1] - row_start[r]) / kCostSuffix;
-            const int S = a.Hkv * row_start[r] + kvh * kCostSuffix * n;
-            own = make_int4(S, n, 0, -1);
-            if (n > 0) {
-                own.z = span_of(S);
-                own.w = span_of(S + kCostSuffix * (n - 1));
+            const int ic = row_start[r + 1] - row_start[r];
+            if (ic > 0) {
+                const int n = (ic - a.cost_item) / kCostSuffix;
+                const long S = (long)a.Hkv * row_start[r] + (long)kvh * ic + a.cost_item;
+                own = make_int4(n, cut.span_of(S), cut.span_of(S + kCostSuffix * (n - 1)), 0);
             }
         }
         const int rank = seq_rank[b];
         if (rank >= 0) {
-            const int g = a.seq_group[b];
+            const int g = grp_of(b);
             const int r = grp_rowbase[g] + rank / MPR;
-            const int n = (row_start[r + 1] - row_start[r]) / a.cost_prefix;
-            const int S = a.Hkv * row_start[r] + kvh * a.cost_prefix * n;
-            pfx = make_int4(S, n, span_of(S), span_of(S + a.cost_prefix * (n - 1)));
+            const int ic = row_start[r + 1] - row_start[r];
+            const int n = (ic - a.cost_item) / a.cost_prefix;
+            const long S = (long)a.Hkv * row_start[r] + (long)kvh * ic + a.cost_item;
+            pfx = make_int4(n, cut.span_of(S), cut.span_of(S + a.cost_prefix * (n - 1)), 0);
         }
         w.merge_desc[2 * i] = own;
         w.merge_desc[2 * i + 1] = pfx;
@@ -279,14 +365,6 @@ hipError_t launch_plan(const Launch &a, hipStream_t s)
 {
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, s, a);
     return hipGetLastError();
-}
-
-// Pages [p_lo, p_hi) of an item (first cost unit S, weight cw per page, n pages) that belong to the span
-// [lo, hi) of the cost stream: those whose first unit S + cw*p lies in the span.
-__device__ __forceinline__ void span_pages(int S, int cw, int n, int lo, int hi, int &p_lo, int &p_hi)
-{
-    p_lo = lo <= S ? 0 : min(n, (lo - S + cw - 1) / cw);
-    p_hi = hi <= S ? 0 : min(n, (hi - S + cw - 1) / cw);
 }
 
 // ------------------------------------------------------------------------------------------------------
@@ -794,18 +872,17 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
 // The read-only inputs and the schedule come in as separate restrict pointers so that the compiler can keep
 // every wave-uniform lookup on the scalar unit, away from the vector-memory counter that paces the LDS ring.
 #define RA_ATTN_PARAMS                                                                                                    \
-    Launch a, const uint16_t *__restrict__ q, const int32_t *__restrict__ block_table, const int32_t *__restrict__ pfx_off, \
-        const int32_t *__restrict__ pfx_pages, const int32_t *__restrict__ hdr, const int32_t *__restrict__ row_start,     \
-        const int4 *__restrict__ row_info, const int32_t *__restrict__ span_first_row, const int32_t *__restrict__ members,  \
-        const int32_t *__restrict__ span_lo
-#define RA_ATTN_ARGS a, q, block_table, pfx_off, pfx_pages, hdr, row_start, row_info, span_first_row, members, span_lo
+    Launch a, const uint16_t *__restrict__ q, const int32_t *__restrict__ block_table, const int32_t *__restrict__ pfx_pages, \
+        const int32_t *__restrict__ hdr, const uint32_t *__restrict__ seg_rec, const int32_t *__restrict__ members
+#define RA_ATTN_ARGS a, q, block_table, pfx_pages, hdr, seg_rec, members
 
 template <int D, int KVB, int NST> __device__ __forceinline__ void attention_body(RA_ATTN_PARAMS, int32_t *next_span)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     const uint32_t lds_addr = (uint32_t)(uintptr_t)lds;
     const int lane = threadIdx.x;
-    const int U = uniform_load(hdr, 0), nR = uniform_load(hdr, 2), nPR = uniform_load(hdr, 3), nspans = uniform_load(hdr, 7);
+    const int nspans = uniform_load(hdr, 7);
+    if ((int)blockIdx.x >= nspans) return;
 
     LaneConst<D, KVB> lc;
     lane_setup<D, KVB>(lc, lane, a.stride_token_b);
@@ -814,83 +891,58 @@ template <int D, int KVB, int NST> __device__ __forceinline__ void attention_bod
     int npend = 0;
 
     // ---- walker: yields this wave's segments in stream order, span after span ----
-    int wk_span = blockIdx.x, wk_lo = 0, wk_hi = 0, wk_r = 0, wk_kvh = -1, wk_rs = 0, wk_units = 0, wk_cw = 1;
-    int wk_x = 0, wk_y = 0, wk_z = 0; // row_info of the current row
-    int wk_next = 0;                  // lane 0: the span taken from the counter
+    // A span's work list is a chain of chunks of eight 8-dword records (a header and up to seven segments).
+    // A chunk is one dword per lane, so it is held in one register and a field is a cross-lane read.
+    uint32_t chunk = 0;
+    int wk_j = 0, wk_n = 0, wk_chain = -1;
+    int wk_next = 0; // lane 0: the span taken from the counter
     bool wk_done = false;
     const bool dynamic = nspans > a.waves;
+    auto field = [&](int i) { return (int)__builtin_amdgcn_readlane(chunk, i); };
+    auto load_chunk = [&](int c) {
+        chunk = seg_rec[(int64_t)c * 64 + lane];
+        wk_j = 0;
+        wk_n = field(0);
+        wk_chain = field(1);
+    };
     auto enter_span = [&](int c) {
-        wk_span = c;
-        wk_lo = uniform_load(span_lo, c);
-        wk_hi = min(U, uniform_load(span_lo, c + 1));
-        wk_r = uniform_load(span_first_row, c);
-        wk_kvh = -1;
+        load_chunk(c);
         // take the span after this one now; the answer is needed only when this one is exhausted
         if (dynamic && lane == 0) wk_next = atomicAdd(next_span, 1);
     };
     auto advance = [&](Segment &out) -> bool {
         for (;;) {
             if (wk_done) return false;
-            if (wk_kvh < 0) { // need a row
-                bool exhausted = wk_r >= nR;
-                if (!exhausted) {
-                    wk_rs = a.Hkv * uniform_load(row_start, wk_r);
-                    exhausted = wk_rs >= wk_hi;
-                }
-                if (exhausted) {
-                    const int nx = dynamic ? __builtin_amdgcn_readfirstlane(wk_next) : nspans;
-                    if (nx >= nspans) {
-                        wk_done = true;
-                        return false;
-                    }
-                    enter_span(nx);
+            if (wk_j == wk_n) {
+                if (wk_chain >= 0) {
+                    load_chunk(wk_chain);
                     continue;
                 }
-                const int32_t *ri = (const int32_t *)(row_info + wk_r);
-                wk_units = uniform_load(ri, 3);
-                if (wk_units == 0) {
-                    wk_r++;
-                    continue;
+                const int nx = dynamic ? __builtin_amdgcn_readfirstlane(wk_next) : nspans;
+                if (nx >= nspans) {
+                    wk_done = true;
+                    return false;
                 }
-                wk_x = uniform_load(ri, 0), wk_y = uniform_load(ri, 1), wk_z = uniform_load(ri, 2);
-                wk_cw = wk_r < nPR ? a.cost_prefix : kCostSuffix;
-                const int ic = wk_cw * wk_units;
-                wk_kvh = wk_lo > wk_rs ? (wk_lo - wk_rs) / ic : 0;
-            }
-            const int S = wk_rs + wk_kvh * wk_cw * wk_units;
-            if (wk_kvh >= a.Hkv || S >= wk_hi) {
-                wk_r++;
-                wk_kvh = -1;
+                enter_span(nx);
                 continue;
             }
-            const int kvh = wk_kvh++;
-            span_pages(S, wk_cw, wk_units, wk_lo, wk_hi, out.pg_lo, out.pg_hi);
-            if (out.pg_lo >= out.pg_hi) continue;
-            out.kvh = kvh;
-            out.prefix = wk_r < nPR;
-            if (!out.prefix) {
-                // a sequence's own pages: the G query heads of this kv head form one 16-row tile
-                out.b = wk_x;
-                out.pages = block_table + (int64_t)wk_x * a.max_pages + wk_y;
-                out.limit = min(wk_z, out.pg_hi * kPage);
-                out.slot = (int64_t)wk_x * a.Hkv + kvh + wk_span;
-                out.moff = 0;
-                out.nrows = a.G;
-            } else {
-                // shared prompt pages of a group: rows = members x G, packed densely into 16-row tiles
-                out.b = 0;
-                out.pages = pfx_pages + uniform_load(pfx_off, wk_x);
-                out.limit = out.pg_hi * kPage;
-                out.slot = (int64_t)wk_r * a.Hkv + kvh + wk_span;
-                out.moff = wk_y;
-                out.nrows = wk_z * a.G;
-            }
+            const int f = 8 * (1 + wk_j++);
+            const int where = field(f + 4);
+            out.kvh = where & 0xffff;
+            out.prefix = where >> 16;
+            out.pages = (out.prefix ? pfx_pages : block_table) + field(f);
+            out.pg_lo = field(f + 1);
+            out.pg_hi = field(f + 2);
+            out.limit = field(f + 3);
+            out.b = out.prefix ? 0 : field(f + 5);
+            out.moff = out.prefix ? field(f + 5) : 0;
+            out.nrows = field(f + 6);
+            out.slot = field(f + 7);
             return true;
         }
     };
 
-    if (wk_span >= nspans || uniform_load(span_lo, wk_span) >= U) return;
-    enter_span(wk_span);
+    enter_span(blockIdx.x);
     Segment cur, nxt;
     bool has_cur = advance(cur);
     if (has_cur) {
@@ -994,8 +1046,8 @@ hipError_t launch_attention(const Launch &a, hipStream_t s)
     size_t lds = attention_lds_bytes(a.D, a.kv_fp8, a.stages);
     const Workspace &w = a.ws;
 #define RA_LAUNCH(K)                                                                                                      \
-    hipLaunchKernelGGL(K, dim3(a.waves), dim3(64), lds, s, a, a.q, a.block_table, a.pfx_off, a.pfx_pages, w.hdr, w.row_start, \
-                       w.row_info, w.span_first_row, w.members, w.span_lo, w.hdr + 5)
+    hipLaunchKernelGGL(K, dim3(a.waves), dim3(64), lds, s, a, a.q, a.block_table, a.pfx_pages, w.hdr,                       \
+                       (const uint32_t *)w.seg_rec, w.members, w.hdr + 5)
     if (a.kv_fp8 && a.stages == 2) {
         if (a.D == 128) RA_LAUNCH(attention_kernel_fp8_s2<128>);
         else RA_LAUNCH(attention_kernel_fp8_s2<64>);
@@ -1023,19 +1075,18 @@ hipError_t launch_attention(const Launch &a, hipStream_t s)
 constexpr int kMergeThreads = 256;
 
 struct PartList {
-    const float *o, *lse;   // slot 0 of the item (span offset not yet added)
+    int c_lo, c_hi;   // spans that hold pages of the item (c_lo > c_hi: none)
+    const float *o;   // partial outputs of span 0 (slot = item + span)
+    const float *lse;
     int64_t ostride, lstride;
-    int S, cw, n, c_lo, c_hi;
 };
 
 __global__ __launch_bounds__(kMergeThreads) void merge_kernel(Launch a, const int4 *__restrict__ merge_desc,
-                                                               const int32_t *__restrict__ span_lo,
                                                                const int32_t *__restrict__ seq_pfx_row,
                                                                const int32_t *__restrict__ seq_rank_in_row)
 {
     const Workspace &w = a.ws;
-    const int item = blockIdx.x;
-    const int b = item / a.Hkv, kvh = item - b * a.Hkv;
+    const int item = blockIdx.x, b = item / a.Hkv, kvh = item - b * a.Hkv;
     const int D = a.D, tpr = D / 4; // threads per output row
     const int4 own = merge_desc[2 * item], pfx = merge_desc[2 * item + 1];
     const int prow = seq_pfx_row[b];
@@ -1043,8 +1094,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(Launch a, const in
     PartList pl[2];
     {
         PartList &p = pl[1];
-        p.S = own.x, p.n = own.y, p.c_lo = own.z, p.c_hi = own.w;
-        p.cw = kCostSuffix;
+        p.c_lo = own.y, p.c_hi = own.z;
         p.o = w.suf_o + (int64_t)item * a.G * D;
         p.lse = w.suf_lse + (int64_t)item * a.G;
         p.ostride = (int64_t)a.G * D;
@@ -1052,8 +1102,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(Launch a, const in
     }
     {
         PartList &p = pl[0];
-        p.S = pfx.x, p.n = pfx.y, p.c_lo = pfx.z, p.c_hi = pfx.w;
-        p.cw = a.cost_prefix;
+        p.c_lo = pfx.y, p.c_hi = pfx.z;
         const int64_t pitem = (int64_t)(prow < 0 ? 0 : prow) * a.Hkv + kvh;
         p.o = w.pfx_o + (pitem * kPrefixRows + row0) * D;
         p.lse = w.pfx_lse + pitem * kPrefixRows + row0;
@@ -1064,18 +1113,11 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(Launch a, const in
         const int d4 = (threadIdx.x % tpr) * 4;
         float M = -INFINITY;
         for (int k = 0; k < 2; k++)
-            for (int c = pl[k].c_lo; c <= pl[k].c_hi; c++) {
-                int p_lo, p_hi;
-                span_pages(pl[k].S, pl[k].cw, pl[k].n, span_lo[c], span_lo[c + 1], p_lo, p_hi);
-                if (p_lo < p_hi) M = fmaxf(M, pl[k].lse[c * pl[k].lstride + hl]);
-            }
+            for (int c = pl[k].c_lo; c <= pl[k].c_hi; c++) M = fmaxf(M, pl[k].lse[c * pl[k].lstride + hl]);
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         float wsum = 0.f;
         for (int k = 0; k < 2; k++)
             for (int c = pl[k].c_lo; c <= pl[k].c_hi; c++) {
-                int p_lo, p_hi;
-                span_pages(pl[k].S, pl[k].cw, pl[k].n, span_lo[c], span_lo[c + 1], p_lo, p_hi);
-                if (p_lo >= p_hi) continue;
                 const float wgt = __builtin_amdgcn_exp2f(pl[k].lse[c * pl[k].lstride + hl] - M);
                 wsum += wgt;
                 acc += wgt * *(const f32x4 *)(pl[k].o + c * pl[k].ostride + (int64_t)hl * D + d4);
@@ -1093,7 +1135,7 @@ hipError_t launch_merge(const Launch &a, hipStream_t s)
 {
     if (a.B == 0) return hipSuccess;
     const Workspace &w = a.ws;
-    hipLaunchKernelGGL(merge_kernel, dim3(a.B * a.Hkv), dim3(kMergeThreads), 0, s, a, w.merge_desc, w.span_lo, w.seq_pfx_row,
+    hipLaunchKernelGGL(merge_kernel, dim3(a.B * a.Hkv), dim3(kMergeThreads), 0, s, a, w.merge_desc, w.seq_pfx_row,
                        w.seq_rank_in_row);
     return hipGetLastError();
 }
