@@ -108,8 +108,11 @@ typedef struct {
 /* ROLLOUT_ATTN_ABI_VERSION of the library that was loaded. */
 uint32_t rollout_attn_abi_version(void);
 
-/* Creates a context on the given HIP device (allocates a few hundred bytes of device memory and queries
- * the device).  *ctx is NULL on failure.  RA_ERR_DEVICE when the device cannot be used. */
+/* Creates a context on the given HIP device: queries the device, allocates a few hundred bytes of device
+ * memory that the context keeps, and measures for about a millisecond how the memory bandwidth is shared
+ * among the device's dies (the attention kernel balances its work by that; the measurement borrows 256 MiB
+ * of device memory and returns it before the call ends, and is skipped when that much is not free).
+ * *ctx is NULL on failure.  RA_ERR_DEVICE when the device cannot be used. */
 ra_status rollout_attn_create(ra_ctx **ctx, int device_ordinal);
 
 /* Frees the context's device memory.  NULL is accepted.  Work already enqueued must have finished. */

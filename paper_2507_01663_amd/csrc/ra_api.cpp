@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <vector>
 
 struct ra_ctx {
     int device;
@@ -66,7 +67,10 @@ ra_status check(const ra_problem *p, char *msg, size_t n)
     if (p->page_size != 16) return fail(RA_ERR_UNSUPPORTED, "page_size=%d (only 16 is supported)", p->page_size);
     if (p->D != 64 && p->D != 128) return fail(RA_ERR_UNSUPPORTED, "D=%d (only 64 and 128 are supported)", p->D);
     if (p->Hq / p->Hkv > 16) return fail(RA_ERR_UNSUPPORTED, "Hq/Hkv=%d (at most 16 is supported)", p->Hq / p->Hkv);
-    if ((int64_t)p->B * p->Hq > (int64_t)1 << 30 || (int64_t)p->B * p->max_pages_per_seq > (int64_t)1 << 40)
+    // 32-bit indices into the block table, and a schedule whose cost stream (at most 16 units per page and kv head,
+    // 256 per sequence and kv head, twice) stays below 2^31 units
+    if ((int64_t)p->B * p->Hq > (int64_t)1 << 30 || (int64_t)p->B * p->max_pages_per_seq >= (int64_t)1 << 31 ||
+        (int64_t)p->Hkv * p->B * (512 + 16 * (int64_t)p->max_pages_per_seq) >= (int64_t)1 << 31)
         return fail(RA_ERR_UNSUPPORTED, "batch too large");
     if (p->B == 0) return RA_OK;
     if (!p->q || !p->k_pool || !p->v_pool || !p->block_table || !p->seq_lens || !p->out || !p->lse)
@@ -131,6 +135,43 @@ extern "C" {
 
 uint32_t rollout_attn_abi_version(void) { return ROLLOUT_ATTN_ABI_VERSION; }
 
+// Measures the dies' relative streaming speed (see calibrate_kernel) and turns it into span weights, per mille
+// of the mean.  Needs a quarter of a gigabyte of device memory for a moment; on any failure, or when the
+// workgroups are not dealt to the dies round-robin as the schedule assumes, the weights are left alone.
+static void calibrate_dies(ra_ctx *c, int waves)
+{
+    if (waves <= 0 || waves % 8) return;
+    const int stages = 16;
+    int nblocks = 1;
+    while (nblocks < waves * stages) nblocks <<= 1;
+    void *buf = nullptr;
+    long long *dev = nullptr;
+    std::vector<long long> host((size_t)2 * waves);
+    double dur[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    bool ok = hipMalloc(&buf, (size_t)nblocks * 16384) == hipSuccess && hipMalloc((void **)&dev, host.size() * 8) == hipSuccess;
+    ok = ok && hipMemset(buf, 0, (size_t)nblocks * 16384) == hipSuccess;
+    for (int rep = 0; rep < 4 && ok; rep++) { // the first run warms up
+        ok = ra::launch_calibrate(buf, nblocks, stages, waves, dev, nullptr) == hipSuccess &&
+             hipMemcpy(host.data(), dev, host.size() * 8, hipMemcpyDeviceToHost) == hipSuccess;
+        for (int w = 0; w < waves && ok; w++) {
+            ok = host[2 * w + 1] == w % 8 && host[2 * w] > 0;
+            if (rep > 0) dur[w % 8] += (double)host[2 * w];
+        }
+    }
+    if (buf) (void)hipFree(buf);
+    if (dev) (void)hipFree(dev);
+    if (!ok) {
+        (void)hipGetLastError();
+        return;
+    }
+    double mean_speed = 0;
+    for (int x = 0; x < 8; x++) mean_speed += 1.0 / dur[x] / 8;
+    for (int x = 0; x < 8; x++) {
+        int w = (int)(1024.0 / dur[x] / mean_speed + 0.5);
+        c->xcd_w[x] = w < 800 ? 800 : (w > 1250 ? 1250 : w);
+    }
+}
+
 ra_status rollout_attn_create(ra_ctx **out, int device)
 {
     if (!out) { set_err(nullptr, "ctx is NULL"); return RA_ERR_INVALID_ARG; }
@@ -147,17 +188,21 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
     c->cost_item = ra::kCostItem;
     c->static_pct = 100;
     c->dyn_pages = 16;
-    // Share of the memory bandwidth each accelerator die gets when all eight stream at once, measured on
-    // MI355X with the attention kernel (per mille of the mean; the pattern follows the dies' place on the package).
+    // Share of the memory bandwidth each accelerator die gets when all eight stream at once (per mille of the
+    // mean).  This is what a typical MI355X shows; the context measures its own device below.
     static const int kXcdSpeed[8] = {1024, 944, 1089, 978, 1064, 973, 1013, 936};
     for (int x = 0; x < 8; x++) c->xcd_w[x] = kXcdSpeed[x];
+    bool calibrate = true;
+    if (const char *ev = getenv("ROLLOUT_ATTN_CALIBRATE")) calibrate = atoi(ev) != 0;
     if (const char *ev = getenv("ROLLOUT_ATTN_XCD_WEIGHTS")) {
         int v[8];
         if (sscanf(ev, "%d,%d,%d,%d,%d,%d,%d,%d", &v[0], &v[1], &v[2], &v[3], &v[4], &v[5], &v[6], &v[7]) == 8) {
             bool ok = true;
             for (int x = 0; x < 8; x++) ok = ok && v[x] >= 700 && v[x] <= 1400; // no span under half the mean
-            if (ok)
+            if (ok) {
                 for (int x = 0; x < 8; x++) c->xcd_w[x] = v[x];
+                calibrate = false;
+            }
         }
     }
     if (const char *ev = getenv("ROLLOUT_ATTN_STATIC_PCT")) {
@@ -170,7 +215,7 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
     }
     if (const char *ev = getenv("ROLLOUT_ATTN_COST_PREFIX")) {
         int v = atoi(ev);
-        if (v >= 1 && v <= 64) c->cost_prefix = v;
+        if (v >= 1 && v <= 16) c->cost_prefix = v;
     }
     if (const char *ev = getenv("ROLLOUT_ATTN_COST_ITEM")) {
         int v = atoi(ev);
@@ -190,6 +235,10 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
     for (int f = 0; f < 2; f++)
         for (int d = 0; d < 2; d++)
             if (e == hipSuccess) e = ra::attention_config(d ? 128 : 64, f, c->num_cus, &c->stages[f][d], &c->waves[f][d]);
+    if (e == hipSuccess && calibrate) calibrate_dies(c, c->waves[0][1]);
+    if (getenv("ROLLOUT_ATTN_VERBOSE"))
+        fprintf(stderr, "rollout_attn: die weights %d %d %d %d %d %d %d %d\n", c->xcd_w[0], c->xcd_w[1], c->xcd_w[2], c->xcd_w[3],
+                c->xcd_w[4], c->xcd_w[5], c->xcd_w[6], c->xcd_w[7]);
     (void)hipSetDevice(prev);
     if (e != hipSuccess) {
         set_err(nullptr, "context set-up on device %d: %s", device, hipGetErrorString(e));

@@ -14,7 +14,7 @@ constexpr int kDynSpansPerWave = 4; // at most this many dynamically scheduled s
 constexpr int kCostSuffix = 4;      // scheduling weight of a page of a sequence's own KV
 constexpr int kChunkSegs = 7;       // segment records per chunk of a span's work list (plus one header record)
 constexpr int kCostPrefix = 5;      // ... of a shared-prefix page (more query rows per byte, so more time per page)
-constexpr int kCostItem = 5;        // ... of a segment, on top of its pages
+constexpr int kCostItem = 16;       // ... of a segment, on top of its pages
 
 // Device pointers into the caller's workspace.  All offsets are fixed by the shape alone.
 struct Workspace {
@@ -64,6 +64,9 @@ size_t carve_workspace(Workspace &ws, void *base, int B, int Hkv, int G, int D, 
 // on the current device, for head dim D.
 hipError_t attention_config(int D, int kv_fp8, int num_cus, int *stages, int *waves);
 
+// Streams nblocks * 16 KB of buf (nblocks a power of two, = waves * stages) through the attention kernel's ring
+// and writes {duration in 10 ns ticks, die} per wave to out[2 * waves].
+hipError_t launch_calibrate(const void *buf, int nblocks, int stages, int waves, long long *out, hipStream_t s);
 hipError_t launch_validate(const Launch &a, hipStream_t s);
 hipError_t launch_plan(const Launch &a, hipStream_t s);
 hipError_t launch_attention(const Launch &a, hipStream_t s);

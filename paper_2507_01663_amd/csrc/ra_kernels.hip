@@ -18,6 +18,19 @@ typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
+// Kernel arguments live in memory that takes a microsecond or two to reach the first time, and the compiler
+// fetches a field where it is first used, often in the middle of the work.  Touching every cache line of them
+// up front makes those trips overlap; later reads hit the scalar cache.
+__device__ __forceinline__ void touch_args(const Launch &a)
+{
+    const int32_t *p = reinterpret_cast<const int32_t *>(&a);
+    int32_t s = 0;
+#pragma unroll
+    for (unsigned i = 0; i < sizeof(Launch) / 4; i += 16) s |= p[i];
+    s |= p[sizeof(Launch) / 4 - 1];
+    asm volatile("" ::"s"(s));
+}
+
 // ------------------------------------------------------------------------------------------------------
 // workspace
 // ------------------------------------------------------------------------------------------------------
@@ -87,39 +100,46 @@ __device__ __forceinline__ void span_pages(int S, int cw, int n, int lo, int hi,
 constexpr int kPlanThreads = 1024;
 constexpr int kPlanCap = 2048; // sequences / groups whose intermediate arrays fit in LDS; beyond, the workspace is used
 
-// Exclusive scan of in[0..n) into out[0..n], out[n] = total (in == out is allowed).  All threads call it.
-__device__ void block_scan(const int32_t *in, int32_t *out, int n, int32_t *tmp /*[17], LDS*/)
+// Exclusive scans of a[0..n) and b[0..n) in place, a[n] and b[n] = totals (b may be null).  All threads call it.
+__device__ void block_scan(int32_t *a, int32_t *b, int n, int32_t *tmp /*[34], LDS*/)
 {
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    int carry = 0;
+    int carry_a = 0, carry_b = 0;
     for (int base = 0; base < n; base += kPlanThreads) {
-        int i = base + tid;
-        int v = i < n ? in[i] : 0;
-        int x = v;
+        const int i = base + tid;
+        const int va = i < n ? a[i] : 0, vb = b && i < n ? b[i] : 0;
+        int xa = va, xb = vb;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
-            int y = __shfl_up(x, d);
-            if (lane >= d) x += y;
+            const int ya = __shfl_up(xa, d), yb = __shfl_up(xb, d);
+            if (lane >= d) xa += ya, xb += yb;
         }
-        if (lane == 63) tmp[wv] = x;
+        if (lane == 63) tmp[wv] = xa, tmp[17 + wv] = xb;
         __syncthreads();
         if (wv == 0) {
-            int t = lane < kPlanThreads / 64 ? tmp[lane] : 0;
-            int sc = t;
+            const int ta = lane < kPlanThreads / 64 ? tmp[lane] : 0, tb = lane < kPlanThreads / 64 ? tmp[17 + lane] : 0;
+            int sa = ta, sb = tb;
 #pragma unroll
             for (int d = 1; d < 16; d <<= 1) {
-                int y = __shfl_up(sc, d);
-                if (lane >= d) sc += y;
+                const int ya = __shfl_up(sa, d), yb = __shfl_up(sb, d);
+                if (lane >= d) sa += ya, sb += yb;
             }
-            if (lane < kPlanThreads / 64) tmp[lane] = sc - t;
-            if (lane == kPlanThreads / 64 - 1) tmp[16] = sc;
+            if (lane < kPlanThreads / 64) tmp[lane] = sa - ta, tmp[17 + lane] = sb - tb;
+            if (lane == kPlanThreads / 64 - 1) tmp[16] = sa, tmp[33] = sb;
         }
         __syncthreads();
-        if (i < n) out[i] = carry + tmp[wv] + x - v;
-        carry += tmp[16];
+        if (i < n) {
+            a[i] = carry_a + tmp[wv] + xa - va;
+            if (b) b[i] = carry_b + tmp[17 + wv] + xb - vb;
+        }
+        carry_a += tmp[16];
+        carry_b += tmp[33];
         __syncthreads();
     }
-    if (tid == 0) out[n] = carry;
+    if (tid == 0) {
+        a[n] = carry_a;
+        if (b) b[n] = carry_b;
+    }
     __syncthreads();
 }
 
@@ -129,29 +149,32 @@ __device__ void block_scan(const int32_t *in, int32_t *out, int n, int32_t *tmp 
 // proportional to the relative speed xcd_w[x] of its die (the weights add up to 8192).  The rest of the
 // stream, if any, is cut into spans of cd units that the waves take from a counter as they finish.
 struct Cuts {
-    long U, S0, cd;
+    int U, S0, cd; // the stream has fewer than 2^31 units (checked on the host); divisions stay 32 bits wide
     int waves, nspans;
     int acc[9]; // running sums of the die weights
-    __device__ long lo(int c) const
+    __device__ int lo(int c) const
     {
-        long v = c < waves ? (long)(c >> 3) * 8 * S0 + ((8 * S0 * acc[c & 7]) >> 13) : (long)waves * S0 + (long)(c - waves) * cd;
-        return v < U ? v : U;
+        const long v = c < waves ? (long)(c >> 3) * 8 * S0 + ((8L * S0 * acc[c & 7]) >> 13) : (long)waves * S0 + (long)(c - waves) * cd;
+        return v < U ? (int)v : U;
     }
-    __device__ int span_of(long pos) const // the span that holds cost unit pos < U
+    __device__ int span_of(int pos) const // the span that holds cost unit pos < U
     {
-        if (pos >= (long)waves * S0) return waves + (int)((pos - (long)waves * S0) / cd);
-        const long blk = pos / (8 * S0), rem = pos - blk * 8 * S0;
+        const long stat = (long)waves * S0;
+        if (pos >= stat) return waves + (int)((unsigned)(pos - (int)stat) / (unsigned)cd);
+        const unsigned blk = (unsigned)pos / (unsigned)(8 * S0);
+        const int rem = pos - (int)blk * 8 * S0;
         int x = 0;
 #pragma unroll
         for (int i = 1; i < 8; i++)
-            if (((8 * S0 * acc[i]) >> 13) <= rem) x = i;
+            if ((int)((8L * S0 * acc[i]) >> 13) <= rem) x = i;
         return (int)blk * 8 + x;
     }
 };
 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
 {
-    __shared__ int32_t scan_tmp[17];
+    touch_args(a);
+    __shared__ int32_t scan_tmp[34];
     __shared__ int32_t l_len[kPlanCap], l_grp[kPlanCap], l_poff[kPlanCap + 1];
     __shared__ int32_t l_grp_count[kPlanCap], l_grp_rowbase[kPlanCap + 1], l_grp_membase[kPlanCap + 1];
     __shared__ int32_t l_seq_rank[kPlanCap], l_prow_g[kPlanCap], l_row_start[2 * kPlanCap + 1];
@@ -203,10 +226,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
     __syncthreads();
     int nPR = 0;
     if (NG) {
-        block_scan(grp_count, grp_membase, NG, scan_tmp);
-        for (int g = tid; g < NG; g += kPlanThreads) grp_rowbase[g] = (grp_count[g] + MPR - 1) / MPR;
+        for (int g = tid; g < NG; g += kPlanThreads) {
+            grp_membase[g] = grp_count[g];
+            grp_rowbase[g] = (grp_count[g] + MPR - 1) / MPR;
+        }
         __syncthreads();
-        block_scan(grp_rowbase, grp_rowbase, NG, scan_tmp);
+        block_scan(grp_membase, grp_rowbase, NG, scan_tmp);
         nPR = grp_rowbase[NG];
     }
     // Rows and their cost per kv head (staged in row_start, scanned in place): an item of n > 0 pages costs
@@ -237,33 +262,34 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
     }
     __syncthreads();
     const int nR = B + nPR;
-    block_scan(row_start, row_start, nR, scan_tmp);
+    block_scan(row_start, nullptr, nR, scan_tmp);
 
     Cuts cut;
-    cut.U = (long)a.Hkv * row_start[nR];
+    cut.U = a.Hkv * row_start[nR];
     cut.waves = a.waves;
     // no span is shorter than a few pages, and none is shorter than one page of either kind, so that every
     // span between the first and the last one of an item holds at least one of its pages
-    long min_span = (long)kMinUnitsPerWave * kCostSuffix;
+    int min_span = kMinUnitsPerWave * kCostSuffix;
     if (min_span < 4 * a.cost_prefix) min_span = 4 * a.cost_prefix; // (a die's share is at least half the mean)
-    cut.S0 = a.static_pct >= 100 ? (cut.U + a.waves - 1) / a.waves : cut.U * a.static_pct / 100 / a.waves;
+    cut.S0 = a.static_pct >= 100 ? (int)(((unsigned)cut.U + a.waves - 1) / (unsigned)a.waves)
+                                 : (int)((unsigned)cut.U / (unsigned)a.waves) * a.static_pct / 100;
     if (cut.S0 < min_span) cut.S0 = min_span;
-    cut.cd = (long)a.dyn_pages * kCostSuffix;
+    cut.cd = a.dyn_pages * kCostSuffix;
     if (cut.cd < min_span) cut.cd = min_span;
-    long ndyn = 0;
-    const long Ud = cut.U - cut.S0 * a.waves;
+    int ndyn = 0;
+    const long Ud = (long)cut.U - (long)cut.S0 * a.waves;
     if (Ud > 0) {
-        const long most = (long)kDynSpansPerWave * a.waves;
-        if ((Ud + cut.cd - 1) / cut.cd > most) cut.cd = (Ud + most - 1) / most;
-        ndyn = (Ud + cut.cd - 1) / cut.cd;
+        const int most = kDynSpansPerWave * a.waves;
+        if (((unsigned)Ud + cut.cd - 1) / (unsigned)cut.cd > (unsigned)most) cut.cd = (int)(((unsigned)Ud + most - 1) / (unsigned)most);
+        ndyn = (int)(((unsigned)Ud + cut.cd - 1) / (unsigned)cut.cd);
     }
-    cut.nspans = a.waves + (int)ndyn;
+    cut.nspans = a.waves + ndyn;
     cut.acc[0] = 0;
 #pragma unroll
     for (int x = 0; x < 8; x++) cut.acc[x + 1] = cut.acc[x] + a.xcd_w[x];
     const int nspans = cut.nspans;
     if (tid == 0) {
-        w.hdr[0] = (int)cut.U;
+        w.hdr[0] = cut.U;
         w.hdr[2] = nR;
         w.hdr[3] = nPR;
         w.hdr[5] = a.waves; // next span to hand out
@@ -289,7 +315,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
     // A record is {index of the row's first page id in its table, first page, end page, token limit,
     // kv head | prefix << 16, sequence (own pages) or first member slot (shared pages), query rows, partial slot}.
     for (int c = tid; c < nspans; c += kPlanThreads) {
-        const int lo = (int)cut.lo(c), hi = (int)cut.lo(c + 1);
+        const int lo = cut.lo(c), hi = cut.lo(c + 1);
         int chunk = c, n = 0;
         if (lo < hi) {
             // first row of the span: the last row that starts at or before the span's first unit
@@ -343,7 +369,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
             const int ic = row_start[r + 1] - row_start[r];
             if (ic > 0) {
                 const int n = (ic - a.cost_item) / kCostSuffix;
-                const long S = (long)a.Hkv * row_start[r] + (long)kvh * ic + a.cost_item;
+                const int S = a.Hkv * row_start[r] + kvh * ic + a.cost_item;
                 own = make_int4(n, cut.span_of(S), cut.span_of(S + kCostSuffix * (n - 1)), 0);
             }
         }
@@ -353,7 +379,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
             const int r = grp_rowbase[g] + rank / MPR;
             const int ic = row_start[r + 1] - row_start[r];
             const int n = (ic - a.cost_item) / a.cost_prefix;
-            const long S = (long)a.Hkv * row_start[r] + (long)kvh * ic + a.cost_item;
+            const int S = a.Hkv * row_start[r] + kvh * ic + a.cost_item;
             pfx = make_int4(n, cut.span_of(S), cut.span_of(S + a.cost_prefix * (n - 1)), 0);
         }
         w.merge_desc[2 * i] = own;
@@ -881,6 +907,7 @@ template <int D, int KVB, int NST> __device__ __forceinline__ void attention_bod
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     const uint32_t lds_addr = (uint32_t)(uintptr_t)lds;
     const int lane = threadIdx.x;
+    touch_args(a);
     const int nspans = uniform_load(hdr, 7);
     if ((int)blockIdx.x >= nspans) return;
 
@@ -1066,6 +1093,53 @@ hipError_t launch_attention(const Launch &a, hipStream_t s)
 }
 
 // ------------------------------------------------------------------------------------------------------
+// die calibration: how fast does each accelerator die stream when all of them stream at once?
+//
+// The attention kernel gives every resident wave one span of the work, and a wave's speed is its die's
+// share of the memory system, which differs from die to die and from machine to machine by up to a tenth.
+// This probe has the attention kernel's launch shape (one wave per workgroup, the same LDS footprint, so
+// the same waves on the same compute units) and its memory behaviour (a two-stage LDS ring of 16 KB stages
+// fed by direct global->LDS loads from scattered 16 KB blocks), and no arithmetic.  Every wave reports how
+// long its share took and which die it ran on.
+// ------------------------------------------------------------------------------------------------------
+
+__global__ __launch_bounds__(64) void calibrate_kernel(const uint8_t *__restrict__ buf, int nblocks, int stages, long long *out)
+{
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)lds;
+    const int lane = threadIdx.x;
+    const long long t0 = wall_clock64();
+    // block of stage s: a fixed permutation of [0, nblocks) (nblocks is a power of two, the multiplier is odd)
+    auto issue = [&](int s) {
+        const uint32_t blk = ((uint32_t)(blockIdx.x + s * gridDim.x) * 40503u) & (uint32_t)(nblocks - 1);
+        const uint8_t *src = buf + (size_t)blk * 16384;
+#pragma unroll
+        for (int n = 0; n < 16; n++) dma16_base((uint32_t)(1024 * n + 16 * lane), src, lds_addr + (s & 1) * 16384 + 1024 * n);
+    };
+    issue(0);
+    for (int s = 0; s < stages; s++) {
+        if (s + 1 < stages) {
+            issue(s + 1);
+            wait_vmcnt<16>();
+        } else {
+            wait_vmcnt<0>();
+        }
+    }
+    if (lane == 0) {
+        out[2 * blockIdx.x] = wall_clock64() - t0;
+        out[2 * blockIdx.x + 1] = __builtin_amdgcn_s_getreg((20) | (0 << 6) | (3 << 11)) & 7; // die (XCC_ID)
+    }
+}
+
+hipError_t launch_calibrate(const void *buf, int nblocks, int stages, int waves, long long *out, hipStream_t s)
+{
+    hipError_t e = hipFuncSetAttribute((const void *)calibrate_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 40960);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(calibrate_kernel, dim3(waves), dim3(64), 40960, s, (const uint8_t *)buf, nblocks, stages, out);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------------
 // merge: out[b,h] and lse[b,h] from the partials of the shared-prefix row and of the sequence's own spans.
 // One workgroup per (sequence, kv head); a thread owns four output elements of one of its G heads.
 // With weights w_i = 2^(lse2_i - M): out = sum w_i o_i / sum w_i, lse = (M + log2 sum w_i) ln 2, always in
@@ -1085,6 +1159,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(Launch a, const in
                                                                const int32_t *__restrict__ seq_pfx_row,
                                                                const int32_t *__restrict__ seq_rank_in_row)
 {
+    touch_args(a);
     const Workspace &w = a.ws;
     const int item = blockIdx.x, b = item / a.Hkv, kvh = item - b * a.Hkv;
     const int D = a.D, tpr = D / 4; // threads per output row
@@ -1109,19 +1184,42 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(Launch a, const in
         p.ostride = (int64_t)kPrefixRows * D;
         p.lstride = kPrefixRows;
     }
+    const int npfx = pl[0].c_hi - pl[0].c_lo + 1, nown = pl[1].c_hi - pl[1].c_lo + 1;
     for (int hl = threadIdx.x / tpr; hl < a.G; hl += kMergeThreads / tpr) {
         const int d4 = (threadIdx.x % tpr) * 4;
-        float M = -INFINITY;
-        for (int k = 0; k < 2; k++)
-            for (int c = pl[k].c_lo; c <= pl[k].c_hi; c++) M = fmaxf(M, pl[k].lse[c * pl[k].lstride + hl]);
+        float M = -INFINITY, wsum = 0.f;
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        float wsum = 0.f;
-        for (int k = 0; k < 2; k++)
-            for (int c = pl[k].c_lo; c <= pl[k].c_hi; c++) {
-                const float wgt = __builtin_amdgcn_exp2f(pl[k].lse[c * pl[k].lstride + hl] - M);
-                wsum += wgt;
-                acc += wgt * *(const f32x4 *)(pl[k].o + c * pl[k].ostride + (int64_t)hl * D + d4);
+        if (npfx <= 2 && nown <= 3) {
+            // the usual case: at most two prefix partials and three own ones; all ten loads go out together
+            float l[5];
+            f32x4 v[5];
+#pragma unroll
+            for (int i = 0; i < 5; i++) {
+                const PartList &p = pl[i < 2 ? 0 : 1];
+                const int c = p.c_lo + (i < 2 ? i : i - 2);
+                const bool have = c <= p.c_hi;
+                l[i] = have ? p.lse[c * p.lstride + hl] : -INFINITY;
+                v[i] = have ? *(const f32x4 *)(p.o + c * p.ostride + (int64_t)hl * D + d4) : f32x4{0.f, 0.f, 0.f, 0.f};
             }
+#pragma unroll
+            for (int i = 0; i < 5; i++) M = fmaxf(M, l[i]);
+#pragma unroll
+            for (int i = 0; i < 5; i++) {
+                const float wgt = l[i] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(l[i] - M);
+                wsum += wgt;
+                acc += wgt * v[i];
+            }
+        } else {
+            for (int k = 0; k < 2; k++)
+                for (int c = pl[k].c_lo; c <= pl[k].c_hi; c++) M = fmaxf(M, pl[k].lse[c * pl[k].lstride + hl]);
+            for (int k = 0; k < 2; k++)
+                for (int c = pl[k].c_lo; c <= pl[k].c_hi; c++) {
+                    const float lv = pl[k].lse[c * pl[k].lstride + hl];
+                    const float wgt = lv == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(lv - M);
+                    wsum += wgt;
+                    acc += wgt * *(const f32x4 *)(pl[k].o + c * pl[k].ostride + (int64_t)hl * D + d4);
+                }
+        }
         const bool empty = wsum == 0.f;
         const float inv = empty ? 0.f : 1.0f / wsum;
         const int64_t bh = (int64_t)b * a.Hq + kvh * a.G + hl;

@@ -23,7 +23,7 @@ def isa(tmp_path_factory):
 def kernels(isa):
     """name -> body text of every attention kernel."""
     out = {}
-    for m in re.finditer(r"^(_ZN2ra19attention_kernel\w+):.*?s_endpgm", isa, flags=re.S | re.M):
+    for m in re.finditer(r"^(_ZN2ra\d+attention_kernel\w+):.*?s_endpgm", isa, flags=re.S | re.M):
         out[m.group(1)] = m.group(0)
     return out
 
@@ -34,3 +34,4 @@ def test_no_scratch_and_no_full_drain_in_the_page_loop(isa):
         assert "scratch_" not in body, name
         # the LDS ring is paced by hand-written waits with a non-zero count; they must be there
         assert re.search(r"s_waitcnt vmcnt\([1-9][0-9]*\)", body), name
+
