@@ -1099,8 +1099,8 @@ hipError_t launch_attention(const Launch &a, hipStream_t s)
 // share of the memory system, which differs from die to die and from machine to machine by up to a tenth.
 // This probe has the attention kernel's launch shape (one wave per workgroup, the same LDS footprint, so
 // the same waves on the same compute units) and its memory behaviour (a two-stage LDS ring of 16 KB stages
-// fed by direct global->LDS loads from scattered 16 KB blocks), and no arithmetic.  Every wave reports how
-// long its share took and which die it ran on.
+// fed by direct global->LDS loads from scattered 16 KB blocks); a pause stands for the arithmetic.  Every
+// wave reports how long its share took and which die it ran on.
 // ------------------------------------------------------------------------------------------------------
 
 __global__ __launch_bounds__(64) void calibrate_kernel(const uint8_t *__restrict__ buf, int nblocks, int stages, long long *out)
@@ -1124,6 +1124,9 @@ __global__ __launch_bounds__(64) void calibrate_kernel(const uint8_t *__restrict
         } else {
             wait_vmcnt<0>();
         }
+        // the attention kernel spends about this long on the arithmetic of a stage, issuing nothing meanwhile;
+        // a wave's speed depends on the memory latency only through the sum of the two
+        __builtin_amdgcn_s_sleep(56);
     }
     if (lane == 0) {
         out[2 * blockIdx.x] = wall_clock64() - t0;
