@@ -59,8 +59,8 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true", help="also run three 1 GiB device copies (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures one GPU only (the path needs no exchange between GPUs; "
-              "see DESIGN.md, 'More than one GPU'); run with --gpus 1", file=sys.stderr)
+        print("bench.py: one GPU only. Sequences are independent, so the path shards over GPUs with no exchange "
+              "and one GPU's throughput on its share is the figure; run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
