@@ -19,7 +19,7 @@ constexpr int kCostItem = 16;       // ... of a segment, on top of its pages
 // Device pointers into the caller's workspace.  All offsets are fixed by the shape alone.
 struct Workspace {
     int32_t *hdr;            // [16]: 0 total cost units, 2 rows, 3 prefix rows, 4 error flags, 5 next span to hand out,
-                             //       7 spans
+                             //       7 spans, 8 overflow chunks of the work lists in use
     int32_t *grp_count;      // [num_groups]      members that use the shared pass
     int32_t *grp_rowbase;    // [num_groups + 1]  first prefix row of the group (relative)
     int32_t *grp_membase;    // [num_groups + 1]  first slot of the group in members[]
@@ -29,7 +29,8 @@ struct Workspace {
     int4 *merge_desc;        // [B*Hkv][2]  {pages, first span, last span, -} of the own row and of the prefix row
     int32_t *members;        // [B]   sequences ordered by prefix row
     int32_t *row_start;      // [2B + 1] exclusive scan of the rows' cost (per kv head); prefix rows come first
-    int32_t *prow_g;         // [B]   group of a prefix row
+    int4 *row_tab;           // [2B]  prefix row: {index of the group's first page id, first member slot, members, pages};
+                             //       sequence row: {sequence, pages skipped, tokens after the skip, pages}
     int4 *seg_rec;           // [chunks][8][2]  what each span's wave does: chunk c < spans belongs to span c; record 0 of a
                              //       chunk is {segments in the chunk (<= 7), next chunk of the span or -1}, then the segments
     float *suf_o;            // [(B*Hkv + spans)][G][D]   partial outputs (normalised); slot = item + span

@@ -64,7 +64,7 @@ size_t carve_workspace(Workspace &ws, void *base, int B, int Hkv, int G, int D, 
     ws.merge_desc = (int4 *)take((size_t)B * Hkv * 32);
     ws.members = (int32_t *)take((size_t)B * 4);
     ws.row_start = (int32_t *)take(((size_t)2 * B + 1) * 4);
-    ws.prow_g = (int32_t *)take((size_t)B * 4);
+    ws.row_tab = (int4 *)take((size_t)2 * B * 16);
     const size_t spans = (size_t)(1 + kDynSpansPerWave) * waves; // upper bound on spans of the cost stream
     // every (item, span) pair that shares pages is one segment: at most items + spans of them
     const size_t chunks = spans + ((size_t)2 * B * Hkv + spans) / kChunkSegs + 2;
@@ -93,11 +93,13 @@ size_t carve_workspace(Workspace &ws, void *base, int B, int Hkv, int G, int D, 
 // [lo, hi) of the cost stream: those whose first unit S + cw*p lies in the span.
 __device__ __forceinline__ void span_pages(int S, int cw, int n, int lo, int hi, int &p_lo, int &p_hi)
 {
-    p_lo = lo <= S ? 0 : min(n, (lo - S + cw - 1) / cw);
-    p_hi = hi <= S ? 0 : min(n, (hi - S + cw - 1) / cw);
+    // (an integer division is dozens of instructions here; most items lie wholly inside a span and need none)
+    const int last = S + cw * (n - 1); // first unit of the last page
+    p_lo = lo <= S ? 0 : (lo > last ? n : (lo - S + cw - 1) / cw);
+    p_hi = hi <= S ? 0 : (hi > last ? n : (hi - S + cw - 1) / cw);
 }
 
-constexpr int kPlanThreads = 1024;
+constexpr int kPlanThreads = 256;
 constexpr int kPlanCap = 2048; // sequences / groups whose intermediate arrays fit in LDS; beyond, the workspace is used
 
 // Exclusive scans of a[0..n) and b[0..n) in place, a[n] and b[n] = totals (b may be null).  All threads call it.
@@ -171,14 +173,13 @@ struct Cuts {
     }
 };
 
-__global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
+__global__ __launch_bounds__(kPlanThreads) void plan_rows_kernel(Launch a)
 {
     touch_args(a);
     __shared__ int32_t scan_tmp[34];
     __shared__ int32_t l_len[kPlanCap], l_grp[kPlanCap], l_poff[kPlanCap + 1];
     __shared__ int32_t l_grp_count[kPlanCap], l_grp_rowbase[kPlanCap + 1], l_grp_membase[kPlanCap + 1];
-    __shared__ int32_t l_seq_rank[kPlanCap], l_prow_g[kPlanCap], l_row_start[2 * kPlanCap + 1];
-    __shared__ int32_t l_overflow;
+    __shared__ int32_t l_seq_rank[kPlanCap], l_row_start[2 * kPlanCap + 1];
     const int tid = threadIdx.x;
     const Workspace &w = a.ws;
     const int B = a.B;
@@ -190,7 +191,6 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
     int32_t *grp_rowbase = small ? l_grp_rowbase : w.grp_rowbase;
     int32_t *grp_membase = small ? l_grp_membase : w.grp_membase;
     int32_t *seq_rank = small ? l_seq_rank : w.seq_rank;
-    int32_t *prow_g = small ? l_prow_g : w.prow_g;
     int32_t *row_start = small ? l_row_start : w.row_start;
     const int32_t *len_src = a.seq_lens, *grp_src = a.seq_group, *poff = a.pfx_off;
     // one trip to memory for everything the schedule depends on
@@ -203,7 +203,6 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
         len_src = l_len, grp_src = l_grp, poff = l_poff;
     }
     for (int g = tid; g < NG; g += kPlanThreads) grp_count[g] = 0;
-    if (tid == 0) l_overflow = 0;
     __syncthreads();
     auto len_of = [&](int b) { // never walk past the table row
         const int L = len_src[b];
@@ -241,8 +240,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
         const int cnt = grp_count[g], np = poff[g + 1] - poff[g];
         const int r0 = grp_rowbase[g];
         for (int k = 0; k * MPR < cnt; k++) {
+            const int left = cnt - k * MPR;
             row_start[r0 + k] = a.cost_item + np * a.cost_prefix;
-            prow_g[r0 + k] = g;
+            w.row_tab[r0 + k] = make_int4(poff[g], grp_membase[g] + k * MPR, left < MPR ? left : MPR, np);
         }
     }
     for (int b = tid; b < B; b += kPlanThreads) {
@@ -259,13 +259,50 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
         w.seq_rank_in_row[b] = rank >= 0 ? rank % MPR : -1;
         const int pages = L > 0 ? (L + kPage - 1) / kPage - skip : 0;
         row_start[nPR + b] = pages > 0 ? a.cost_item + pages * kCostSuffix : 0;
+        w.row_tab[nPR + b] = make_int4(b, skip, L - skip * kPage, pages);
     }
     __syncthreads();
     const int nR = B + nPR;
     block_scan(row_start, nullptr, nR, scan_tmp);
 
+    // hand over to the second kernel: the scanned row costs and the counts
+    for (int r = tid; r <= nR; r += kPlanThreads) w.row_start[r] = row_start[r];
+    if (tid == 0) {
+        w.hdr[0] = a.Hkv * row_start[nR];
+        w.hdr[2] = nR;
+        w.hdr[3] = nPR;
+        w.hdr[8] = 0; // overflow chunks in use
+    }
+}
+
+// Second half of the schedule, spread over many compute units: the cuts, every span's work list, and the merge
+// descriptors.  Each workgroup first copies the scanned row costs and the row table into LDS.
+constexpr int kSpanThreads = 128;
+
+__global__ __launch_bounds__(kSpanThreads) void plan_spans_kernel(Launch a)
+{
+    touch_args(a);
+    __shared__ int32_t l_row_start[2 * kPlanCap + 1];
+    __shared__ int4 l_row_tab[2 * kPlanCap];
+    const int tid = threadIdx.x;
+    const int gtid = blockIdx.x * kSpanThreads + tid, gstride = gridDim.x * kSpanThreads;
+    const Workspace &w = a.ws;
+    const int32_t *row_start = w.row_start;
+    const int4 *row_tab = w.row_tab;
+    // (there are at most 2B rows; copying that many without waiting for the count saves a trip to memory)
+    const int rows_most = 2 * a.B;
+    if (rows_most <= 2 * kPlanCap) {
+        for (int r = tid; r <= rows_most; r += kSpanThreads) l_row_start[r] = w.row_start[r];
+        for (int r = tid; r < rows_most; r += kSpanThreads) l_row_tab[r] = w.row_tab[r];
+        row_start = l_row_start, row_tab = l_row_tab;
+    }
+    const int U = w.hdr[0], nR = w.hdr[2], nPR = w.hdr[3];
+    const int my_item = gtid < a.B * a.Hkv ? gtid : 0;
+    const int my_prow = w.seq_pfx_row[my_item / a.Hkv]; // for the merge descriptors below; fetched with the rest
+    __syncthreads();
+
     Cuts cut;
-    cut.U = a.Hkv * row_start[nR];
+    cut.U = U;
     cut.waves = a.waves;
     // no span is shorter than a few pages, and none is shorter than one page of either kind, so that every
     // span between the first and the last one of an item holds at least one of its pages
@@ -288,33 +325,15 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
 #pragma unroll
     for (int x = 0; x < 8; x++) cut.acc[x + 1] = cut.acc[x] + a.xcd_w[x];
     const int nspans = cut.nspans;
-    if (tid == 0) {
-        w.hdr[0] = cut.U;
-        w.hdr[2] = nR;
-        w.hdr[3] = nPR;
+    if (gtid == 0) {
         w.hdr[5] = a.waves; // next span to hand out
         w.hdr[7] = nspans;
     }
-    // what a row is: {group, first member slot, members, pages} or {sequence, pages skipped, tokens after, pages}
-    auto row_info = [&](int r) {
-        if (r < nPR) {
-            const int g = prow_g[r], k = r - grp_rowbase[g], left = grp_count[g] - k * MPR;
-            return make_int4(g, grp_membase[g] + k * MPR, left < MPR ? left : MPR, poff[g + 1] - poff[g]);
-        }
-        const int b = r - nPR, L = len_of(b);
-        int skip = 0;
-        if (seq_rank[b] >= 0) {
-            const int g = grp_of(b);
-            skip = poff[g + 1] - poff[g];
-        }
-        return make_int4(b, skip, L - skip * kPage, L > 0 ? (L + kPage - 1) / kPage - skip : 0);
-    };
-
     // The work list of every span: one record per segment (the pages of one (row, kv head) item that lie in
     // the span), so that the attention waves find their work with one load instead of walking these tables.
     // A record is {index of the row's first page id in its table, first page, end page, token limit,
     // kv head | prefix << 16, sequence (own pages) or first member slot (shared pages), query rows, partial slot}.
-    for (int c = tid; c < nspans; c += kPlanThreads) {
+    for (int c = gtid; c < nspans; c += gstride) {
         const int lo = cut.lo(c), hi = cut.lo(c + 1);
         int chunk = c, n = 0;
         if (lo < hi) {
@@ -330,7 +349,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
                 if (rs >= hi) break;
                 const int ic = row_start[r + 1] - row_start[r]; // cost of one item of the row
                 if (ic == 0) continue;
-                const int4 info = row_info(r);
+                const int4 info = row_tab[r];
                 const bool prefix = r < nPR;
                 const int cw = prefix ? a.cost_prefix : kCostSuffix;
                 for (int kvh = lo > rs ? (lo - rs) / ic : 0; kvh < a.Hkv; kvh++) {
@@ -340,7 +359,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
                     span_pages(S + a.cost_item, cw, info.w, lo, hi, p_lo, p_hi);
                     if (p_lo >= p_hi) continue;
                     if (n == kChunkSegs) { // chain another chunk
-                        const int nc = nspans + atomicAdd(&l_overflow, 1);
+                        const int nc = nspans + atomicAdd(&w.hdr[8], 1);
                         w.seg_rec[(size_t)chunk * 16] = make_int4(n, nc, 0, 0);
                         chunk = nc;
                         n = 0;
@@ -350,7 +369,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
                         rec[0] = make_int4(info.x * a.max_pages + info.y, p_lo, p_hi, min(info.z, p_hi * kPage));
                         rec[1] = make_int4(kvh, info.x, a.G, info.x * a.Hkv + kvh + c);
                     } else {
-                        rec[0] = make_int4(poff[info.x], p_lo, p_hi, p_hi * kPage);
+                        rec[0] = make_int4(info.x, p_lo, p_hi, p_hi * kPage);
                         rec[1] = make_int4(kvh | (1 << 16), info.y, info.z * a.G, r * a.Hkv + kvh + c);
                     }
                     n++;
@@ -361,7 +380,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
     }
     // For the merge: the spans that hold pages of each (sequence, kv head)'s own row and of its prefix row,
     // {pages, first span, last span, unused}.  Every span in that range holds at least one of the pages.
-    for (int i = tid; i < B * a.Hkv; i += kPlanThreads) {
+    for (int i = gtid; i < a.B * a.Hkv; i += gstride) {
         const int b = i / a.Hkv, kvh = i - b * a.Hkv;
         int4 own = make_int4(0, 0, -1, 0), pfx = make_int4(0, 0, -1, 0);
         {
@@ -373,10 +392,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
                 own = make_int4(n, cut.span_of(S), cut.span_of(S + kCostSuffix * (n - 1)), 0);
             }
         }
-        const int rank = seq_rank[b];
-        if (rank >= 0) {
-            const int g = grp_of(b);
-            const int r = grp_rowbase[g] + rank / MPR;
+        const int r = i == gtid ? my_prow : w.seq_pfx_row[b];
+        if (r >= 0) {
             const int ic = row_start[r + 1] - row_start[r];
             const int n = (ic - a.cost_item) / a.cost_prefix;
             const int S = a.Hkv * row_start[r] + kvh * ic + a.cost_item;
@@ -389,7 +406,13 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Launch a)
 
 hipError_t launch_plan(const Launch &a, hipStream_t s)
 {
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, s, a);
+    hipLaunchKernelGGL(plan_rows_kernel, dim3(1), dim3(kPlanThreads), 0, s, a);
+    // one thread per span and per (sequence, kv head); the span count is only known on the device, so the grid
+    // covers the most there can be
+    const int most = (1 + kDynSpansPerWave) * a.waves;
+    const int work = a.static_pct >= 100 ? a.waves : most;
+    const int n = work > a.B * a.Hkv ? work : a.B * a.Hkv;
+    hipLaunchKernelGGL(plan_spans_kernel, dim3((n + kSpanThreads - 1) / kSpanThreads), dim3(kSpanThreads), 0, s, a);
     return hipGetLastError();
 }
 
