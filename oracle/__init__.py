@@ -52,6 +52,10 @@ def _lib():
         lib.oracle_e4m3_decode.restype = ctypes.c_double
         lib.oracle_e4m3_decode.argtypes = [ctypes.c_uint8]
         lib.oracle_threads.restype = ctypes.c_int
+        lib.oracle_e4m3_encode.restype = ctypes.c_uint8
+        lib.oracle_e4m3_encode.argtypes = [ctypes.c_float]
+        lib.oracle_append.restype = ctypes.c_int
+        lib.oracle_append.argtypes = [ctypes.POINTER(_CProblem), ctypes.c_void_p, ctypes.c_void_p]
         _LIB = lib
     return _LIB
 
@@ -163,3 +167,30 @@ def merge_partials(outs, lses):
 
 def threads():
     return int(_lib().oracle_threads())
+
+
+def e4m3_encode(x):
+    """Nearest OCP E4M3 code (ties to even, saturating at 448, NaN -> 0x7F) of every binary32 value in x."""
+    lib = _lib()
+    x = np.asarray(x, dtype=np.float32)
+    return np.array([lib.oracle_e4m3_encode(float(v)) for v in x.ravel()], dtype=np.uint8).reshape(x.shape)
+
+
+def append(p, k_new, v_new):
+    """Appends one token per sequence at position seq_lens[b] (paged write; e4m3 pools quantise on write and
+    maintain the per-(page, head) scales as described in the C file).  ``p.k_pool``, ``p.v_pool`` (and
+    ``p.k_scale``, ``p.v_scale``) must be C-contiguous numpy arrays of the pool's type; they are modified in
+    place.  ``k_new``, ``v_new``: bf16 bits, uint16 [B, Hkv, D].  ``p.seq_lens`` is not changed.  Returns the
+    number of sequences skipped because their length or page id is out of range."""
+    fp8 = p.kv_dtype == "fp8_e4m3"
+    for a, dt in ((p.k_pool, np.uint8 if fp8 else np.uint16), (p.v_pool, np.uint8 if fp8 else np.uint16)):
+        assert a.dtype == dt and a.flags["C_CONTIGUOUS"] and a.flags["WRITEABLE"]
+    if fp8:
+        for a in (p.k_scale, p.v_scale):
+            assert a.dtype == np.float32 and a.flags["C_CONTIGUOUS"] and a.flags["WRITEABLE"]
+    m = _Marshalled(p)  # its views alias the arrays checked above
+    assert m.k.ctypes.data == p.k_pool.ctypes.data and m.v.ctypes.data == p.v_pool.ctypes.data
+    kn = np.ascontiguousarray(k_new, dtype=np.uint16)
+    vn = np.ascontiguousarray(v_new, dtype=np.uint16)
+    assert kn.shape == (m.B, m.Hkv, m.D) and vn.shape == kn.shape
+    return int(_lib().oracle_append(ctypes.byref(m.c), kn.ctypes.data, vn.ctypes.data))

@@ -230,3 +230,156 @@ int oracle_threads(void)
     return 1;
 #endif
 }
+
+/* ------------------------------------------------------------------------
+ * KV append: the write that precedes attention in every decode iteration
+ * (auto-regressive generation appends one token's key and value per
+ * sequence and step: paper Sec. 2.1.1).  The paper does not define it; the
+ * definition below is ours and is the one the HIP library is held to.
+ *
+ * For every sequence b with L = seq_lens[b] (the length BEFORE the append),
+ * the new token goes to position L: page pg = block_table[b][L / page],
+ * slot s = L % page, for every kv head.  Sequences whose L is negative or
+ * not below max_pages_per_seq * page, or whose page id is out of range, are
+ * left alone.  seq_lens is not changed.
+ *
+ * bf16 pools: the 16-bit patterns are copied.
+ *
+ * e4m3 pools, per (page, kv head), K and V alike, everything in IEEE
+ * binary32 with round-to-nearest-even (the decision of a code is taken in
+ * that precision on both sides):
+ *   a = max_d |x_d|                                   (x = the new row)
+ *   s == 0 (a fresh page):  scale = a > 0 ? a / 448 : 1
+ *   s  > 0:                 old = scale[pg][kv]
+ *                           if a <= old * 448:  scale = old
+ *                           else                scale = a / 448, and every
+ *                              stored slot j < s is re-quantised:
+ *                              code[j][d] = enc((dec(code[j][d]) * old) / scale)
+ *   code[s][d] = enc(x_d / scale),  scale[pg][kv] = scale
+ * enc rounds to the nearest E4M3 value, ties to the even code, saturates at
+ * +-448 and maps NaN to 0x7F.
+ * ------------------------------------------------------------------------ */
+
+static float bf16_to_f32(uint16_t bits)
+{
+    uint32_t u = (uint32_t)bits << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+/* Nearest E4M3 code of a binary32 value, written out from the format's
+ * definition: candidates are enumerated by exponent, not by bit tricks. */
+uint8_t oracle_e4m3_encode(float y)
+{
+    if (y != y)
+        return 0x7F;
+    uint8_t sign = signbit(y) ? 0x80 : 0x00;
+    double a = fabs((double)y);
+    if (a >= 448.0)
+        return sign | 0x7E;              /* saturate (480 would be the next step; there is none) */
+    /* the grid around a: step 2^-9 below 2^-6 (subnormals), else 2^(e-3) for 2^e <= a < 2^(e+1) */
+    int e = -6;
+    if (a >= ldexp(1.0, -6))
+        e = (int)floor(log2(a));
+    if (ldexp(1.0, e) > a)
+        e--;                             /* guard against log2 rounding up at a power of two */
+    if (a >= ldexp(1.0, e + 1))
+        e++;
+    if (e < -6)
+        e = -6;
+    double step = ldexp(1.0, e - 3);
+    double qd = a / step;                /* exact: a power of two divides */
+    double lo = floor(qd), frac = qd - lo;
+    long q = (long)lo;
+    if (frac > 0.5 || (frac == 0.5 && (q & 1)))
+        q++;
+    /* q counts steps from 0 in this binade: value = q * step; turn it back into a code */
+    double v = (double)q * step;
+    if (v >= 448.0)
+        return sign | 0x7E;
+    if (v < ldexp(1.0, -6))
+        return sign | (uint8_t)q;        /* subnormal: q in 0..7 (q == 8 is 2^-6, handled below) */
+    int ev = (int)floor(log2(v));
+    if (ldexp(1.0, ev) > v)
+        ev--;
+    if (v >= ldexp(1.0, ev + 1))
+        ev++;
+    int m = (int)(v / ldexp(1.0, ev - 3)) - 8;
+    return sign | (uint8_t)(((ev + 7) << 3) | m);
+}
+
+static float e4m3_to_f32(uint8_t code)
+{
+    return (float)oracle_e4m3_decode(code); /* exact: at most 4 significant bits */
+}
+
+static void append_fp8_tile(uint8_t *tile, int64_t stride_token, int D, int slot, float *scale, const uint16_t *row)
+{
+    float a = 0.0f;
+    for (int d = 0; d < D; d++) {
+        float x = fabsf(bf16_to_f32(row[d]));
+        if (x > a)
+            a = x;
+    }
+    float s;
+    if (slot == 0) {
+        s = a > 0.0f ? a / 448.0f : 1.0f;
+    } else {
+        float old = *scale;
+        volatile float cap = old * 448.0f;       /* one binary32 rounding, no contraction */
+        if (a <= cap) {
+            s = old;
+        } else {
+            s = a / 448.0f;
+            for (int j = 0; j < slot; j++)
+                for (int d = 0; d < D; d++) {
+                    volatile float y = e4m3_to_f32(tile[j * stride_token + d]) * old;
+                    volatile float z = y / s;
+                    tile[j * stride_token + d] = oracle_e4m3_encode(z);
+                }
+        }
+    }
+    for (int d = 0; d < D; d++) {
+        volatile float z = bf16_to_f32(row[d]) / s;
+        tile[slot * stride_token + d] = oracle_e4m3_encode(z);
+    }
+    *scale = s;
+}
+
+/* k_new, v_new: bf16 bits [B][Hkv][D].  The pools and scales of p are written.  Returns the number of sequences
+ * that were skipped (bad length or page id). */
+int oracle_append(const oracle_problem *p, const uint16_t *k_new, const uint16_t *v_new)
+{
+    int skipped = 0;
+    for (int b = 0; b < p->B; b++) {
+        int64_t L = p->seq_lens[b];
+        if (L < 0 || L >= (int64_t)p->max_pages_per_seq * p->page_size) {
+            skipped++;
+            continue;
+        }
+        int32_t pg = p->block_table[(int64_t)b * p->max_pages_per_seq + L / p->page_size];
+        int slot = (int)(L % p->page_size);
+        if (pg < 0 || pg >= p->num_pages) {
+            skipped++;
+            continue;
+        }
+        for (int kv = 0; kv < p->Hkv; kv++) {
+            int64_t tile = (int64_t)pg * p->stride_page + (int64_t)kv * p->stride_head;
+            const uint16_t *kr = k_new + ((int64_t)b * p->Hkv + kv) * p->D;
+            const uint16_t *vr = v_new + ((int64_t)b * p->Hkv + kv) * p->D;
+            if (p->kv_dtype == 0) {
+                uint16_t *kp = (uint16_t *)p->k_pool + tile + (int64_t)slot * p->stride_token;
+                uint16_t *vp = (uint16_t *)p->v_pool + tile + (int64_t)slot * p->stride_token;
+                memcpy(kp, kr, (size_t)p->D * 2);
+                memcpy(vp, vr, (size_t)p->D * 2);
+            } else {
+                float *ks = (float *)p->k_scale + (int64_t)pg * p->Hkv + kv;
+                float *vs = (float *)p->v_scale + (int64_t)pg * p->Hkv + kv;
+                append_fp8_tile((uint8_t *)p->k_pool + tile, p->stride_token, p->D, slot, ks, kr);
+                append_fp8_tile((uint8_t *)p->v_pool + tile, p->stride_token, p->D, slot, vs, vr);
+            }
+        }
+    }
+    return skipped;
+}
