@@ -159,6 +159,20 @@ def main():
                      "traffic": recorded_traffic(args.workload)},
     }
 
+    # The KV append that precedes each decode step's attention, timed on its own (it is not part of `value`):
+    # all-zero rows, so the pools' contents that the attention reads stay what they were.
+    zero_rows = torch.zeros(probs[0].B, probs[0].Hkv, probs[0].D, dtype=torch.bfloat16, device="cuda:0")
+    for _ in range(10):
+        dec.append(devs[0].c, zero_rows, zero_rows, stream)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record(stream)
+    for i in range(100):
+        dec.append(devs[i % len(devs)].c, zero_rows, zero_rows, stream)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    out["append"] = {"us_per_call": round(ev0.elapsed_time(ev1) * 10, 2), "tokens_per_call": probs[0].B,
+                     "note": "one token per sequence, all kv heads; launch-bound"}
+
     if not args.no_cpu_baseline:
         import oracle
         reps = 3

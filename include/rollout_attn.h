@@ -147,6 +147,28 @@ ra_status rollout_attn_decode(ra_ctx *ctx, const ra_problem *problem, void *work
 ra_status rollout_attn_debug_gather(ra_ctx *ctx, const ra_problem *problem, int32_t b, int32_t kv_head,
                                     void *k_out, void *v_out, int64_t capacity_tokens, void *hip_stream);
 
+/* KV append: writes one new token per sequence into the paged cache, the step that precedes the attention
+ * of a decode iteration (auto-regressive generation: paper Sec. 2.1.1; the paper does not define the write,
+ * this header does).  For every sequence b the token goes to position L = seq_lens[b], the length BEFORE the
+ * append: page block_table[b][L / page_size], slot L % page_size, every kv head.  seq_lens is not modified
+ * (the caller adds one afterwards).  k_new, v_new: dev, bf16 [B][Hkv][D], contiguous, 4-byte aligned.
+ * `problem` must be valid as for rollout_attn_decode; of its device data only block_table and seq_lens are
+ * read, and the pools (for e4m3 also k_scale and v_scale) are WRITTEN although the struct declares them
+ * const.  No two sequences may append into the same page (shared prompt pages are whole pages, so a new
+ * token never lands in one).  A sequence whose length is negative or not below max_pages_per_seq * page_size,
+ * or whose page id is not in [0, num_pages), is skipped.
+ *   bf16 pools: the 16-bit patterns are copied.
+ *   e4m3 pools, per (page, kv head), K and V alike, in IEEE binary32 with round-to-nearest-even:
+ *     a = max_d |x_d| of the new row;
+ *     slot 0 (a fresh page): scale = a > 0 ? a / 448 : 1;
+ *     slot s > 0: if a <= scale * 448 the page keeps its scale, else scale' = a / 448 and every stored
+ *       slot j < s is re-quantised, code = enc((dec(code) * scale) / scale');
+ *     the new row is stored as enc(x_d / scale); enc rounds to the nearest E4M3 value, ties to the even code,
+ *     saturating at +-448.
+ * Enqueued on hip_stream; returns without waiting. */
+ra_status rollout_attn_append(ra_ctx *ctx, const ra_problem *problem, const void *k_new, const void *v_new,
+                              void *hip_stream);
+
 /* Per-kernel timing for benchmarks.  While enabled, rollout_attn_decode records HIP events on its stream
  * around its three phases (schedule, attention, merge); rollout_attn_get_timing waits for the events of the
  * most recent decode call and returns the three durations in milliseconds.  Off by default: the events cost

@@ -69,6 +69,8 @@ def load_library():
     lib.rollout_attn_debug_gather.restype = ctypes.c_int
     lib.rollout_attn_debug_gather.argtypes = [ctypes.c_void_p, P(ra_problem), ctypes.c_int32, ctypes.c_int32,
                                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+    lib.rollout_attn_append.restype = ctypes.c_int
+    lib.rollout_attn_append.argtypes = [ctypes.c_void_p, P(ra_problem), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     lib.rollout_attn_set_timing.restype = ctypes.c_int
     lib.rollout_attn_set_timing.argtypes = [ctypes.c_void_p, ctypes.c_int]
     lib.rollout_attn_get_timing.restype = ctypes.c_int
@@ -123,6 +125,10 @@ def rollout_attn_decode(ctx, problem, workspace_ptr, workspace_bytes, hip_stream
 def rollout_attn_debug_gather(ctx, problem, b, kv_head, k_out_ptr, v_out_ptr, capacity_tokens, hip_stream=None):
     _check(load_library().rollout_attn_debug_gather(ctx, ctypes.byref(problem), b, kv_head, k_out_ptr, v_out_ptr,
                                                     capacity_tokens, hip_stream), ctx)
+
+
+def rollout_attn_append(ctx, problem, k_new_ptr, v_new_ptr, hip_stream=None):
+    _check(load_library().rollout_attn_append(ctx, ctypes.byref(problem), k_new_ptr, v_new_ptr, hip_stream), ctx)
 
 
 def rollout_attn_set_timing(ctx, enable):
@@ -203,6 +209,12 @@ class Decoder:
         ws = self.workspace(problem)
         s = stream if stream is not None else torch.cuda.current_stream(self.device_ordinal)
         rollout_attn_decode(self.ctx, problem, ctypes.c_void_p(ws.data_ptr()), ws.numel(), ctypes.c_void_p(s.cuda_stream))
+
+    def append(self, problem, k_new, v_new, stream=None):
+        """Enqueues the KV append of one token per sequence (k_new, v_new: bf16 tensors [B, Hkv, D])."""
+        import torch
+        s = stream if stream is not None else torch.cuda.current_stream(self.device_ordinal)
+        rollout_attn_append(self.ctx, problem, _ptr(k_new), _ptr(v_new), ctypes.c_void_p(s.cuda_stream))
 
     def debug_gather(self, problem, b, kv_head, k_out, v_out, stream=None):
         import torch

@@ -353,6 +353,27 @@ ra_status rollout_attn_debug_gather(ra_ctx *c, const ra_problem *p, int32_t b, i
     return RA_OK;
 }
 
+ra_status rollout_attn_append(ra_ctx *c, const ra_problem *p, const void *k_new, const void *v_new, void *stream)
+{
+    if (!c) { set_err(nullptr, "ctx is NULL"); return RA_ERR_INVALID_ARG; }
+    ra_status st = check(p, c->err, sizeof c->err);
+    if (st != RA_OK) return st;
+    if (p->B == 0) return RA_OK;
+    if (!k_new || !v_new || (((uintptr_t)k_new | (uintptr_t)v_new) & 3)) {
+        set_err(c, "append: k_new and v_new must be non-NULL and 4-byte aligned");
+        return RA_ERR_INVALID_ARG;
+    }
+    ra::Launch a;
+    fill_launch(a, c, p);
+    int prev = 0;
+    hipError_t e = hipGetDevice(&prev);
+    if (e == hipSuccess && prev != c->device) e = hipSetDevice(c->device);
+    if (e == hipSuccess) e = ra::launch_append(a, k_new, v_new, (hipStream_t)stream);
+    if (prev != c->device) (void)hipSetDevice(prev);
+    if (e != hipSuccess) { set_err(c, "HIP: %s", hipGetErrorString(e)); return RA_ERR_DEVICE; }
+    return RA_OK;
+}
+
 ra_status rollout_attn_set_timing(ra_ctx *c, int enable)
 {
     if (!c) { set_err(nullptr, "ctx is NULL"); return RA_ERR_INVALID_ARG; }

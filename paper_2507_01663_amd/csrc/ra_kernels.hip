@@ -1265,6 +1265,113 @@ hipError_t launch_merge(const Launch &a, hipStream_t s)
 }
 
 // ------------------------------------------------------------------------------------------------------
+// KV append: one new token per sequence into its page (the write before a decode step's attention).
+// One wave per (sequence, kv head) writes the K row and the V row.  e4m3 pools quantise on write and keep
+// the per-(page, head) scale: a row that fits the page's range uses the page's scale; a larger one sets a
+// new scale and the page's stored rows are re-quantised to it.  All of it in binary32, every operation
+// rounded once, so the codes are decided exactly as the format's definition says.
+// ------------------------------------------------------------------------------------------------------
+
+// E4M3 value of a code (exact in binary32).  S.1111.111 is NaN.
+__device__ __forceinline__ float e4m3_value(uint32_t c)
+{
+    const int e = (c >> 3) & 15, m = c & 7;
+    float v = e ? ldexpf(1.0f + 0.125f * (float)m, e - 7) : 0.001953125f * (float)m;
+    if (e == 15 && m == 7) v = __uint_as_float(0x7fc00000u);
+    return (c & 0x80) ? -v : v;
+}
+
+// Nearest E4M3 code of z: ties to the even code, saturating at +-448, NaN -> 0x7F.
+__device__ __forceinline__ uint32_t e4m3_nearest(float z)
+{
+    uint32_t u = __float_as_uint(z);
+    const uint32_t sign = (u >> 24) & 0x80;
+    u &= 0x7fffffffu;
+    if (u > 0x7f800000u) return 0x7f;
+    const float a = __uint_as_float(u);
+    if (a >= 448.0f) return sign | 0x7e;
+    if (a < 0.015625f) return sign | (uint32_t)rintf(a * 512.0f); // steps of 2^-9 below 2^-6; 8 steps are 2^-6 itself
+    u += 0x7ffffu + ((u >> 20) & 1); // keep three mantissa bits, round half to even (a carry moves to the next binade)
+    const uint32_t code = ((((u >> 23) - 127 + 7) << 3) | ((u >> 20) & 7));
+    return sign | (code > 0x7e ? 0x7e : code);
+}
+
+template <int EPL> // elements per lane: D / 64
+__device__ __forceinline__ void append_row(const Launch &a, uint8_t *tile, float *scale_ptr, int slot, const uint16_t *row, int lane)
+{
+    float x[EPL];
+    uint16_t bits[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; e++) {
+        bits[e] = row[EPL * lane + e];
+        x[e] = __uint_as_float((uint32_t)bits[e] << 16);
+    }
+    if (!a.kv_fp8) {
+        uint16_t *dst = (uint16_t *)(tile + (int64_t)slot * a.stride_token_b) + EPL * lane;
+#pragma unroll
+        for (int e = 0; e < EPL; e++) dst[e] = bits[e];
+        return;
+    }
+    float amax = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; e++) amax = fmaxf(amax, fabsf(x[e]));
+#pragma unroll
+    for (int d = 32; d; d >>= 1) amax = fmaxf(amax, __shfl_xor(amax, d));
+    float s;
+    if (slot == 0) {
+        s = amax > 0.f ? amax / 448.0f : 1.0f;
+    } else {
+        const float old = *scale_ptr;
+        if (amax <= old * 448.0f) {
+            s = old;
+        } else {
+            s = amax / 448.0f;
+            for (int j = 0; j < slot; j++) {
+                uint8_t *p = tile + (int64_t)j * a.stride_token_b + EPL * lane;
+#pragma unroll
+                for (int e = 0; e < EPL; e++) {
+                    const float y = e4m3_value(p[e]) * old;
+                    p[e] = (uint8_t)e4m3_nearest(y / s);
+                }
+            }
+        }
+    }
+    uint8_t *dst = tile + (int64_t)slot * a.stride_token_b + EPL * lane;
+#pragma unroll
+    for (int e = 0; e < EPL; e++) dst[e] = (uint8_t)e4m3_nearest(x[e] / s);
+    if (lane == 0) *scale_ptr = s;
+}
+
+__global__ __launch_bounds__(64) void append_kernel(Launch a, const uint16_t *__restrict__ k_new, const uint16_t *__restrict__ v_new)
+{
+    const int item = blockIdx.x, b = item / a.Hkv, kvh = item - b * a.Hkv, lane = threadIdx.x;
+    const int L = a.seq_lens[b];
+    if (L < 0 || L >= a.max_pages * kPage) return; // no room in the table row: skipped
+    const int pg = a.block_table[(int64_t)b * a.max_pages + L / kPage];
+    if (pg < 0 || pg >= a.num_pages) return;       // never write outside the pool
+    const int slot = L % kPage;
+    const int64_t off = (int64_t)pg * a.stride_page_b + (int64_t)kvh * a.stride_head_b;
+    const uint16_t *kr = k_new + (int64_t)item * a.D, *vr = v_new + (int64_t)item * a.D;
+    float *ks = const_cast<float *>(a.k_scale) + (int64_t)pg * a.Hkv + kvh;
+    float *vs = const_cast<float *>(a.v_scale) + (int64_t)pg * a.Hkv + kvh;
+    uint8_t *kt = const_cast<uint8_t *>(a.k_pool) + off, *vt = const_cast<uint8_t *>(a.v_pool) + off;
+    if (a.D == 128) {
+        append_row<2>(a, kt, ks, slot, kr, lane);
+        append_row<2>(a, vt, vs, slot, vr, lane);
+    } else {
+        append_row<1>(a, kt, ks, slot, kr, lane);
+        append_row<1>(a, vt, vs, slot, vr, lane);
+    }
+}
+
+hipError_t launch_append(const Launch &a, const void *k_new, const void *v_new, hipStream_t s)
+{
+    if (a.B == 0) return hipSuccess;
+    hipLaunchKernelGGL(append_kernel, dim3(a.B * a.Hkv), dim3(64), 0, s, a, (const uint16_t *)k_new, (const uint16_t *)v_new);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------------
 // gather (debug / parity of the page arithmetic) and validation
 // ------------------------------------------------------------------------------------------------------
 
