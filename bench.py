@@ -57,6 +57,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sharing", action="store_true", help="ignore the prompt-group hint (A/B)")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run three 1 GiB device copies (counter calibration)")
+    ap.add_argument("--weight-copy", action="store_true",
+                    help="stream host-to-device copies on a second stream during the timed steps (the device-visible side "
+                         "of an asynchronous weight update) and report both rates")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: one GPU only. Sequences are independent, so the path shards over GPUs with no exchange "
@@ -120,10 +123,32 @@ def main():
 
     run(args.warmup)
     torch.cuda.synchronize()
+    copy_info = None
+    if args.weight_copy:
+        # enough 256 MiB host-to-device copies, queued on a stream of their own (default priority), to outlast the steps
+        chunk = 1 << 28
+        host = torch.empty(chunk, dtype=torch.uint8, pin_memory=True)
+        dev_w = torch.empty(chunk, dtype=torch.uint8, device="cuda:0")
+        side = torch.cuda.Stream(device=0)
+        t_est = args.steps * 0.3e-3 if cfg["resp"] != "stream" and args.workload != "tail32b" else args.steps * 2.5e-3
+        ncopies = max(4, int(t_est * 60e9 / chunk) + 4)
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(side):
+            c0.record(side)
+            for _ in range(ncopies):
+                dev_w.copy_(host, non_blocking=True)
+            c1.record(side)
     t0 = time.perf_counter()
     run(args.steps)
-    torch.cuda.synchronize()
+    stream.synchronize()
     wall = time.perf_counter() - t0
+    if args.weight_copy:
+        torch.cuda.synchronize()
+        copy_s = c0.elapsed_time(c1) * 1e-3
+        copy_info = {"host_to_device_GBps": round(ncopies * chunk / copy_s / 1e9, 1), "copies": ncopies, "copy_seconds": round(copy_s, 4),
+                     "steps_seconds": round(wall, 4), "note": "the copies ran for the whole of the timed steps" if copy_s >= wall else
+                     "the copies ended before the timed steps did"}
+    torch.cuda.synchronize()
     total_bytes = sum(alg_bytes[i % len(devs)] for i in range(args.steps))
     ms_per_step = wall * 1e3 / args.steps
     gbps = total_bytes / wall / 1e9
@@ -158,6 +183,9 @@ def main():
                      "unit": "GB/s", "frac": round(att_gbps / HBM_PEAK_GBPS, 4),
                      "traffic": recorded_traffic(args.workload)},
     }
+
+    if copy_info:
+        out["weight_copy"] = copy_info
 
     # The KV append that precedes each decode step's attention, timed on its own (it is not part of `value`):
     # all-zero rows, so the pools' contents that the attention reads stay what they were.
