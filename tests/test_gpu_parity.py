@@ -145,6 +145,33 @@ def test_many_members_need_several_prefix_rows(dec):
     compare(*run(dec, p).results(), ref_out, ref_lse, "wide group")
 
 
+def test_batch_beyond_the_schedules_lds_tables(dec):
+    from gpu_util import compare
+    # more sequences (and groups) than the schedule kernels keep in LDS: their tables then live in the workspace
+    ngroups, R = 1100, 2
+    rng = np.random.default_rng(9)
+    resp = rng.integers(0, 40, size=ngroups * R)
+    p = workload.build_problem("large_b", 4, 2, 64, [16] * ngroups, R, resp, seed=9)
+    assert p.B > 2048 and ngroups <= 2048
+    ref_out, ref_lse = oracle.decode(p)
+    compare(*run(dec, p).results(), ref_out, ref_lse, "B = %d" % p.B)
+    compare(*run(dec, p, use_hint=False).results(), ref_out, ref_lse, "B = %d, no hint" % p.B)
+    # and more groups than fit as well
+    ngroups = 2100
+    resp = rng.integers(0, 40, size=ngroups)
+    p = workload.build_problem("large_g", 4, 2, 64, [16] * ngroups, 1, resp, seed=10)
+    ref_out, ref_lse = oracle.decode(p)
+    compare(*run(dec, p).results(), ref_out, ref_lse, "groups = %d" % ngroups)
+
+
+def test_sixteen_query_heads_per_kv_head(dec):
+    from gpu_util import compare
+    for D in (64, 128):
+        p = workload.build_problem("g16", 32, 2, D, [48, 16], 3, [0, 5, 77, 130, 16, 33], seed=12)
+        ref_out, ref_lse = oracle.decode(p)
+        compare(*run(dec, p).results(), ref_out, ref_lse, "G = 16, D = %d" % D)
+
+
 def test_gather_is_bit_exact(dec):
     from gpu_util import DeviceProblem
     for name in ("tiny", "mid32b"):
