@@ -169,6 +169,22 @@ ra_status rollout_attn_debug_gather(ra_ctx *ctx, const ra_problem *problem, int3
 ra_status rollout_attn_append(ra_ctx *ctx, const ra_problem *problem, const void *k_new, const void *v_new,
                               void *hip_stream);
 
+/* Token-balanced dispatch, on the host (no device is touched, no context is needed): deals n items with
+ * weights[i] >= 0 (say, the KV tokens of prompt group i) to k parts (data-parallel ranks, GPUs) so that the
+ * parts' totals are close.  The paper balances its workers' tokens this way, as one-dimensional bin packing
+ * solved with the Karmarkar-Karp algorithm, with equal sample counts for data parallelism and without that
+ * constraint for pipeline stages (Sec. 4.4).  This is the k-way largest differencing method: every item
+ * starts as a partial solution of k sets (itself and k-1 empty ones); the two partial solutions with the
+ * largest spread (largest minus smallest set total) are merged, largest set with smallest, until one is left.
+ * equal_count != 0 starts instead from groups of k consecutive items of the list sorted by decreasing weight,
+ * one item per set, so that every part ends with floor(n/k) or ceil(n/k) items.  Ties are broken by item
+ * index and creation order, so the result is unique: part[i] in [0, k), parts numbered by decreasing total;
+ * part_sums (may be NULL) receives the k totals.  weights, part, part_sums: HOST memory, caller-owned.
+ * RA_ERR_INVALID_ARG for n < 0, k < 1, a negative weight or a missing array; RA_ERR_DEVICE when host memory
+ * runs out. */
+ra_status rollout_attn_balance(const int64_t *weights, int64_t n, int32_t k, int32_t equal_count, int32_t *part,
+                               int64_t *part_sums);
+
 /* Per-kernel timing for benchmarks.  While enabled, rollout_attn_decode records HIP events on its stream
  * around its three phases (schedule, attention, merge); rollout_attn_get_timing waits for the events of the
  * most recent decode call and returns the three durations in milliseconds.  Off by default: the events cost

@@ -71,6 +71,8 @@ def load_library():
                                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
     lib.rollout_attn_append.restype = ctypes.c_int
     lib.rollout_attn_append.argtypes = [ctypes.c_void_p, P(ra_problem), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    lib.rollout_attn_balance.restype = ctypes.c_int
+    lib.rollout_attn_balance.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
     lib.rollout_attn_set_timing.restype = ctypes.c_int
     lib.rollout_attn_set_timing.argtypes = [ctypes.c_void_p, ctypes.c_int]
     lib.rollout_attn_get_timing.restype = ctypes.c_int
@@ -129,6 +131,17 @@ def rollout_attn_debug_gather(ctx, problem, b, kv_head, k_out_ptr, v_out_ptr, ca
 
 def rollout_attn_append(ctx, problem, k_new_ptr, v_new_ptr, hip_stream=None):
     _check(load_library().rollout_attn_append(ctx, ctypes.byref(problem), k_new_ptr, v_new_ptr, hip_stream), ctx)
+
+
+def rollout_attn_balance(weights, k, equal_count=False):
+    """(part, part_sums) as numpy arrays; weights: non-negative integers."""
+    import numpy as np
+    w = np.ascontiguousarray(weights, dtype=np.int64)
+    part = np.empty(w.size, dtype=np.int32)
+    sums = np.empty(max(int(k), 0), dtype=np.int64)
+    _check(load_library().rollout_attn_balance(w.ctypes.data, w.size, int(k), int(bool(equal_count)), part.ctypes.data,
+                                               sums.ctypes.data), None)
+    return part, sums
 
 
 def rollout_attn_set_timing(ctx, enable):
