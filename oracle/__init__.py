@@ -10,7 +10,9 @@ The paper motivates the computation (memory-bound auto-regressive rollout,
 Sec. 2.1.1; groups of responses to one prompt, Sec. 7.1; highly variable
 response lengths, Sec. 7.4) but prints no formula for it; the definition
 used is textbook scaled-dot-product attention with grouped query heads and a
-paged cache, as written out at the top of the C file.
+paged cache, as written out at the top of the C file.  The same C file holds
+the oracle of the KV append (``append`` below); ``oracle/balance.py`` is the
+oracle of the token-balanced dispatch.
 """
 import ctypes
 import os
