@@ -56,6 +56,9 @@ def _lib():
         lib.oracle_threads.restype = ctypes.c_int
         lib.oracle_e4m3_encode.restype = ctypes.c_uint8
         lib.oracle_e4m3_encode.argtypes = [ctypes.c_float]
+        lib.oracle_prefill.restype = ctypes.c_int
+        lib.oracle_prefill.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int,
+                                       ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
         lib.oracle_append.restype = ctypes.c_int
         lib.oracle_append.argtypes = [ctypes.POINTER(_CProblem), ctypes.c_void_p, ctypes.c_void_p]
         _LIB = lib
@@ -196,3 +199,21 @@ def append(p, k_new, v_new):
     vn = np.ascontiguousarray(v_new, dtype=np.uint16)
     assert kn.shape == (m.B, m.Hkv, m.D) and vn.shape == kn.shape
     return int(_lib().oracle_append(ctypes.byref(m.c), kn.ctypes.data, vn.ctypes.data))
+
+
+def prefill(q, k, v, cu_seqlens, softmax_scale, nthreads=0):
+    """Causal attention of packed prompts over themselves (the arithmetic of the prefill that fills a group's
+    shared pages).  q: bf16 bits uint16 [T, Hq, D]; k, v: [T, Hkv, D]; cu_seqlens: int32 [groups + 1].
+    Returns (out float64 [T, Hq, D], lse float64 [T, Hq])."""
+    q = np.ascontiguousarray(q, dtype=np.uint16)
+    k = np.ascontiguousarray(k, dtype=np.uint16)
+    v = np.ascontiguousarray(v, dtype=np.uint16)
+    cu = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    assert k.shape == (T, Hkv, D) and v.shape == k.shape and cu[0] == 0 and cu[-1] == T
+    out = np.empty((T, Hq, D), dtype=np.float64)
+    lse = np.empty((T, Hq), dtype=np.float64)
+    _raise(_lib().oracle_prefill(q.ctypes.data, k.ctypes.data, v.ctypes.data, cu.ctypes.data, cu.size - 1, Hq, Hkv, D,
+                                 float(np.float32(softmax_scale)), out.ctypes.data, lse.ctypes.data, nthreads))
+    return out, lse

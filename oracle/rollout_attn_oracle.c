@@ -383,3 +383,77 @@ int oracle_append(const oracle_problem *p, const uint16_t *k_new, const uint16_t
     }
     return skipped;
 }
+
+/* ------------------------------------------------------------------------
+ * Prompt prefill: the attention of a whole prompt over itself, the step that
+ * fills the pages a prompt group shares before its responses are decoded
+ * (paper Sec. 2.1.1: generation starts from the prompt; Sec. 7.1: several
+ * responses per prompt).  Not defined by the paper; textbook causal
+ * attention, written out:
+ *
+ * Prompts are packed: prompt g has tokens cu[g] .. cu[g+1]-1 of
+ * q [T][Hq][D], k, v [T][Hkv][D] (bf16 bits).  For token t of prompt g at
+ * position i = t - cu[g], head h, kv = floor(h / G):
+ *     s_j  = scale * <q[t,h,:], k[cu[g]+j, kv, :]>        j = 0..i   (causal)
+ *     out[t,h,:] = sum_j softmax(s)_j * v[cu[g]+j, kv, :],  lse[t,h] = ln sum_j exp(s_j)
+ * in fp64, two passes, no tiling.  Writing K and V into the group's pages is
+ * a copy (bf16) or the whole-page quantisation the input generator uses
+ * (e4m3) and is checked by the tests directly; this function is the
+ * arithmetic.
+ * ------------------------------------------------------------------------ */
+int oracle_prefill(const uint16_t *q, const uint16_t *k, const uint16_t *v, const int32_t *cu, int ngroups, int Hq, int Hkv,
+                   int D, float softmax_scale, double *out, double *lse, int nthreads)
+{
+    if (ngroups < 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || Hq % Hkv)
+        return 1;
+    const int G = Hq / Hkv;
+    const double scale = (double)softmax_scale;
+    int rc = 0;
+#ifdef _OPENMP
+    if (nthreads > 0)
+        omp_set_num_threads(nthreads);
+#else
+    (void)nthreads;
+#endif
+    for (int g = 0; g < ngroups; g++) {
+        const int t0 = cu[g], t1 = cu[g + 1];
+        if (t1 < t0) {
+            rc = 1;
+            continue;
+        }
+#pragma omp parallel for schedule(dynamic, 8) collapse(2)
+        for (int t = t0; t < t1; t++)
+            for (int h = 0; h < Hq; h++) {
+                const int kv = h / G, n = t - t0 + 1;
+                double *s = (double *)malloc((size_t)n * sizeof(double));
+                if (!s)
+                    continue;
+                const uint16_t *qr = q + ((int64_t)t * Hq + h) * D;
+                double M = -INFINITY;
+                for (int j = 0; j < n; j++) {
+                    const uint16_t *kr = k + ((int64_t)(t0 + j) * Hkv + kv) * D;
+                    double acc = 0.0;
+                    for (int d = 0; d < D; d++)
+                        acc += bf16_to_f64(qr[d]) * bf16_to_f64(kr[d]);
+                    s[j] = scale * acc;
+                    if (s[j] > M)
+                        M = s[j];
+                }
+                double Z = 0.0;
+                for (int j = 0; j < n; j++)
+                    Z += exp(s[j] - M);
+                double *o = out + ((int64_t)t * Hq + h) * D;
+                for (int d = 0; d < D; d++)
+                    o[d] = 0.0;
+                for (int j = 0; j < n; j++) {
+                    const double p = exp(s[j] - M) / Z;
+                    const uint16_t *vr = v + ((int64_t)(t0 + j) * Hkv + kv) * D;
+                    for (int d = 0; d < D; d++)
+                        o[d] += p * bf16_to_f64(vr[d]);
+                }
+                lse[(int64_t)t * Hq + h] = M + log(Z);
+                free(s);
+            }
+    }
+    return rc;
+}
