@@ -147,6 +147,26 @@ ra_status rollout_attn_decode(ra_ctx *ctx, const ra_problem *problem, void *work
 ra_status rollout_attn_debug_gather(ra_ctx *ctx, const ra_problem *problem, int32_t b, int32_t kv_head,
                                     void *k_out, void *v_out, int64_t capacity_tokens, void *hip_stream);
 
+/* Where rollout_attn_debug_schedule left the schedule in the workspace (byte offsets from its start). */
+typedef struct {
+    int64_t header_offset;      /* int32[16]: [0] cost units of the stream, [2] work rows, [3] of which shared-prefix
+                                   rows, [7] spans */
+    int64_t work_list_offset;   /* chunks of 8 records of 8 int32; chunk c < spans starts span c's list; record 0 of a
+                                   chunk is {segments in the chunk, next chunk or -1}; a segment record is {index of the
+                                   row's first page id in its table, first page, end page, token limit, kv head |
+                                   shared << 16, sequence or first member slot, query rows, partial slot} */
+    int64_t merge_desc_offset;  /* per (sequence, kv head) two int32[4]: {pages, first span, last span, 0} of the
+                                   sequence's own pages and of its group's shared pages (first > last: none) */
+    int32_t waves;              /* resident attention waves = static spans */
+    int32_t segments_per_chunk;
+} ra_schedule_info;
+
+/* Runs only the schedule kernels of rollout_attn_decode (same arguments) and reports where their results lie in
+ * the workspace, for tests of the schedule's invariants: every page of every (work row, kv head) item belongs
+ * to exactly one span's list, in order, and the merge descriptors name exactly the spans that hold them. */
+ra_status rollout_attn_debug_schedule(ra_ctx *ctx, const ra_problem *problem, void *workspace, size_t workspace_bytes,
+                                      void *hip_stream, ra_schedule_info *info);
+
 /* KV append: writes one new token per sequence into the paged cache, the step that precedes the attention
  * of a decode iteration (auto-regressive generation: paper Sec. 2.1.1; the paper does not define the write,
  * this header does).  For every sequence b the token goes to position L = seq_lens[b], the length BEFORE the

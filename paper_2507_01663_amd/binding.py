@@ -69,6 +69,9 @@ def load_library():
     lib.rollout_attn_debug_gather.restype = ctypes.c_int
     lib.rollout_attn_debug_gather.argtypes = [ctypes.c_void_p, P(ra_problem), ctypes.c_int32, ctypes.c_int32,
                                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+    lib.rollout_attn_debug_schedule.restype = ctypes.c_int
+    lib.rollout_attn_debug_schedule.argtypes = [ctypes.c_void_p, P(ra_problem), ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
+                                                P(ra_schedule_info)]
     lib.rollout_attn_append.restype = ctypes.c_int
     lib.rollout_attn_append.argtypes = [ctypes.c_void_p, P(ra_problem), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     lib.rollout_attn_balance.restype = ctypes.c_int
@@ -127,6 +130,13 @@ def rollout_attn_decode(ctx, problem, workspace_ptr, workspace_bytes, hip_stream
 def rollout_attn_debug_gather(ctx, problem, b, kv_head, k_out_ptr, v_out_ptr, capacity_tokens, hip_stream=None):
     _check(load_library().rollout_attn_debug_gather(ctx, ctypes.byref(problem), b, kv_head, k_out_ptr, v_out_ptr,
                                                     capacity_tokens, hip_stream), ctx)
+
+
+def rollout_attn_debug_schedule(ctx, problem, workspace_ptr, workspace_bytes, hip_stream=None):
+    info = ra_schedule_info()
+    _check(load_library().rollout_attn_debug_schedule(ctx, ctypes.byref(problem), workspace_ptr, workspace_bytes, hip_stream,
+                                                      ctypes.byref(info)), ctx)
+    return info
 
 
 def rollout_attn_append(ctx, problem, k_new_ptr, v_new_ptr, hip_stream=None):
@@ -190,6 +200,11 @@ def problem_from_tensors(q, k_pool, v_pool, block_table, seq_lens, out, lse, sof
     return p
 
 
+class ra_schedule_info(ctypes.Structure):
+    _fields_ = [("header_offset", ctypes.c_int64), ("work_list_offset", ctypes.c_int64), ("merge_desc_offset", ctypes.c_int64),
+                ("waves", ctypes.c_int32), ("segments_per_chunk", ctypes.c_int32)]
+
+
 class Decoder:
     """A context plus a cached workspace tensor on one device."""
 
@@ -222,6 +237,14 @@ class Decoder:
         ws = self.workspace(problem)
         s = stream if stream is not None else torch.cuda.current_stream(self.device_ordinal)
         rollout_attn_decode(self.ctx, problem, ctypes.c_void_p(ws.data_ptr()), ws.numel(), ctypes.c_void_p(s.cuda_stream))
+
+    def schedule(self, problem, stream=None):
+        """Runs only the schedule; returns (ra_schedule_info, the workspace tensor it was written to)."""
+        import torch
+        ws = self.workspace(problem)
+        s = stream if stream is not None else torch.cuda.current_stream(self.device_ordinal)
+        info = rollout_attn_debug_schedule(self.ctx, problem, ctypes.c_void_p(ws.data_ptr()), ws.numel(), ctypes.c_void_p(s.cuda_stream))
+        return info, ws
 
     def append(self, problem, k_new, v_new, stream=None):
         """Enqueues the KV append of one token per sequence (k_new, v_new: bf16 tensors [B, Hkv, D])."""

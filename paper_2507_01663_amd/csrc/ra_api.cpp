@@ -353,6 +353,36 @@ ra_status rollout_attn_debug_gather(ra_ctx *c, const ra_problem *p, int32_t b, i
     return RA_OK;
 }
 
+ra_status rollout_attn_debug_schedule(ra_ctx *c, const ra_problem *p, void *workspace, size_t workspace_bytes, void *stream,
+                                      ra_schedule_info *info)
+{
+    if (!c) { set_err(nullptr, "ctx is NULL"); return RA_ERR_INVALID_ARG; }
+    ra_status st = check(p, c->err, sizeof c->err);
+    if (st != RA_OK) return st;
+    if (!info) { set_err(c, "info is NULL"); return RA_ERR_INVALID_ARG; }
+    ra::Launch a;
+    fill_launch(a, c, p);
+    size_t need = ra::carve_workspace(a.ws, workspace, a.B, a.Hkv, a.G, a.D, a.num_groups, a.waves);
+    if (!workspace || ((uintptr_t)workspace & 255)) { set_err(c, "workspace is NULL or not 256-byte aligned"); return RA_ERR_INVALID_ARG; }
+    if (workspace_bytes < need) {
+        set_err(c, "workspace of %zu bytes given, %zu needed", workspace_bytes, need);
+        return RA_ERR_WORKSPACE_TOO_SMALL;
+    }
+    info->header_offset = (char *)a.ws.hdr - (char *)workspace;
+    info->work_list_offset = (char *)a.ws.seg_rec - (char *)workspace;
+    info->merge_desc_offset = (char *)a.ws.merge_desc - (char *)workspace;
+    info->waves = a.waves;
+    info->segments_per_chunk = ra::kChunkSegs;
+    if (p->B == 0) return RA_OK;
+    int prev = 0;
+    hipError_t e = hipGetDevice(&prev);
+    if (e == hipSuccess && prev != c->device) e = hipSetDevice(c->device);
+    if (e == hipSuccess) e = ra::launch_plan(a, (hipStream_t)stream);
+    if (prev != c->device) (void)hipSetDevice(prev);
+    if (e != hipSuccess) { set_err(c, "HIP: %s", hipGetErrorString(e)); return RA_ERR_DEVICE; }
+    return RA_OK;
+}
+
 ra_status rollout_attn_append(ra_ctx *c, const ra_problem *p, const void *k_new, const void *v_new, void *stream)
 {
     if (!c) { set_err(nullptr, "ctx is NULL"); return RA_ERR_INVALID_ARG; }
