@@ -189,6 +189,56 @@ ra_status rollout_attn_debug_schedule(ra_ctx *ctx, const ra_problem *problem, vo
 ra_status rollout_attn_append(ra_ctx *ctx, const ra_problem *problem, const void *k_new, const void *v_new,
                               void *hip_stream);
 
+/*
+ * Prompt prefill: the step before the first decode step.  The prompts of a batch (one per prompt group when
+ * several responses are sampled per prompt: paper Sec. 7.1) are packed back to back; every prompt token attends
+ * causally to its own prompt, and the prompts' K and V rows are written into the pages that the group's
+ * members then share.  The paper runs this inside its inference engine and does not define it (Sec. 2.1.1);
+ * this header does.  Prompt g holds tokens [cu_seqlens[g], cu_seqlens[g+1]) of the packed arrays; for its token
+ * i (0-based inside the prompt), head h, kv = h / (Hq / Hkv):
+ *     s_j      = softmax_scale * <q[i,h,:], k[j,kv,:]>,  j = 0 .. i
+ *     out[i,h] = sum_j softmax(s)_j * v[j,kv,:]          (bf16)
+ *     lse[i,h] = ln sum_j exp(s_j)                       (fp32, natural log)
+ * Layouts: q, out bf16 [T][Hq][D]; k, v bf16 [T][Hkv][D]; lse fp32 [T][Hq]; all contiguous, 16-byte aligned,
+ * T = total_tokens = cu_seqlens[num_prompts].  cu_seqlens: dev int32 [num_prompts + 1], starts at 0,
+ * non-decreasing.  max_prompt_len is a HOST-side upper bound of every prompt's length (the launch is sized by
+ * it; tokens of a prompt at or past it are not processed).
+ * Cache write (k_pool != NULL): token i of prompt g goes to page pages[page_offsets[g] + i / page_size], slot
+ * i % page_size, every kv head, of pools laid out as in ra_problem (same strides, kv_dtype, scales); a prompt
+ * with more tokens than its pages hold has the rest left unwritten, and so has a page id outside
+ * [0, num_pages).  No page may be listed twice.  bf16 pools take the bit patterns.  e4m3 pools are quantised
+ * one (page, kv head) at a time in IEEE binary32: scale = (largest |x| among the rows written to the page) /
+ * 448, or 1 when that is 0; code = nearest E4M3 of x / scale, ties to the even code; slots of a last, partly
+ * filled page that receive no token are left as they were.
+ * Supported: page_size == 16; D in {64, 128}; Hq % Hkv == 0.  total_tokens * Hq * D < 2^40.
+ */
+typedef struct {
+    int32_t num_prompts, total_tokens, max_prompt_len;
+    int32_t Hq, Hkv, D;
+    const void *q;               /* dev */
+    const void *k;               /* dev */
+    const void *v;               /* dev */
+    const int32_t *cu_seqlens;   /* dev */
+    float softmax_scale;
+    void *out;                   /* dev */
+    float *lse;                  /* dev */
+    /* cache write; k_pool == NULL: none, and the fields below are not read */
+    void *k_pool;                /* dev or NULL */
+    void *v_pool;                /* dev */
+    int32_t page_size, num_pages;
+    int64_t kv_stride_page, kv_stride_head, kv_stride_token; /* in elements */
+    int32_t kv_dtype;            /* ra_kv_dtype */
+    float *k_scale;              /* dev, fp32 [num_pages][Hkv]; NULL unless fp8 */
+    float *v_scale;
+    const int32_t *page_offsets; /* dev int32 [num_prompts + 1] */
+    const int32_t *pages;        /* dev int32 [page_offsets[num_prompts]] */
+} ra_prefill;
+
+/* Enqueues the cache write (if asked for) and the causal attention of the packed prompts on hip_stream and
+ * returns without waiting.  Needs no workspace.  Deterministic.  RA_ERR_INVALID_ARG / RA_ERR_UNSUPPORTED as
+ * for rollout_attn_decode; nothing is enqueued then. */
+ra_status rollout_attn_prefill(ra_ctx *ctx, const ra_prefill *prefill, void *hip_stream);
+
 /* Token-balanced dispatch, on the host (no device is touched, no context is needed): deals n items with
  * weights[i] >= 0 (say, the KV tokens of prompt group i) to k parts (data-parallel ranks, GPUs) so that the
  * parts' totals are close.  The paper balances its workers' tokens this way, as one-dimensional bin packing

@@ -38,6 +38,22 @@ class ra_problem(ctypes.Structure):
     ]
 
 
+class ra_prefill(ctypes.Structure):
+    _fields_ = [
+        ("num_prompts", ctypes.c_int32), ("total_tokens", ctypes.c_int32), ("max_prompt_len", ctypes.c_int32),
+        ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32), ("D", ctypes.c_int32),
+        ("q", ctypes.c_void_p), ("k", ctypes.c_void_p), ("v", ctypes.c_void_p), ("cu_seqlens", ctypes.c_void_p),
+        ("softmax_scale", ctypes.c_float),
+        ("out", ctypes.c_void_p), ("lse", ctypes.c_void_p),
+        ("k_pool", ctypes.c_void_p), ("v_pool", ctypes.c_void_p),
+        ("page_size", ctypes.c_int32), ("num_pages", ctypes.c_int32),
+        ("kv_stride_page", ctypes.c_int64), ("kv_stride_head", ctypes.c_int64), ("kv_stride_token", ctypes.c_int64),
+        ("kv_dtype", ctypes.c_int32),
+        ("k_scale", ctypes.c_void_p), ("v_scale", ctypes.c_void_p),
+        ("page_offsets", ctypes.c_void_p), ("pages", ctypes.c_void_p),
+    ]
+
+
 def library_path():
     return _LIB_PATH
 
@@ -74,6 +90,8 @@ def load_library():
                                                 P(ra_schedule_info)]
     lib.rollout_attn_append.restype = ctypes.c_int
     lib.rollout_attn_append.argtypes = [ctypes.c_void_p, P(ra_problem), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    lib.rollout_attn_prefill.restype = ctypes.c_int
+    lib.rollout_attn_prefill.argtypes = [ctypes.c_void_p, P(ra_prefill), ctypes.c_void_p]
     lib.rollout_attn_balance.restype = ctypes.c_int
     lib.rollout_attn_balance.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
     lib.rollout_attn_set_timing.restype = ctypes.c_int
@@ -143,6 +161,10 @@ def rollout_attn_append(ctx, problem, k_new_ptr, v_new_ptr, hip_stream=None):
     _check(load_library().rollout_attn_append(ctx, ctypes.byref(problem), k_new_ptr, v_new_ptr, hip_stream), ctx)
 
 
+def rollout_attn_prefill(ctx, prefill, hip_stream=None):
+    _check(load_library().rollout_attn_prefill(ctx, ctypes.byref(prefill), hip_stream), ctx)
+
+
 def rollout_attn_balance(weights, k, equal_count=False):
     """(part, part_sums) as numpy arrays; weights: non-negative integers."""
     import numpy as np
@@ -200,6 +222,35 @@ def problem_from_tensors(q, k_pool, v_pool, block_table, seq_lens, out, lse, sof
     return p
 
 
+def prefill_from_tensors(q, k, v, cu_seqlens, max_prompt_len, out, lse, softmax_scale, k_pool=None, v_pool=None, k_scale=None,
+                         v_scale=None, page_offsets=None, pages=None):
+    """Fills a ra_prefill from device tensors: q/out bf16 [T,Hq,D]; k/v bf16 [T,Hkv,D]; cu_seqlens int32 [n+1];
+    lse float32 [T,Hq]; optionally the pools [num_pages,Hkv,page,D] (bf16 or uint8) and the prompts' page lists."""
+    import torch
+    for t in (q, k, v, out, lse, cu_seqlens):
+        assert t.is_contiguous()
+    assert q.dtype == k.dtype == v.dtype == out.dtype == torch.bfloat16 and lse.dtype == torch.float32
+    assert cu_seqlens.dtype == torch.int32 and k.shape == v.shape and q.shape == out.shape
+    p = ra_prefill()
+    p.total_tokens, p.Hq, p.D = q.shape
+    p.Hkv = k.shape[1]
+    p.num_prompts = cu_seqlens.numel() - 1
+    p.max_prompt_len = int(max_prompt_len)
+    p.q, p.k, p.v, p.cu_seqlens = _ptr(q), _ptr(k), _ptr(v), _ptr(cu_seqlens)
+    p.softmax_scale = float(softmax_scale)
+    p.out, p.lse = _ptr(out), _ptr(lse)
+    if k_pool is not None:
+        assert k_pool.stride() == v_pool.stride() and k_pool.stride(3) == 1
+        assert page_offsets.dtype == torch.int32 and pages.dtype == torch.int32
+        p.k_pool, p.v_pool = _ptr(k_pool), _ptr(v_pool)
+        p.num_pages, _, p.page_size, _ = k_pool.shape
+        p.kv_stride_page, p.kv_stride_head, p.kv_stride_token = k_pool.stride(0), k_pool.stride(1), k_pool.stride(2)
+        p.kv_dtype = RA_KV_FP8_E4M3 if k_pool.element_size() == 1 else RA_KV_BF16
+        p.k_scale, p.v_scale = _ptr(k_scale), _ptr(v_scale)
+        p.page_offsets, p.pages = _ptr(page_offsets), _ptr(pages)
+    return p
+
+
 class ra_schedule_info(ctypes.Structure):
     _fields_ = [("header_offset", ctypes.c_int64), ("work_list_offset", ctypes.c_int64), ("merge_desc_offset", ctypes.c_int64),
                 ("waves", ctypes.c_int32), ("segments_per_chunk", ctypes.c_int32)]
@@ -251,6 +302,12 @@ class Decoder:
         import torch
         s = stream if stream is not None else torch.cuda.current_stream(self.device_ordinal)
         rollout_attn_append(self.ctx, problem, _ptr(k_new), _ptr(v_new), ctypes.c_void_p(s.cuda_stream))
+
+    def prefill(self, prefill, stream=None):
+        """Enqueues the prompts' causal attention (and the cache write, if the ra_prefill names pools)."""
+        import torch
+        s = stream if stream is not None else torch.cuda.current_stream(self.device_ordinal)
+        rollout_attn_prefill(self.ctx, prefill, ctypes.c_void_p(s.cuda_stream))
 
     def debug_gather(self, problem, b, kv_head, k_out, v_out, stream=None):
         import torch

@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librollout_attn.so")
-SOURCES = ["ra_kernels.hip", "ra_api.cpp", "ra_balance.cpp"]
+SOURCES = ["ra_kernels.hip", "ra_prefill.hip", "ra_api.cpp", "ra_balance.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-mllvm", "-amdgpu-mfma-vgpr-form=1",

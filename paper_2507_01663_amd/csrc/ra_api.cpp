@@ -404,6 +404,69 @@ ra_status rollout_attn_append(ra_ctx *c, const ra_problem *p, const void *k_new,
     return RA_OK;
 }
 
+ra_status rollout_attn_prefill(ra_ctx *c, const ra_prefill *p, void *stream)
+{
+    if (!c) { set_err(nullptr, "ctx is NULL"); return RA_ERR_INVALID_ARG; }
+    auto fail = [&](ra_status st, const char *fmt, ...) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(c->err, sizeof c->err, fmt, ap);
+        va_end(ap);
+        return st;
+    };
+    if (!p) return fail(RA_ERR_INVALID_ARG, "prefill is NULL");
+    if (p->num_prompts < 0 || p->total_tokens < 0 || p->max_prompt_len < 0 || p->Hq <= 0 || p->Hkv <= 0 || p->D <= 0)
+        return fail(RA_ERR_INVALID_ARG, "negative or zero dimension (num_prompts=%d total_tokens=%d max_prompt_len=%d Hq=%d "
+                                        "Hkv=%d D=%d)", p->num_prompts, p->total_tokens, p->max_prompt_len, p->Hq, p->Hkv, p->D);
+    if (p->Hq % p->Hkv) return fail(RA_ERR_INVALID_ARG, "Hq=%d is not a multiple of Hkv=%d", p->Hq, p->Hkv);
+    if (!std::isfinite(p->softmax_scale) || p->softmax_scale <= 0.f)
+        return fail(RA_ERR_INVALID_ARG, "softmax_scale must be positive and finite");
+    if (p->D != 64 && p->D != 128) return fail(RA_ERR_UNSUPPORTED, "D=%d (only 64 and 128 are supported)", p->D);
+    if ((int64_t)p->total_tokens * p->Hq * p->D >= (int64_t)1 << 40) return fail(RA_ERR_UNSUPPORTED, "batch too large");
+    if (p->num_prompts == 0 || p->total_tokens == 0 || p->max_prompt_len == 0) return RA_OK;
+    if (!p->q || !p->k || !p->v || !p->cu_seqlens || !p->out || !p->lse)
+        return fail(RA_ERR_INVALID_ARG, "a required pointer (q, k, v, cu_seqlens, out, lse) is NULL");
+    if (((uintptr_t)p->q | (uintptr_t)p->k | (uintptr_t)p->v | (uintptr_t)p->out) % 16 || (uintptr_t)p->lse % 4)
+        return fail(RA_ERR_INVALID_ARG, "q, k, v and out must be 16-byte aligned, lse 4-byte aligned");
+    ra::PrefillLaunch a;
+    memset(&a, 0, sizeof a);
+    a.num_prompts = p->num_prompts; a.max_len = p->max_prompt_len; a.Hq = p->Hq; a.Hkv = p->Hkv; a.D = p->D; a.G = p->Hq / p->Hkv;
+    a.q = (const uint16_t *)p->q; a.k = (const uint16_t *)p->k; a.v = (const uint16_t *)p->v;
+    a.cu = p->cu_seqlens;
+    a.scale_log2 = p->softmax_scale * 1.4426950408889634f;
+    a.out = (uint16_t *)p->out; a.lse = p->lse; a.zeros = c->zeros;
+    if (p->k_pool) {
+        if (p->kv_dtype != RA_KV_BF16 && p->kv_dtype != RA_KV_FP8_E4M3)
+            return fail(RA_ERR_INVALID_ARG, "kv_dtype=%d is not a ra_kv_dtype", p->kv_dtype);
+        if (p->page_size != 16) return fail(RA_ERR_UNSUPPORTED, "page_size=%d (only 16 is supported)", p->page_size);
+        const int es = p->kv_dtype == RA_KV_FP8_E4M3 ? 1 : 2;
+        if (!p->v_pool || !p->page_offsets || !p->pages || p->num_pages < 0)
+            return fail(RA_ERR_INVALID_ARG, "the cache write needs v_pool, page_offsets, pages and num_pages >= 0");
+        if (p->kv_stride_token < p->D || p->kv_stride_head < 0 || p->kv_stride_page < 0)
+            return fail(RA_ERR_INVALID_ARG, "kv strides must be non-negative and kv_stride_token >= D");
+        if ((p->kv_stride_token * es) % 16 || (p->kv_stride_head * es) % 16 || (p->kv_stride_page * es) % 16)
+            return fail(RA_ERR_INVALID_ARG, "kv strides must be multiples of 16 bytes");
+        if (p->kv_stride_token * es * 16 > INT32_MAX) return fail(RA_ERR_UNSUPPORTED, "kv_stride_token too large");
+        if (((uintptr_t)p->k_pool | (uintptr_t)p->v_pool) % 16)
+            return fail(RA_ERR_INVALID_ARG, "k_pool and v_pool must be 16-byte aligned");
+        if (es == 1 && (!p->k_scale || !p->v_scale)) return fail(RA_ERR_INVALID_ARG, "fp8 KV needs k_scale and v_scale");
+        a.kv_fp8 = es == 1; a.num_pages = p->num_pages;
+        a.k_pool = (uint8_t *)p->k_pool; a.v_pool = (uint8_t *)p->v_pool;
+        a.stride_page_b = p->kv_stride_page * es; a.stride_head_b = p->kv_stride_head * es;
+        a.stride_token_b = (int32_t)(p->kv_stride_token * es);
+        a.k_scale = p->k_scale; a.v_scale = p->v_scale;
+        a.page_off = p->page_offsets; a.pages = p->pages;
+    }
+    int prev = 0;
+    hipError_t e = hipGetDevice(&prev);
+    if (e == hipSuccess && prev != c->device) e = hipSetDevice(c->device);
+    if (e == hipSuccess && p->k_pool) e = ra::launch_prefill_write(a, (hipStream_t)stream);
+    if (e == hipSuccess) e = ra::launch_prefill(a, (hipStream_t)stream);
+    if (prev != c->device) (void)hipSetDevice(prev);
+    if (e != hipSuccess) { set_err(c, "HIP: %s", hipGetErrorString(e)); return RA_ERR_DEVICE; }
+    return RA_OK;
+}
+
 ra_status rollout_attn_set_timing(ra_ctx *c, int enable)
 {
     if (!c) { set_err(nullptr, "ctx is NULL"); return RA_ERR_INVALID_ARG; }

@@ -1,4 +1,4 @@
-// Internal interface between the C-ABI layer (ra_api.cpp) and the gfx950 kernels (ra_kernels.hip).
+// Internal interface between the C-ABI layer (ra_api.cpp) and the gfx950 kernels (ra_kernels.hip, ra_prefill.hip).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stddef.h>
@@ -56,6 +56,24 @@ struct Launch {
     Workspace ws;
 };
 
+// Prompt prefill: packed prompts, their causal attention, and where their K and V rows go in the cache.
+struct PrefillLaunch {
+    int32_t num_prompts, max_len, Hq, Hkv, D, G;
+    const uint16_t *q, *k, *v;   // bf16 [T][Hq][D], [T][Hkv][D]
+    const int32_t *cu;           // [num_prompts + 1] first token of each prompt
+    float scale_log2;            // softmax_scale * log2(e)
+    uint16_t *out;               // bf16 [T][Hq][D]
+    float *lse;                  // [T][Hq]
+    const void *zeros;           // >= 16 bytes of zeros
+    // cache write (launch_prefill_write)
+    int32_t kv_fp8, num_pages;
+    uint8_t *k_pool, *v_pool;
+    int64_t stride_page_b, stride_head_b; // bytes
+    int32_t stride_token_b;               // bytes
+    float *k_scale, *v_scale;
+    const int32_t *page_off, *pages;      // [num_prompts + 1], [page_off[num_prompts]]
+};
+
 // Upper bound on prefix rows for a shape.
 int prefix_rows_max(int B, int G, int num_groups);
 // Carves the workspace; returns the bytes needed.  base may be null (size query).
@@ -74,6 +92,9 @@ hipError_t launch_attention(const Launch &a, hipStream_t s);
 hipError_t launch_merge(const Launch &a, hipStream_t s);
 // Writes the new K and V rows (bf16 [B][Hkv][D]) at position seq_lens[b] of every sequence; see append_kernel.
 hipError_t launch_append(const Launch &a, const void *k_new, const void *v_new, hipStream_t s);
+// Causal attention of the packed prompts (prefill_kernel) and the write of their K/V rows into pages.
+hipError_t launch_prefill(const PrefillLaunch &a, hipStream_t s);
+hipError_t launch_prefill_write(const PrefillLaunch &a, hipStream_t s);
 hipError_t launch_gather(const Launch &a, int b, int kvh, void *k_out, void *v_out, int64_t cap, hipStream_t s);
 
 } // namespace ra

@@ -35,3 +35,22 @@ def test_no_scratch_and_no_full_drain_in_the_page_loop(isa):
         # the LDS ring is paced by hand-written waits with a non-zero count; they must be there
         assert re.search(r"s_waitcnt vmcnt\([1-9][0-9]*\)", body), name
 
+
+
+def test_prefill_kernels_keep_their_accumulators_in_registers():
+    import tempfile
+    from paper_2507_01663_amd import build
+    with tempfile.TemporaryDirectory() as tmp:
+        out = os.path.join(tmp, "ra_prefill.s")
+        flags = [f for f in build.FLAGS if f not in ("-shared", "-fPIC")]
+        subprocess.run([os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")] + flags + ["-S", "--cuda-device-only", "-o", out,
+                                                                                  os.path.join(build.CSRC, "ra_prefill.hip")],
+                       check=True, stderr=subprocess.DEVNULL)
+        text = open(out).read()
+    found = re.findall(r"^(_ZN2ra14prefill_kernel\w+):.*?s_endpgm", text, flags=re.S | re.M)
+    assert len(found) == 2                                   # D = 64 and D = 128
+    for m in re.finditer(r"^(_ZN2ra14prefill_kernel\w+):(.*?)s_endpgm", text, flags=re.S | re.M):
+        assert "scratch_" not in m.group(2), m.group(1)
+        assert "v_mfma_f32_16x16x32_bf16" in m.group(2), m.group(1)
+        assert re.search(r"s_waitcnt vmcnt\([1-9][0-9]*\)", m.group(2)), m.group(1)
+    assert text.count(".private_segment_fixed_size: 0") == 4  # the two attention and the two cache-write kernels

@@ -336,3 +336,68 @@ def make_problem(config, seed=0, step=0, kv_dtype="bf16", pool=None, num_pages=N
     return build_problem(name, cfg["Hq"], cfg["Hkv"], cfg["D"], prompts, cfg["R"], resp, kv_dtype=kv_dtype,
                          seed=seed, cfg_id=cfg["id"], step=step, poison=not stream, pool=pool,
                          num_pages=num_pages, make_values=make_values)
+
+
+# ----------------------------------------------------------------------------
+# prompt prefill
+# ----------------------------------------------------------------------------
+
+@dataclass
+class PrefillBatch:
+    """Packed prompts for the prefill step: token t of the batch is row t of q
+    ([T, Hq, D]) and of k, v ([T, Hkv, D]), all bf16 bit patterns; prompt g is
+    rows cu_seqlens[g] .. cu_seqlens[g+1]; its pages are
+    pages[page_offsets[g] .. page_offsets[g+1]] of a pool of num_pages."""
+    name: str
+    Hq: int
+    Hkv: int
+    D: int
+    cu_seqlens: np.ndarray
+    q: np.ndarray
+    k: np.ndarray
+    v: np.ndarray
+    softmax_scale: np.float32
+    num_pages: int
+    page_offsets: np.ndarray
+    pages: np.ndarray
+
+    @property
+    def lens(self):
+        return np.diff(self.cu_seqlens).astype(np.int64)
+
+    def causal_pairs(self):
+        """(query, key) pairs of the causal mask, over all prompts."""
+        n = self.lens
+        return int((n * (n + 1) // 2).sum())
+
+    def flops(self):
+        """Multiply-adds of the two products, counted as two operations each."""
+        return 4 * self.D * self.Hq * self.causal_pairs()
+
+
+def build_prefill(name, Hq, Hkv, D, prompt_lens, seed=0, cfg_id=99, slack=1.25):
+    """Prompts of the given lengths with N(0,1) bf16 queries, keys and values, and
+    for each prompt ceil(len / PAGE) distinct pages of a randomly permuted pool."""
+    lens = np.asarray(prompt_lens, dtype=np.int64)
+    cu = np.zeros(lens.size + 1, dtype=np.int32)
+    cu[1:] = np.cumsum(lens)
+    T = int(cu[-1])
+    npg = (lens + PAGE - 1) // PAGE
+    needed = int(npg.sum())
+    num_pages = max(needed + 1, int(math.ceil(slack * needed)))
+    phys = _rng(seed, cfg_id, 0, 5).permutation(num_pages)[:needed].astype(np.int32)
+    off = np.zeros(lens.size + 1, dtype=np.int32)
+    off[1:] = np.cumsum(npg)
+    tid = 500 + cfg_id * 8
+    return PrefillBatch(name=name, Hq=Hq, Hkv=Hkv, D=D, cu_seqlens=cu,
+                        q=normal_bf16(T * Hq * D, seed, tid).reshape(T, Hq, D),
+                        k=normal_bf16(T * Hkv * D, seed, tid + 1).reshape(T, Hkv, D),
+                        v=normal_bf16(T * Hkv * D, seed, tid + 2).reshape(T, Hkv, D),
+                        softmax_scale=np.float32(1.0 / math.sqrt(D)), num_pages=num_pages, page_offsets=off, pages=phys)
+
+
+def make_prefill(config, seed=0, groups=None):
+    """The prompts of a named configuration: one prompt per group, all of the configuration's prompt length."""
+    cfg = CONFIGS[config]
+    n = cfg["groups"] if groups is None else groups
+    return build_prefill(config, cfg["Hq"], cfg["Hkv"], cfg["D"], [cfg["prompt"]] * n, seed=seed, cfg_id=cfg["id"])
