@@ -73,7 +73,7 @@ __device__ __forceinline__ float row_sum(float x)
 
 // LDS placement of 16-byte unit c of tile row r: rows are kept whole, units are XOR-swizzled inside the
 // row so that the 16 rows of an MFMA operand read and the 4 rows of a transposed read spread over banks.
-__device__ __forceinline__ int swz(int r) { return 2 * (r & 3) + ((r >> 2) & 1); }
+__device__ __forceinline__ int swz(int r) { return 2 * (r & 3) + ((r >> 2) & 1) + (r & 8); }
 
 // Geometry of a page in LDS for head dim D and KVB bytes per stored element (2: bf16, 1: e4m3).
 template <int D, int KVB> struct Geo {

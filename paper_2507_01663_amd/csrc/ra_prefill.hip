@@ -2,90 +2,209 @@
 // their K and V rows into the pages of the cache that the decode steps then read (once per prompt group when
 // several responses are sampled for one prompt: paper Sec. 7.1).
 //
-// Unlike the decode step this is a dense contraction, bound by the matrix cores.  A workgroup of four waves
-// takes 256 consecutive query rows of one (prompt, head); the sixteen 16-row query tiles are dealt to the waves
-// round-robin, so that under the causal mask every wave has the same amount of work.  K and V stream through an
-// LDS ring in stages of 32 keys (K0 K1 V0 V1, one 16-key tile loaded by each wave with direct global->LDS
-// loads); every wave multiplies every stage with its own four query tiles, held in registers:
-//   S^T[key, row] = K_tile . Q^T,   O^T[d, row] += V_tiles^T . P^T     (16x16x32 MFMA, fp32 accumulation)
-// with the softmax running per query row in fp32 (base 2), as in the decode kernel, whose tile layout in LDS
-// and operand layouts this kernel shares.
+// Unlike the decode step this is a dense contraction, bound by the matrix cores.  A workgroup of eight waves
+// (two per SIMD, so that one wave's vector work runs while the other's MFMAs do) takes 256 consecutive query
+// rows of one (prompt, head), 32 rows per wave.  K and V stream through an LDS ring in stages of 32 keys (K0 K1
+// V0 V1, half a 16-key tile loaded by each wave with direct global->LDS loads); every wave multiplies every
+// stage with its own query rows, held in registers:
+//   S^T[key, row] = K . Q^T,   O^T[d, row] += V^T . P^T     (32x32x16 MFMA, fp32 accumulation)
+// with the softmax running per query row in fp32 (base 2).  The tile layout in LDS is the decode kernel's.
 #include "ra_device.h"
 
 namespace ra {
 
-constexpr int kPfWaves = 4;                        // waves per workgroup
-constexpr int kPfTiles = 4;                        // 16-row query tiles per wave
-constexpr int kPfBlock = 16 * kPfTiles * kPfWaves; // query rows per workgroup
-constexpr int kPfSlots = 4;                        // ring slots of one stage (32 keys) each
+constexpr int kPfWaves = 8;                  // waves per workgroup, two per SIMD
+constexpr int kPfRows = 32;                  // query rows per wave: one 32x32 MFMA tile
+constexpr int kPfBlock = kPfRows * kPfWaves; // query rows per workgroup
+constexpr int kPfSlots = 6;                  // ring slots of one stage (32 keys) each
 
-// One stage of 32 keys against the query tiles TMIN..3 of a wave.  MASKED: the first of those tiles straddles
-// the diagonal, so its keys beyond the row are dropped; all later tiles lie wholly below it.
-// key0 = index of the stage's first key in the prompt, row0[t] = index of tile t's first row.
-template <int D, int TMIN, bool MASKED>
-__device__ __forceinline__ void prefill_stage(const uint8_t *st, uint32_t st_addr, const LaneConst<D, 2> &lc, float scale_log2,
-                                              int key0, int row0_first, const bf16x8 (&qf)[kPfTiles][D / 32],
-                                              f32x4 (&o)[kPfTiles][D / 16], float (&m)[kPfTiles], float (&lsum)[kPfTiles])
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+// Per-lane constants of the 32x32x16 products.  A lane is (n = lane % 32, hh = lane / 32).  With the tile layout
+// of lane_setup() (rows of D bf16, 16-byte units XOR-swizzled inside the row) every LDS address the step needs is
+// one of two per-lane bases XOR a compile-time constant, as long as stages start at multiples of their size:
+//   K operand of k-step i (key n, d = 16 i + 8 hh .. + 7):          stage + (k_base ^ 32 i)
+//   V operand, d-tile dt, keys 4 hh + 8 rd .. + 3 of tile V0 / V1:  stage + 2 tiles (+ 1) + (v_base ^ 64 dt ^ kVrd rd)
+// the latter through the transposing read, whose 16 lanes address a 4-key x 16-d block, lane a supplying key a / 4,
+// d = 4 (a % 4) .. + 3.
+template <int D> struct PfLane {
+    int k_base, v_base;
+};
+
+template <int D> __device__ __forceinline__ void pf_lane_setup(PfLane<D> &pl, int lane)
 {
     using G = Geo<D, 2>;
-    const int lane = threadIdx.x & 63, j = lane >> 4;
-    f32x4 s[kPfTiles][2];
-#pragma unroll
-    for (int pg = 0; pg < 2; pg++) {
-#pragma unroll
-        for (int t = TMIN; t < kPfTiles; t++) s[t][pg] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int i = 0; i < G::kKReads; i++) {
-            const bf16x8 kf = *(const bf16x8 *)(st + pg * G::kTile + lc.k_off[i]);
-#pragma unroll
-            for (int t = TMIN; t < kPfTiles; t++) s[t][pg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[t][i], s[t][pg], 0, 0, 0);
-        }
-    }
-    bf16x8 pf[kPfTiles];
-#pragma unroll
-    for (int t = TMIN; t < kPfTiles; t++) {
-        float v[8];
-#pragma unroll
-        for (int e = 0; e < 4; e++) {
-            v[e] = s[t][0][e];
-            v[4 + e] = s[t][1][e];
-        }
-        if (MASKED && t == TMIN) {
-            // this lane's row, and its keys 4j+e of the two 16-key tiles
-            const int row = row0_first + (lane & 15), k = key0 + 4 * j;
-#pragma unroll
-            for (int e = 0; e < 4; e++) {
-                if (k + e > row) v[e] = -INFINITY;
-                if (k + kPage + e > row) v[4 + e] = -INFINITY;
-            }
-        }
-        // the scale is positive, so the maximum may be taken before it is applied
-        const float mx = row_max(fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7]))));
-        const float mn = fmaxf(m[t], mx * scale_log2);
-        f32x8 p;
-#pragma unroll
-        for (int e = 0; e < 8; e++) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(v[e], scale_log2, -mn));
-        const float ps = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
-        pf[t] = __builtin_convertvector(p, bf16x8);
-        if (__any(mn != m[t])) {
-            const float alpha = __builtin_amdgcn_exp2f(m[t] - mn);
-            m[t] = mn;
-            lsum[t] *= alpha;
-#pragma unroll
-            for (int dt = 0; dt < G::kDTiles; dt++) o[t][dt] *= alpha;
-        }
-        lsum[t] += ps;
-    }
+    constexpr int UM = G::kUnits - 1;
+    const int n = lane & 31, hh = lane >> 5;
+    const int r = n & 15;
+    // unit (2 i + hh) ^ swz(r) = 2 i ^ (swz(r) ^ hh)
+    pl.k_base = (n >> 4) * G::kTile + G::kRowBytes * r + 16 * ((swz(r) & UM) ^ hh);
+    const int a = lane & 15, dh = (lane >> 4) & 1;
+    const int vrow = 4 * hh + (a >> 2);           // + 8 rd
+    const int c = 2 * dh + ((a >> 1) & 1);        // + 4 dt
+    pl.v_base = G::kRowBytes * vrow + 16 * (c ^ (swz(vrow) & UM)) + 8 * (a & 1);
+}
+template <int D> __device__ __forceinline__ int pf_k_off(const PfLane<D> &pl, int i) { return pl.k_base ^ (32 * i); }
+template <int D> __device__ __forceinline__ int pf_v_off(const PfLane<D> &pl, int dt, int rd)
+{
+    // eight rows further on; with sixteen units per row the swizzle of those rows differs in its top bit
+    constexpr int kVrd = 8 * Geo<D, 2>::kRowBytes + (Geo<D, 2>::kUnits == 16 ? 128 : 0);
+    return pl.v_base ^ ((64 * dt) ^ (kVrd * rd));
+}
+
+template <int D> struct PfState {
+    bf16x8 qf[D / 16]; // Q^T operand of k-step i: row n, d = 16 i + 8 hh .. + 7
+    f32x16 o[D / 32];  // O^T accumulators: element e of d-tile dt is d = 32 dt + 8 (e / 4) + 4 hh + e % 4, row n
+    f32x16 s;          // scores of the stage whose weights are computed next: element e is key 8 (e / 4) + 4 hh + e % 4
+    float m, lsum;     // reference point of the exponent (same in both lanes of a row); this lane's part of the row sum
+};
+
+__device__ __forceinline__ float max3(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+constexpr float kPfSlack = 8.0f;
+
+// One step of a wave's software pipeline (see the kernel): weights of stage s and scores of stage s + 1 (NEXT; MASK:
+// that stage is the wave's diagonal one), then O += P V of stage s and the row maxima of the new scores.
+template <int D, bool MASK, bool NEXT>
+__device__ __forceinline__ void pf_step(PfState<D> &st, const uint8_t *k_next, uint32_t v_addr, const PfLane<D> &pl,
+                                        float scale_log2, int key_next, int row)
+{
+    using G = Geo<D, 2>;
     typedef s16x4 __attribute__((address_space(3))) * lds_s16x4;
     typedef short s16x8 __attribute__((ext_vector_type(8)));
-    const uint32_t vb = st_addr + 2 * G::kTile;
+    const int hh = (threadIdx.x & 63) >> 5;
+    constexpr int KS = D / 16, DT = D / 32;
+#define PF_FENCE() __builtin_amdgcn_sched_barrier(0)
+    PF_FENCE();
+    // K operands are read four products ahead of their use
+    constexpr int KA = KS < 4 ? KS : 4;
+    bf16x8 kf[KS];
+    if (NEXT) {
 #pragma unroll
-    for (int dt = 0; dt < G::kDTiles; dt++) {
-        const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(vb + lc.v_off[dt]));
-        const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(vb + G::kTile + lc.v_off[dt]));
-        const bf16x8 vf = __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7));
+        for (int i = 0; i < KA; i++) kf[i] = *(const bf16x8 *)(k_next + pf_k_off(pl, i));
+    }
+    s16x4 vr[DT][2][2];
+    auto v_read = [&](int dt, int kk) {
+        vr[dt][kk][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(v_addr + kk * G::kTile + pf_v_off(pl, dt, 0)));
+        vr[dt][kk][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(v_addr + kk * G::kTile + pf_v_off(pl, dt, 1)));
+    };
+    PF_FENCE();
+    // weights: item k < 16: element k (exponential, running sum, and with every second one the rounding of a pair to
+    // bf16); item 16: the row sum
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    u32x4 pw[2];
+    float pprev = 0.f, acc0 = 0.f, acc1 = 0.f;
+    auto w_item = [&](int k) {
+        if (k < 16) {
+            const float pk = __builtin_amdgcn_exp2f(__builtin_fmaf(st.s[k], scale_log2, -st.m));
+            if (k & 1) {
+                acc1 += pk;
+                pw[k >> 3][(k >> 1) & 3] = __builtin_bit_cast(unsigned, __builtin_convertvector((f32x2{pprev, pk}), bf16x2));
+            } else {
+                acc0 += pk;
+                pprev = pk;
+            }
+        } else {
+            st.lsum += acc0 + acc1;
+        }
+    };
+    constexpr int NW = 17;
+    f32x16 sn;
+    if (NEXT) {
+        // the first weights cover the latency of the K reads
 #pragma unroll
-        for (int t = TMIN; t < kPfTiles; t++) o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[t], o[t][dt], 0, 0, 0);
+        for (int k = 0; k < 3; k++) w_item(k);
+        PF_FENCE();
+#pragma unroll
+        for (int i = 0; i < KS; i++) {
+            if (i == 0) {
+#pragma unroll
+                for (int e = 0; e < 16; e++) sn[e] = 0.f;
+            }
+            sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], st.qf[i], sn, 0, 0, 0);
+            if (i + KA < KS) kf[i + KA] = *(const bf16x8 *)(k_next + pf_k_off(pl, i + KA));
+#pragma unroll
+            for (int w = 3 + i * (NW - 3) / KS; w < 3 + (i + 1) * (NW - 3) / KS; w++) w_item(w);
+            if (i >= KS - DT) v_read((i - (KS - DT)) / 2, (i - (KS - DT)) % 2);
+            PF_FENCE();
+        }
+    } else {
+#pragma unroll
+        for (int n = 0; n < DT; n++) v_read(n / 2, n % 2);
+#pragma unroll
+        for (int w = 0; w < NW; w++) w_item(w);
+        PF_FENCE();
+    }
+    // O^T += V^T P^T; in the MFMAs' shadow the mask and the maxima of the new scores.
+    // item k: 0..3 the causal mask (MASK), 4..11 partial maxima, 12 the exchange, 13 the end
+    float mx = 0.f, mn = 0.f;
+    bool grew = false;
+    auto m_item = [&](int k) {
+        if (k < 4) {
+            if (MASK) {
+                // element e = 4 k + x is key 8 k + 4 hh + x of the stage
+                const int kk = key_next + 8 * k + 4 * hh;
+#pragma unroll
+                for (int x = 0; x < 4; x++) {
+                    if (kk + x > row) sn[4 * k + x] = -INFINITY;
+                }
+            }
+        } else if (k == 4) {
+            mx = max3(sn[0], sn[1], sn[2]);
+        } else if (k < 11) {
+            mx = max3(mx, sn[2 * k - 7], sn[2 * k - 6]); // k = 5..10: elements 3..14
+        } else if (k == 11) {
+            mx = max3(mx, sn[15], sn[15]);
+        } else if (k == 12) {
+            const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+            mx = max3(__uint_as_float(r[0]), __uint_as_float(r[1]), __uint_as_float(r[1]));
+        } else {
+            mn = mx * scale_log2; // the scale is positive, so the maximum may be taken before it is applied
+            grew = mn > st.m + kPfSlack;
+            st.s = sn;
+        }
+    };
+    constexpr int NMI = NEXT ? 14 : 0;
+    constexpr int NPV = 2 * DT;
+#pragma unroll
+    for (int n = 0; n < NPV; n++) {
+        const int dt = n / 2, kk = n % 2;
+        if (n + DT < NPV) v_read((n + DT) / 2, (n + DT) % 2); // four products ahead of its use
+        const bf16x8 vf = __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(vr[dt][kk][0], vr[dt][kk][1], 0, 1, 2, 3, 4, 5, 6, 7));
+        st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, __builtin_bit_cast(bf16x8, pw[kk]), st.o[dt], 0, 0, 0);
+#pragma unroll
+        for (int w = n * NMI / NPV; w < (n + 1) * NMI / NPV; w++) m_item(w);
+        PF_FENCE();
+    }
+    if (NEXT) {
+        if (__any(grew)) {
+            mn = mn > st.m ? mn : st.m;
+            const float alpha = __builtin_amdgcn_exp2f(st.m - mn);
+            st.m = mn;
+            st.lsum *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < DT; dt++) st.o[dt] *= alpha;
+        }
+    }
+#undef PF_FENCE
+}
+
+// Scores of a stage for the wave's rows (no vector work to overlap with: used once, for the first stage).
+template <int D>
+__device__ __forceinline__ void pf_scores(const uint8_t *k_stage, const PfLane<D> &pl, const bf16x8 (&qf)[D / 16], f32x16 &sn)
+{
+#pragma unroll
+    for (int e = 0; e < 16; e++) sn[e] = 0.f;
+#pragma unroll
+    for (int i = 0; i < D / 16; i++) {
+        const bf16x8 kf = *(const bf16x8 *)(k_stage + pf_k_off(pl, i));
+        sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[i], sn, 0, 0, 0);
     }
 }
 
@@ -95,9 +214,11 @@ template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel
 {
     using G = Geo<D, 2>;
     constexpr int NST = kPfSlots;
+    constexpr int DPW = G::kDmaPerTile / 2; // loads of a wave per stage: half a tile
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     const uint32_t lds_addr = (uint32_t)(uintptr_t)lds;
-    const int lane = threadIdx.x & 63, j = lane >> 4;
+    static_assert(G::kStage % 4096 == 0 || D == 64, "LDS addresses are formed by XOR");
+    const int lane = threadIdx.x & 63, n = lane & 31, hh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
 
     const int nqb = (a.max_len + kPfBlock - 1) / kPfBlock;
@@ -115,83 +236,140 @@ template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel
 
     LaneConst<D, 2> lc;
     lane_setup<D, 2>(lc, lane, a.Hkv * D * 2);
+    PfLane<D> pl;
+    pf_lane_setup<D>(pl, lane);
 
-    // wave w loads tile w of a stage's {K0, K1, V0, V1}
-    const uint8_t *src_base = (const uint8_t *)((wave < 2 ? a.k : a.v) + ((int64_t)t0 * a.Hkv + kvh) * D);
+    // wave w loads half w % 2 (eight keys) of tile w / 2 of a stage's {K0, K1, V0, V1}
+    const int tile = wave >> 1, half = wave & 1;
+    const uint8_t *src_base = (const uint8_t *)((tile < 2 ? a.k : a.v) + ((int64_t)t0 * a.Hkv + kvh) * D);
     const int64_t tok_bytes = (int64_t)a.Hkv * D * 2;
+    int my_off[DPW]; // the wave's part of the tile: loads DPW * half .. + DPW - 1 of the tile's
+#pragma unroll
+    for (int x = 0; x < DPW; x++) my_off[x] = half ? lc.dma_off[DPW + x] : lc.dma_off[x];
     auto issue = [&](int s) {
-        const int tok = 32 * s + kPage * (wave & 1);
-        issue_tile<D, 2>(lc, src_base + tok * tok_bytes, len - tok, lds_addr + (s % NST) * G::kStage + wave * G::kTile, a.zeros);
-    };
-    int issued = 0;
-    for (; issued < NST - 1 && issued < nst; issued++) issue(issued);
-
-    // Q^T operand: for k-step i, lane (row = lane % 16, j) holds d = 32 i + 8 j .. + 7 of its row
-    bf16x8 qf[kPfTiles][G::kKSteps];
+        const int tok = 32 * s + kPage * (tile & 1);
+        const uint8_t *src = src_base + tok * tok_bytes;
+        const int nvalid = len - tok; // keys of the tile that exist; the others read zeros
+        const uint32_t dst = lds_addr + (s % NST) * G::kStage + tile * G::kTile + 1024 * DPW * half;
 #pragma unroll
-    for (int t = 0; t < kPfTiles; t++) {
-        const int row = q0 + 16 * (wave + kPfWaves * t) + (lane & 15);
-#pragma unroll
-        for (int i = 0; i < G::kKSteps; i++) {
-            bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (row < len) v = *(const bf16x8 *)(a.q + ((int64_t)(t0 + row) * a.Hq + h) * D + 32 * i + 8 * j);
-            qf[t][i] = v;
-        }
-    }
-    f32x4 o[kPfTiles][G::kDTiles];
-    float m[kPfTiles], lsum[kPfTiles];
-#pragma unroll
-    for (int t = 0; t < kPfTiles; t++) {
-        m[t] = -INFINITY;
-        lsum[t] = 0.f;
-#pragma unroll
-        for (int dt = 0; dt < G::kDTiles; dt++) o[t][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
-
-    const int first_diag = q0 >> 5; // stages before this one lie wholly below every row of the block
-    for (int s = 0; s < nst; s++) {
-        // this wave's loads of stage s have landed ...
-        WaitTail<NST - 1, G::kDmaPerTile>::run(issued - 1 - s);
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        // ... and so have the other waves'; and everyone is done with stage s - 1, whose slot takes stage s + NST - 1
-        if (issued < nst) {
-            issue(issued);
-            issued++;
-        }
-        const uint8_t *st = lds + (s % NST) * G::kStage;
-        const uint32_t st_addr = lds_addr + (s % NST) * G::kStage;
-        const int key0 = 32 * s;
-        if (s < first_diag) {
-            prefill_stage<D, 0, false>(st, st_addr, lc, a.scale_log2, key0, 0, qf, o, m, lsum);
-        } else {
-            // tile T = wave + 4 t has a row at or past the stage's first key when T >= 2 (s - first_diag)
-            const int need = 2 * (s - first_diag) - wave;
-            const int tmin = need <= 0 ? 0 : (need + kPfWaves - 1) / kPfWaves;
-            const int row0 = q0 + 16 * (wave + kPfWaves * tmin);
-            switch (tmin) {
-            case 0: prefill_stage<D, 0, true>(st, st_addr, lc, a.scale_log2, key0, row0, qf, o, m, lsum); break;
-            case 1: prefill_stage<D, 1, true>(st, st_addr, lc, a.scale_log2, key0, row0, qf, o, m, lsum); break;
-            case 2: prefill_stage<D, 2, true>(st, st_addr, lc, a.scale_log2, key0, row0, qf, o, m, lsum); break;
-            case 3: prefill_stage<D, 3, true>(st, st_addr, lc, a.scale_log2, key0, row0, qf, o, m, lsum); break;
-            default: break; // every row of this wave lies before the stage
+        for (int x = 0; x < DPW; x++) {
+            if (nvalid >= kPage) {
+                dma16_base((uint32_t)my_off[x], src, dst + 1024 * x);
+            } else {
+                const int r = (64 * (DPW * half + x) + lane) / G::kUnits; // the tile row this lane brings
+                const void *p = r < nvalid ? (const void *)(src + my_off[x]) : a.zeros;
+                dma16(p, dst + 1024 * x);
             }
         }
+    };
+    int issued = 0;
+    for (; issued < NST && issued < nst; issued++) issue(issued);
+
+    // The wave's 32-row tile.  Waves w and w + 4 share a SIMD; tiles w and 7 - w have the same work between them
+    // under the causal mask whatever w is.
+    const int T = wave < 4 ? wave : 11 - wave;
+    const int row = q0 + kPfRows * T + n;
+    PfState<D> st;
+#pragma unroll
+    for (int i = 0; i < D / 16; i++) {
+        bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (row < len) v = *(const bf16x8 *)(a.q + ((int64_t)(t0 + row) * a.Hq + h) * D + 16 * i + 8 * hh);
+        st.qf[i] = v;
+    }
+    st.lsum = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < D / 32; dt++) {
+#pragma unroll
+        for (int e = 0; e < 16; e++) st.o[dt][e] = 0.f;
     }
 
+    // The ring.  While a wave is in step s it reads V of stage s and K of stage s + 1; the barrier that opens step
+    // s says that every wave's loads of stage s + 1 have landed and that every wave has left step s - 1, whose
+    // stage's slot then takes stage s - 1 + NST.
+    auto open_stage = [&](int s) { // makes stage s readable
+        WaitTail<NST - 1, DPW>::run(issued - 1 - s);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+    };
+    // the stage that holds the tile's diagonal is the last one the wave works on; earlier ones lie wholly below it
+    int last = (q0 >> 5) + T;
+    const bool diag_in_range = last < nst;
+    last = diag_in_range ? last : nst - 1;
+
+    open_stage(0);
+    pf_scores<D>(lds, pl, st.qf, st.s);
+    if (last == 0) {
 #pragma unroll
-    for (int t = 0; t < kPfTiles; t++) {
-        const int row = q0 + 16 * (wave + kPfWaves * t) + (lane & 15);
-        const float l = row_sum(lsum[t]);
-        const float inv = 1.0f / l;
-        if (row < len) {
-            const int64_t rh = (int64_t)(t0 + row) * a.Hq + h;
-            uint16_t *dst = a.out + rh * D + 4 * j;
-#pragma unroll
-            for (int dt = 0; dt < G::kDTiles; dt++) *(bf16x4 *)(dst + 16 * dt) = __builtin_convertvector(o[t][dt] * inv, bf16x4);
-            if (j == 0) a.lse[rh] = (m[t] + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+        for (int e = 0; e < 16; e++) {
+            if (8 * (e / 4) + 4 * hh + (e % 4) > row) st.s[e] = -INFINITY;
         }
     }
+    {
+        float mx = max3(st.s[0], st.s[1], st.s[2]);
+#pragma unroll
+        for (int e = 3; e < 15; e += 2) mx = max3(mx, st.s[e], st.s[e + 1]);
+        mx = max3(mx, st.s[15], st.s[15]);
+        const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+        st.m = max3(__uint_as_float(r[0]), __uint_as_float(r[1]), __uint_as_float(r[1])) * a.scale_log2;
+    }
+    // every wave keeps the ring going for all nst stages; it computes up to its own last stage: full steps, then the
+    // step whose new scores cross the diagonal, then the step without new scores
+    auto ring = [&](int s) {
+        if (s + 1 < nst) {
+            open_stage(s + 1);
+            if (s >= 1 && issued < nst) {
+                issue(issued);
+                issued++;
+            }
+        }
+    };
+#define PF_STEP(MASK, NEXT)                                                                                                \
+    pf_step<D, MASK, NEXT>(st, lds + ((s + 1) % NST) * G::kStage, lds_addr + (s % NST) * G::kStage + 2 * G::kTile, pl,   \
+                           a.scale_log2, 32 * (s + 1), row)
+    int s = 0;
+    for (; s + 1 < last; s++) {
+        ring(s);
+        PF_STEP(false, true);
+    }
+    if (s + 1 == last) {
+        ring(s);
+        PF_STEP(true, true);
+        s++;
+    }
+    ring(s);
+    PF_STEP(false, false);
+    for (s++; s < nst; s++) ring(s);
+#undef PF_STEP
+
+    // a row's sum is spread over its two lanes
+    float l;
+    {
+        const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(st.lsum), __float_as_uint(st.lsum), false, false);
+        l = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    }
+    const float inv = 1.0f / l;
+    const int64_t rh = (int64_t)(t0 + row) * a.Hq + h;
+#pragma unroll
+    for (int dt = 0; dt < D / 32; dt++) {
+#pragma unroll
+        for (int qp = 0; qp < 2; qp++) {
+            // elements 8 qp .. + 3 are d = 32 dt + 16 qp + 4 hh .. + 3, elements 8 qp + 4 .. + 7 the same 8 further on;
+            // the two lanes of a row trade halves so that each holds eight consecutive d
+            f32x4 lo, hi;
+#pragma unroll
+            for (int x = 0; x < 4; x++) {
+                lo[x] = st.o[dt][8 * qp + x] * inv;
+                hi[x] = st.o[dt][8 * qp + 4 + x] * inv;
+            }
+            const bf16x4 blo = __builtin_convertvector(lo, bf16x4), bhi = __builtin_convertvector(hi, bf16x4);
+            const u32x2 wlo = __builtin_bit_cast(u32x2, blo), whi = __builtin_bit_cast(u32x2, bhi);
+            const u32x2 s0 = __builtin_amdgcn_permlane32_swap(wlo[0], whi[0], false, false);
+            const u32x2 s1 = __builtin_amdgcn_permlane32_swap(wlo[1], whi[1], false, false);
+            // lane hh = 0 now has d = 32 dt + 16 qp + 0..7, lane hh = 1 has + 8..15
+            if (row < len) *(u32x4 *)(a.out + rh * D + 32 * dt + 16 * qp + 8 * hh) = u32x4{s0[0], s1[0], s0[1], s1[1]};
+        }
+    }
+    if (row < len && hh == 0) a.lse[rh] = (st.m + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
 }
 
 hipError_t launch_prefill(const PrefillLaunch &a, hipStream_t s)
@@ -209,6 +387,7 @@ hipError_t launch_prefill(const PrefillLaunch &a, hipStream_t s)
         hipLaunchKernelGGL(prefill_kernel<128>, dim3((unsigned)blocks), dim3(64 * kPfWaves), lds, s, a);
     } else {
         constexpr int lds = kPfSlots * G64::kStage;
+        static_assert(lds <= 65536, "no attribute needed");
         hipLaunchKernelGGL(prefill_kernel<64>, dim3((unsigned)blocks), dim3(64 * kPfWaves), lds, s, a);
     }
     return hipGetLastError();

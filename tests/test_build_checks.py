@@ -13,7 +13,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def isa(tmp_path_factory):
     from paper_2507_01663_amd import build
     out = tmp_path_factory.mktemp("isa") / "ra_kernels.s"
-    flags = [f for f in build.FLAGS if f not in ("-shared", "-fPIC")]
+    flags = [f for f in build.flags_for("ra_kernels.hip") if f != "-fPIC"]
     cmd = [os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")] + flags + ["-S", "--cuda-device-only", "-o", str(out),
                                                                        os.path.join(build.CSRC, "ra_kernels.hip")]
     subprocess.run(cmd, check=True, stderr=subprocess.DEVNULL)
@@ -42,7 +42,7 @@ def test_prefill_kernels_keep_their_accumulators_in_registers():
     from paper_2507_01663_amd import build
     with tempfile.TemporaryDirectory() as tmp:
         out = os.path.join(tmp, "ra_prefill.s")
-        flags = [f for f in build.FLAGS if f not in ("-shared", "-fPIC")]
+        flags = [f for f in build.flags_for("ra_prefill.hip") if f != "-fPIC"]
         subprocess.run([os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")] + flags + ["-S", "--cuda-device-only", "-o", out,
                                                                                   os.path.join(build.CSRC, "ra_prefill.hip")],
                        check=True, stderr=subprocess.DEVNULL)
@@ -51,6 +51,6 @@ def test_prefill_kernels_keep_their_accumulators_in_registers():
     assert len(found) == 2                                   # D = 64 and D = 128
     for m in re.finditer(r"^(_ZN2ra14prefill_kernel\w+):(.*?)s_endpgm", text, flags=re.S | re.M):
         assert "scratch_" not in m.group(2), m.group(1)
-        assert "v_mfma_f32_16x16x32_bf16" in m.group(2), m.group(1)
+        assert "v_mfma_f32_32x32x16_bf16" in m.group(2), m.group(1)
         assert re.search(r"s_waitcnt vmcnt\([1-9][0-9]*\)", m.group(2)), m.group(1)
     assert text.count(".private_segment_fixed_size: 0") == 4  # the two attention and the two cache-write kernels
