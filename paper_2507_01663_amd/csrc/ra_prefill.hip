@@ -4,9 +4,9 @@
 //
 // Unlike the decode step this is a dense contraction, bound by the matrix cores.  A workgroup of eight waves
 // (two per SIMD, so that one wave's vector work runs while the other's MFMAs do) takes 256 consecutive query
-// rows of one (prompt, head), 32 rows per wave.  K and V stream through an LDS ring in stages of 32 keys (K0 K1
-// V0 V1, half a 16-key tile loaded by each wave with direct global->LDS loads); every wave multiplies every
-// stage with its own query rows, held in registers:
+// rows of one (prompt, head), 32 rows per wave.  K and V stream through an LDS ring in chunks of two stages of 32
+// keys (K0 K1 V0 V1 | K2 K3 V2 V3, one 16-key tile loaded by each wave with direct global->LDS loads); every wave
+// multiplies every stage with its own query rows, held in registers:
 //   S^T[key, row] = K . Q^T,   O^T[d, row] += V^T . P^T     (32x32x16 MFMA, fp32 accumulation)
 // with the softmax running per query row in fp32 (base 2).  The tile layout in LDS is the decode kernel's.
 #include "ra_device.h"
@@ -16,7 +16,7 @@ namespace ra {
 constexpr int kPfWaves = 8;                  // waves per workgroup, two per SIMD
 constexpr int kPfRows = 32;                  // query rows per wave: one 32x32 MFMA tile
 constexpr int kPfBlock = kPfRows * kPfWaves; // query rows per workgroup
-constexpr int kPfSlots = 6;                  // ring slots of one stage (32 keys) each
+constexpr int kPfSlots = 4;                  // ring slots of one chunk (two stages of 32 keys) each
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
@@ -213,11 +213,10 @@ __device__ __forceinline__ void pf_scores(const uint8_t *k_stage, const PfLane<D
 template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel(PrefillLaunch a)
 {
     using G = Geo<D, 2>;
-    constexpr int NST = kPfSlots;
-    constexpr int DPW = G::kDmaPerTile / 2; // loads of a wave per stage: half a tile
-    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+    constexpr int NSL = kPfSlots;           // ring slots; a stage s lives at (s % (2 NSL)) * G::kStage
+    static_assert((NSL & (NSL - 1)) == 0, "slot arithmetic by masking");
+    extern __shared__ __attribute__((aligned(16384))) uint8_t lds[]; // the step forms LDS addresses by XOR
     const uint32_t lds_addr = (uint32_t)(uintptr_t)lds;
-    static_assert(G::kStage % 4096 == 0 || D == 64, "LDS addresses are formed by XOR");
     const int lane = threadIdx.x & 63, n = lane & 31, hh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
 
@@ -239,31 +238,22 @@ template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel
     PfLane<D> pl;
     pf_lane_setup<D>(pl, lane);
 
-    // wave w loads half w % 2 (eight keys) of tile w / 2 of a stage's {K0, K1, V0, V1}
-    const int tile = wave >> 1, half = wave & 1;
-    const uint8_t *src_base = (const uint8_t *)((tile < 2 ? a.k : a.v) + ((int64_t)t0 * a.Hkv + kvh) * D);
+    // wave w loads tile w of a chunk's {K0 K1 V0 V1 | K2 K3 V2 V3}
+    constexpr int DPW = G::kDmaPerTile; // loads of a wave per chunk: one tile
+    const int nchunks = (nst + 1) >> 1;
+    const int tile = wave & 3;
+    int tok = 32 * (wave >> 2) + kPage * (tile & 1); // first key of the wave's tile in the chunk to load next
     const int64_t tok_bytes = (int64_t)a.Hkv * D * 2;
-    int my_off[DPW]; // the wave's part of the tile: loads DPW * half .. + DPW - 1 of the tile's
-#pragma unroll
-    for (int x = 0; x < DPW; x++) my_off[x] = half ? lc.dma_off[DPW + x] : lc.dma_off[x];
-    auto issue = [&](int s) {
-        const int tok = 32 * s + kPage * (tile & 1);
-        const uint8_t *src = src_base + tok * tok_bytes;
-        const int nvalid = len - tok; // keys of the tile that exist; the others read zeros
-        const uint32_t dst = lds_addr + (s % NST) * G::kStage + tile * G::kTile + 1024 * DPW * half;
-#pragma unroll
-        for (int x = 0; x < DPW; x++) {
-            if (nvalid >= kPage) {
-                dma16_base((uint32_t)my_off[x], src, dst + 1024 * x);
-            } else {
-                const int r = (64 * (DPW * half + x) + lane) / G::kUnits; // the tile row this lane brings
-                const void *p = r < nvalid ? (const void *)(src + my_off[x]) : a.zeros;
-                dma16(p, dst + 1024 * x);
-            }
-        }
-    };
+    const uint8_t *src = (const uint8_t *)((tile < 2 ? a.k : a.v) + ((int64_t)(t0 + tok) * a.Hkv + kvh) * D);
+    const uint32_t dst = lds_addr + (wave >> 2) * G::kStage + tile * G::kTile;
     int issued = 0;
-    for (; issued < NST && issued < nst; issued++) issue(issued);
+    auto issue = [&]() {
+        issue_tile<D, 2>(lc, src, len - tok, dst + (issued & (NSL - 1)) * 2 * G::kStage, a.zeros); // keys past the end read zeros
+        src += 64 * tok_bytes;
+        tok += 64;
+        issued++;
+    };
+    while (issued < NSL && issued < nchunks) issue();
 
     // The wave's 32-row tile.  Waves w and w + 4 share a SIMD; tiles w and 7 - w have the same work between them
     // under the causal mask whatever w is.
@@ -283,11 +273,11 @@ template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel
         for (int e = 0; e < 16; e++) st.o[dt][e] = 0.f;
     }
 
-    // The ring.  While a wave is in step s it reads V of stage s and K of stage s + 1; the barrier that opens step
-    // s says that every wave's loads of stage s + 1 have landed and that every wave has left step s - 1, whose
-    // stage's slot then takes stage s - 1 + NST.
-    auto open_stage = [&](int s) { // makes stage s readable
-        WaitTail<NST - 1, DPW>::run(issued - 1 - s);
+    // The ring.  While a wave is in step s it reads V of stage s and K of stage s + 1.  The barrier that opens chunk
+    // c (before step 2 c - 1, the first to read its K) says that every wave's loads of the chunk have landed and that
+    // every wave has left the last step that read chunk c - 2, whose slot then takes chunk c + 2.
+    auto open_chunk = [&](int c) {
+        WaitTail<NSL - 1, DPW>::run(issued - 1 - c);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
     };
@@ -296,7 +286,7 @@ template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel
     const bool diag_in_range = last < nst;
     last = diag_in_range ? last : nst - 1;
 
-    open_stage(0);
+    open_chunk(0);
     pf_scores<D>(lds, pl, st.qf, st.s);
     if (last == 0) {
 #pragma unroll
@@ -312,20 +302,18 @@ template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel
         const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
         st.m = max3(__uint_as_float(r[0]), __uint_as_float(r[1]), __uint_as_float(r[1])) * a.scale_log2;
     }
-    // every wave keeps the ring going for all nst stages; it computes up to its own last stage: full steps, then the
+    // every wave keeps the ring going for all the stages; it computes up to its own last stage: full steps, then the
     // step whose new scores cross the diagonal, then the step without new scores
-    auto ring = [&](int s) {
-        if (s + 1 < nst) {
-            open_stage(s + 1);
-            if (s >= 1 && issued < nst) {
-                issue(issued);
-                issued++;
-            }
+    auto ring = [&](int s) { // before step s
+        if ((s & 1) && s + 1 < nst) {
+            const int c = (s + 1) >> 1;
+            open_chunk(c);
+            if (c >= 2 && issued < nchunks) issue();
         }
     };
 #define PF_STEP(MASK, NEXT)                                                                                                \
-    pf_step<D, MASK, NEXT>(st, lds + ((s + 1) % NST) * G::kStage, lds_addr + (s % NST) * G::kStage + 2 * G::kTile, pl,   \
-                           a.scale_log2, 32 * (s + 1), row)
+    pf_step<D, MASK, NEXT>(st, lds + ((s + 1) & (2 * NSL - 1)) * G::kStage,                                                \
+                           lds_addr + (s & (2 * NSL - 1)) * G::kStage + 2 * G::kTile, pl, a.scale_log2, 32 * (s + 1), row)
     int s = 0;
     for (; s + 1 < last; s++) {
         ring(s);
@@ -381,12 +369,12 @@ hipError_t launch_prefill(const PrefillLaunch &a, hipStream_t s)
     if (blocks == 0) return hipSuccess;
     if (blocks > INT32_MAX) return hipErrorInvalidValue;
     if (a.D == 128) {
-        constexpr int lds = kPfSlots * G128::kStage;
+        constexpr int lds = kPfSlots * 2 * G128::kStage;
         hipError_t e = hipFuncSetAttribute((const void *)prefill_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(prefill_kernel<128>, dim3((unsigned)blocks), dim3(64 * kPfWaves), lds, s, a);
     } else {
-        constexpr int lds = kPfSlots * G64::kStage;
+        constexpr int lds = kPfSlots * 2 * G64::kStage;
         static_assert(lds <= 65536, "no attribute needed");
         hipLaunchKernelGGL(prefill_kernel<64>, dim3((unsigned)blocks), dim3(64 * kPfWaves), lds, s, a);
     }
