@@ -253,7 +253,7 @@ template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel
         tok += 64;
         issued++;
     };
-    while (issued < NSL && issued < nchunks) issue();
+    while (issued < 2 && issued < nchunks) issue(); // the rest follows the barriers, one chunk at a time
 
     // The wave's 32-row tile.  Waves w and w + 4 share a SIMD; tiles w and 7 - w have the same work between them
     // under the causal mask whatever w is.
@@ -275,7 +275,8 @@ template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel
 
     // The ring.  While a wave is in step s it reads V of stage s and K of stage s + 1.  The barrier that opens chunk
     // c (before step 2 c - 1, the first to read its K) says that every wave's loads of the chunk have landed and that
-    // every wave has left the last step that read chunk c - 2, whose slot then takes chunk c + 2.
+    // every wave has left the last step that read chunk c - 2, whose slot then takes chunk c + 2 (chunks 0 and 1 are
+    // loaded up front).
     auto open_chunk = [&](int c) {
         WaitTail<NSL - 1, DPW>::run(issued - 1 - c);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -287,6 +288,7 @@ template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel
     last = diag_in_range ? last : nst - 1;
 
     open_chunk(0);
+    if (issued < nchunks) issue();
     pf_scores<D>(lds, pl, st.qf, st.s);
     if (last == 0) {
 #pragma unroll
@@ -306,9 +308,8 @@ template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel
     // step whose new scores cross the diagonal, then the step without new scores
     auto ring = [&](int s) { // before step s
         if ((s & 1) && s + 1 < nst) {
-            const int c = (s + 1) >> 1;
-            open_chunk(c);
-            if (c >= 2 && issued < nchunks) issue();
+            open_chunk((s + 1) >> 1);
+            if (issued < nchunks) issue();
         }
     };
 #define PF_STEP(MASK, NEXT)                                                                                                \
