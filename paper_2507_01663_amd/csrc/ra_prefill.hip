@@ -208,8 +208,8 @@ __device__ __forceinline__ void pf_scores(const uint8_t *k_stage, const PfLane<D
     }
 }
 
-// Grid: (query block, prompt, head), the blocks with the most keys first.  max_len is the host's upper bound of
-// a prompt's length; blocks past a prompt's real length leave at once.
+// One workgroup per (prompt, head, block of 256 query rows).  max_len is the host's upper bound of a prompt's
+// length; blocks past a prompt's real length leave at once.
 template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel(PrefillLaunch a)
 {
     using G = Geo<D, 2>;
@@ -220,15 +220,19 @@ template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel
     const int lane = threadIdx.x & 63, n = lane & 31, hh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
 
+    // Workgroups are dealt to the eight dies round-robin, and each die has its own L2.  All workgroups of a
+    // (prompt, kv head) pair, which read the same K and V, therefore go to one die: die x takes the pairs x, x + 8,
+    // ... one after the other, each with its query blocks from the longest down and the heads of the kv head together.
     const int nqb = (a.max_len + kPfBlock - 1) / kPfBlock;
-    int bid = blockIdx.x;
-    const int h = bid % a.Hq;
-    bid /= a.Hq;
-    const int g = bid % a.num_prompts;
-    const int q0 = (nqb - 1 - bid / a.num_prompts) * kPfBlock;
+    const int per_pair = nqb * a.G;
+    const int die = blockIdx.x & 7, turn = blockIdx.x >> 3;
+    const int pair = (turn / per_pair) * 8 + die, r = turn % per_pair;
+    if (pair >= a.num_prompts * a.Hkv) return; // the whole workgroup
+    const int g = pair / a.Hkv, kvh = pair % a.Hkv;
+    const int h = kvh * a.G + r % a.G;
+    const int q0 = (nqb - 1 - r / a.G) * kPfBlock;
     const int t0 = uniform_load(a.cu, g), len = uniform_load(a.cu, g + 1) - t0;
     if (q0 >= len) return; // the whole workgroup
-    const int kvh = h / a.G;
     int kend = q0 + kPfBlock;
     kend = kend < len ? kend : len;
     const int nst = (kend + 31) >> 5;
@@ -366,7 +370,8 @@ hipError_t launch_prefill(const PrefillLaunch &a, hipStream_t s)
     using G128 = Geo<128, 2>;
     using G64 = Geo<64, 2>;
     const int nqb = (a.max_len + kPfBlock - 1) / kPfBlock;
-    const int64_t blocks = (int64_t)nqb * a.num_prompts * a.Hq;
+    const int64_t pairs = (int64_t)a.num_prompts * a.Hkv; // dealt to eight dies, see the kernel
+    const int64_t blocks = 8 * ((pairs + 7) / 8) * nqb * a.G;
     if (blocks == 0) return hipSuccess;
     if (blocks > INT32_MAX) return hipErrorInvalidValue;
     if (a.D == 128) {
