@@ -293,6 +293,25 @@ template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel
 
     open_chunk(0);
     if (issued < nchunks) issue();
+    // The query rows are the one input no workgroup has touched before, so a block would start with a trip to
+    // HBM.  Each block therefore touches (one dword per 64-byte line) the query rows of the block that the same die
+    // starts a generation of workgroups later (32 compute units per die, one workgroup each), which then finds
+    // them in the die's L2.  The values are not used; their registers stay reserved until the loads have returned.
+    uint32_t touched[D * 2 / 128];
+    {
+        const int turn2 = turn + 32;
+        const int pair2 = (turn2 / per_pair) * 8 + die, r2 = turn2 % per_pair;
+        bool ok = pair2 < a.num_prompts * a.Hkv;
+        const int g2 = ok ? pair2 / a.Hkv : 0;
+        const int t2 = uniform_load(a.cu, g2), len2 = uniform_load(a.cu, g2 + 1) - t2;
+        const int h2 = (pair2 % a.Hkv) * a.G + r2 % a.G;
+        const int row2 = (nqb - 1 - r2 / a.G) * kPfBlock + kPfRows * wave + (lane >> 1);
+        ok = ok && row2 < len2;
+        const uint16_t *p2 = ok ? a.q + ((int64_t)(t2 + row2) * a.Hq + h2) * D + 32 * (lane & 1) : a.q;
+#pragma unroll
+        for (int x = 0; x < D * 2 / 128; x++)
+            asm volatile("global_load_dword %0, %1, off" : "=v"(touched[x]) : "v"(p2 + 64 * x) : "memory");
+    }
     pf_scores<D>(lds, pl, st.qf, st.s);
     if (last == 0) {
 #pragma unroll
@@ -334,6 +353,9 @@ template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel
     for (s++; s < nst; s++) ring(s);
 #undef PF_STEP
 
+    wait_vmcnt<0>();
+#pragma unroll
+    for (int x = 0; x < D * 2 / 128; x++) asm volatile("" ::"v"(touched[x]));
     // a row's sum is spread over its two lanes
     float l;
     {
