@@ -55,7 +55,14 @@ typedef enum { RA_KV_BF16 = 0, RA_KV_FP8_E4M3 = 1 } ra_kv_dtype;
 enum {
     RA_FLAG_VALIDATE = 1u,          /* check device-side lengths / page ids / hint first (one extra kernel + a
                                        stream synchronisation) */
-    RA_FLAG_NO_PREFIX_SHARING = 2u  /* ignore the prompt-group hint (for A/B comparison) */
+    RA_FLAG_NO_PREFIX_SHARING = 2u, /* ignore the prompt-group hint (for A/B comparison) */
+    RA_FLAG_REUSE_SCHEDULE = 4u     /* skip the schedule kernels and use the schedule that the previous
+                                       rollout_attn_decode call on the same context left in the same workspace.
+                                       For the layers of one decode step: the schedule depends only on B, the head
+                                       counts, D, max_pages_per_seq, seq_lens, seq_group, prefix_page_offsets and
+                                       RA_FLAG_NO_PREFIX_SHARING, which must all be what they were in that call; q,
+                                       out, lse, the pools, the scales and the page ids in block_table and
+                                       prefix_pages may differ.  Nothing checks this. */
 };
 
 /*

@@ -10,7 +10,7 @@ _lib = None
 
 RA_OK, RA_ERR_INVALID_ARG, RA_ERR_UNSUPPORTED, RA_ERR_WORKSPACE_TOO_SMALL, RA_ERR_OUT_OF_RANGE, RA_ERR_DEVICE = range(6)
 RA_KV_BF16, RA_KV_FP8_E4M3 = 0, 1
-RA_FLAG_VALIDATE, RA_FLAG_NO_PREFIX_SHARING = 1, 2
+RA_FLAG_VALIDATE, RA_FLAG_NO_PREFIX_SHARING, RA_FLAG_REUSE_SCHEDULE = 1, 2, 4
 _STATUS_NAMES = ["RA_OK", "RA_ERR_INVALID_ARG", "RA_ERR_UNSUPPORTED", "RA_ERR_WORKSPACE_TOO_SMALL",
                  "RA_ERR_OUT_OF_RANGE", "RA_ERR_DEVICE"]
 

@@ -61,7 +61,7 @@ ra_status check(const ra_problem *p, char *msg, size_t n)
     if (p->Hq % p->Hkv) return fail(RA_ERR_INVALID_ARG, "Hq=%d is not a multiple of Hkv=%d", p->Hq, p->Hkv);
     if (p->kv_dtype != RA_KV_BF16 && p->kv_dtype != RA_KV_FP8_E4M3)
         return fail(RA_ERR_INVALID_ARG, "kv_dtype=%d is not a ra_kv_dtype", p->kv_dtype);
-    if (p->flags & ~(uint32_t)(RA_FLAG_VALIDATE | RA_FLAG_NO_PREFIX_SHARING))
+    if (p->flags & ~(uint32_t)(RA_FLAG_VALIDATE | RA_FLAG_NO_PREFIX_SHARING | RA_FLAG_REUSE_SCHEDULE))
         return fail(RA_ERR_INVALID_ARG, "unknown bits in flags=0x%x", p->flags);
     if (!std::isfinite(p->softmax_scale)) return fail(RA_ERR_INVALID_ARG, "softmax_scale is not finite");
     if (p->page_size != 16) return fail(RA_ERR_UNSUPPORTED, "page_size=%d (only 16 is supported)", p->page_size);
@@ -320,7 +320,9 @@ ra_status rollout_attn_decode(ra_ctx *c, const ra_problem *p, void *workspace, s
     }
     const bool tm = c->timing != 0;
     if (e == hipSuccess && tm) e = hipEventRecord(c->ev[0], s);
-    if (e == hipSuccess) e = ra::launch_plan(a, s);
+    // (a schedule with a dynamically scheduled tail carries a counter that the attention kernel uses up)
+    const bool reuse = (p->flags & RA_FLAG_REUSE_SCHEDULE) && a.static_pct >= 100;
+    if (e == hipSuccess && !reuse) e = ra::launch_plan(a, s);
     if (e == hipSuccess && tm) e = hipEventRecord(c->ev[1], s);
     if (e == hipSuccess) e = ra::launch_attention(a, s);
     if (e == hipSuccess && tm) e = hipEventRecord(c->ev[2], s);

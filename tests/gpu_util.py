@@ -46,8 +46,11 @@ class DeviceProblem:
         return self.out.float().cpu().numpy().astype(np.float64), self.lse.cpu().numpy().astype(np.float64)
 
 
-def compare(out, lse, ref_out, ref_lse, what=""):
-    """Asserts the three tolerances; returns the measured errors."""
+def compare(out, lse, ref_out, ref_lse, what="", abs_rel=0.0):
+    """Asserts the three tolerances; returns the measured errors.  abs_rel widens the element-wise bound to
+    ABS_TOL + abs_rel * |ref| for outputs that are not small: rounding the exact result to bf16 alone moves an
+    element by up to 2**-9 of its magnitude, which passes ABS_TOL once |ref| > 5 (prompt prefill: the first tokens of a
+    prompt average over few values; a decode step averages over hundreds and never gets there)."""
     assert np.isfinite(out).all(), what + ": non-finite output"
     empty = np.isneginf(ref_lse)
     assert (np.isneginf(lse) == empty).all(), what + ": -inf pattern of lse differs"
@@ -58,7 +61,8 @@ def compare(out, lse, ref_out, ref_lse, what=""):
     rel = np.where(den > 0, num / np.maximum(den, 1e-300), num)
     rel_err = float(rel.max()) if rel.size else 0.0
     lse_err = float(np.abs(lse[~empty] - ref_lse[~empty]).max()) if (~empty).any() else 0.0
-    assert abs_err <= ABS_TOL, "%s: max abs err %.3e" % (what, abs_err)
+    excess = float((np.abs(d) - abs_rel * np.abs(ref_out)).max()) if d.size else 0.0
+    assert excess <= ABS_TOL, "%s: max abs err %.3e (%.3e beyond the magnitude allowance)" % (what, abs_err, excess)
     assert rel_err <= REL_TOL, "%s: max row rel err %.3e" % (what, rel_err)
     assert lse_err <= LSE_TOL, "%s: max lse err %.3e" % (what, lse_err)
     return abs_err, rel_err, lse_err

@@ -356,3 +356,24 @@ def test_full_size_stream72b_steps(dec):
         rows = sampled_rows(p, int(0.05 * p.B * p.Hq), 2)
         errs = compare_rows(dp, p, rows, "stream72b step %d" % step)
         log("stream72b step %d, %d rows: abs %.2e rel %.2e lse %.2e" % ((step, len(rows)) + errs))
+
+
+def test_schedule_reused_for_another_layer(dec):
+    import paper_2507_01663_amd as ra
+    from gpu_util import DeviceProblem, compare
+    # the layers of one decode step share lengths and groups, not queries, pools or page ids: the second problem has
+    # its own of each and runs on the first one's schedule
+    p1 = workload.make_problem("mid7b", seed=1)
+    p2 = workload.make_problem("mid7b", seed=1)
+    p2.q = workload.normal_bf16(p2.q.size, 77, 1).reshape(p2.q.shape)
+    perm = np.random.default_rng(5).permutation(p2.num_pages).astype(np.int32)      # the same cache at other page ids
+    inv = np.empty_like(perm)
+    inv[perm] = np.arange(p2.num_pages, dtype=np.int32)
+    p2.k_pool, p2.v_pool = p1.k_pool[inv].copy(), p1.v_pool[inv].copy()
+    p2.block_table = np.where(p1.block_table >= 0, perm[np.maximum(p1.block_table, 0)], -1).astype(np.int32)
+    p2.prefix_pages = perm[p1.prefix_pages]
+    d1, d2 = DeviceProblem(p1), DeviceProblem(p2, flags=ra.RA_FLAG_REUSE_SCHEDULE)
+    dec.decode(d1.c)
+    dec.decode(d2.c)
+    compare(*d1.results(), *oracle.decode(p1), "layer 1")
+    compare(*d2.results(), *oracle.decode(p2), "layer 2 on layer 1's schedule")

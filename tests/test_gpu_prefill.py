@@ -8,11 +8,18 @@ import torch
 import oracle
 import paper_2507_01663_amd as ra
 import workload
-from gpu_util import ABS_TOL, LSE_TOL, REL_TOL, bits_to_bf16, compare
+from gpu_util import ABS_TOL, LSE_TOL, REL_TOL, bits_to_bf16
+from gpu_util import compare as compare_decode
 from workload.gen import PAGE, bf16_bits_to_f32
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
+OUT_ULP = 2.0 ** -8      # one bf16 unit in the last place, relative: the allowance for outputs that are not small
+
+
+def compare(out, lse, ref_out, ref_lse, what=""):
+    """The decode tolerances, with the element-wise bound widened by one bf16 ulp of the reference's magnitude."""
+    return compare_decode(out, lse, ref_out, ref_lse, what, abs_rel=OUT_ULP)
 
 
 @pytest.fixture(scope="module")
