@@ -242,17 +242,23 @@ template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel
     PfLane<D> pl;
     pf_lane_setup<D>(pl, lane);
 
-    // wave w loads tile w of a chunk's {K0 K1 V0 V1 | K2 K3 V2 V3}
-    constexpr int DPW = G::kDmaPerTile; // loads of a wave per chunk: one tile
+    // waves 0..3 load the chunks {K0 K1 V0 V1 | K2 K3 V2 V3}: wave w brings tile w of both stages.  (Waves 4..7, the
+    // second on each SIMD, are the ones that arrive last at the barriers; they issue no loads.)
+    constexpr int DPW = 2 * G::kDmaPerTile; // loads of a loading wave per chunk
     const int nchunks = (nst + 1) >> 1;
     const int tile = wave & 3;
-    int tok = 32 * (wave >> 2) + kPage * (tile & 1); // first key of the wave's tile in the chunk to load next
+    const bool loader = wave < 4;
+    int tok = kPage * (tile & 1); // first key of the wave's tile in the chunk to load next
     const int64_t tok_bytes = (int64_t)a.Hkv * D * 2;
     const uint8_t *src = (const uint8_t *)((tile < 2 ? a.k : a.v) + ((int64_t)(t0 + tok) * a.Hkv + kvh) * D);
-    const uint32_t dst = lds_addr + (wave >> 2) * G::kStage + tile * G::kTile;
+    const uint32_t dst = lds_addr + tile * G::kTile;
     int issued = 0;
     auto issue = [&]() {
-        issue_tile<D, 2>(lc, src, len - tok, dst + (issued & (NSL - 1)) * 2 * G::kStage, a.zeros); // keys past the end read zeros
+        if (loader) {
+            const uint32_t d = dst + (issued & (NSL - 1)) * 2 * G::kStage;
+            issue_tile<D, 2>(lc, src, len - tok, d, a.zeros); // keys past the end read zeros
+            issue_tile<D, 2>(lc, src + 32 * tok_bytes, len - tok - 32, d + G::kStage, a.zeros);
+        }
         src += 64 * tok_bytes;
         tok += 64;
         issued++;
@@ -282,7 +288,7 @@ template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel
     // every wave has left the last step that read chunk c - 2, whose slot then takes chunk c + 2 (chunks 0 and 1 are
     // loaded up front).
     auto open_chunk = [&](int c) {
-        WaitTail<NSL - 1, DPW>::run(issued - 1 - c);
+        if (loader) WaitTail<NSL - 1, DPW>::run(issued - 1 - c);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
     };
