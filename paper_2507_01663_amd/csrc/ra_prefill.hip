@@ -60,12 +60,20 @@ template <int D> struct PfState {
     float m, lsum;     // reference point of the exponent (same in both lanes of a row); this lane's part of the row sum
 };
 
+// max(a, b, c) as the instruction computes it.  (Through fmaxf the compiler first quiets possible signalling NaNs of
+// every operand with an instruction of its own, which doubles the cost of the reduction.)  The compiler does not
+// look inside: it pads the distance between an MFMA and a vector instruction that reads its result only for
+// instructions it knows, so the first read of an MFMA's accumulator must not be one of these (see first_max).
 __device__ __forceinline__ float max3(float a, float b, float c)
 {
     float r;
     asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
     return r;
 }
+// The first step of a maximum over fresh MFMA results, by an instruction the compiler knows; once it has run, the
+// whole accumulator (one MFMA writes all of it) is safe to read.
+__device__ __forceinline__ float first_max(float a, float b) { return fmaxf(a, b); }
+
 constexpr float kPfSlack = 8.0f;
 
 // One step of a wave's software pipeline (see the kernel): weights of stage s and scores of stage s + 1 (NEXT; MASK:
@@ -156,7 +164,7 @@ __device__ __forceinline__ void pf_step(PfState<D> &st, const uint8_t *k_next, u
                 }
             }
         } else if (k == 4) {
-            mx = max3(sn[0], sn[1], sn[2]);
+            mx = max3(first_max(sn[0], sn[1]), sn[2], sn[2]);
         } else if (k < 11) {
             mx = max3(mx, sn[2 * k - 7], sn[2 * k - 6]); // k = 5..10: elements 3..14
         } else if (k == 11) {
@@ -298,12 +306,28 @@ template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel
     last = diag_in_range ? last : nst - 1;
 
     open_chunk(0);
+    pf_scores<D>(lds, pl, st.qf, st.s);
+    if (last == 0) {
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+            if (8 * (e / 4) + 4 * hh + (e % 4) > row) st.s[e] = -INFINITY;
+        }
+    }
+    {
+        float mx = max3(first_max(st.s[0], st.s[1]), st.s[2], st.s[2]);
+#pragma unroll
+        for (int e = 3; e < 15; e += 2) mx = max3(mx, st.s[e], st.s[e + 1]);
+        mx = max3(mx, st.s[15], st.s[15]);
+        const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+        st.m = max3(__uint_as_float(r[0]), __uint_as_float(r[1]), __uint_as_float(r[1])) * a.scale_log2;
+    }
+    // (only now, so that the wait for the query rows above does not also wait for these loads)
     if (issued < nchunks) issue();
     // The query rows are the one input no workgroup has touched before, so a block would start with a trip to
     // HBM.  Each block therefore touches (one dword per 64-byte line) the query rows of the block that the same die
     // starts a generation of workgroups later (32 compute units per die, one workgroup each), which then finds
-    // them in the die's L2.  The values are not used; their registers stay reserved until the loads have returned.
-    uint32_t touched[D * 2 / 128];
+    // them in the die's L2.  The dwords go to a scrap area of LDS behind the ring (a load into registers would
+    // write them at a time the compiler does not know of).
     {
         const int turn2 = turn + 32;
         const int pair2 = (turn2 / per_pair) * 8 + die, r2 = turn2 % per_pair;
@@ -315,23 +339,7 @@ template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel
         ok = ok && row2 < len2;
         const uint16_t *p2 = ok ? a.q + ((int64_t)(t2 + row2) * a.Hq + h2) * D + 32 * (lane & 1) : a.q;
 #pragma unroll
-        for (int x = 0; x < D * 2 / 128; x++)
-            asm volatile("global_load_dword %0, %1, off" : "=v"(touched[x]) : "v"(p2 + 64 * x) : "memory");
-    }
-    pf_scores<D>(lds, pl, st.qf, st.s);
-    if (last == 0) {
-#pragma unroll
-        for (int e = 0; e < 16; e++) {
-            if (8 * (e / 4) + 4 * hh + (e % 4) > row) st.s[e] = -INFINITY;
-        }
-    }
-    {
-        float mx = max3(st.s[0], st.s[1], st.s[2]);
-#pragma unroll
-        for (int e = 3; e < 15; e += 2) mx = max3(mx, st.s[e], st.s[e + 1]);
-        mx = max3(mx, st.s[15], st.s[15]);
-        const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-        st.m = max3(__uint_as_float(r[0]), __uint_as_float(r[1]), __uint_as_float(r[1])) * a.scale_log2;
+        for (int x = 0; x < D * 2 / 128; x++) dma4(p2 + 64 * x, lds_addr + NSL * 2 * G::kStage + 256 * wave);
     }
     // every wave keeps the ring going for all the stages; it computes up to its own last stage: full steps, then the
     // step whose new scores cross the diagonal, then the step without new scores
@@ -359,9 +367,7 @@ template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel
     for (s++; s < nst; s++) ring(s);
 #undef PF_STEP
 
-    wait_vmcnt<0>();
-#pragma unroll
-    for (int x = 0; x < D * 2 / 128; x++) asm volatile("" ::"v"(touched[x]));
+    wait_vmcnt<0>(); // nothing may land in LDS after the workgroup has left
     // a row's sum is spread over its two lanes
     float l;
     {
@@ -403,13 +409,14 @@ hipError_t launch_prefill(const PrefillLaunch &a, hipStream_t s)
     if (blocks == 0) return hipSuccess;
     if (blocks > INT32_MAX) return hipErrorInvalidValue;
     if (a.D == 128) {
-        constexpr int lds = kPfSlots * 2 * G128::kStage;
+        constexpr int lds = kPfSlots * 2 * G128::kStage + 256 * kPfWaves; // ring + scrap
         hipError_t e = hipFuncSetAttribute((const void *)prefill_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(prefill_kernel<128>, dim3((unsigned)blocks), dim3(64 * kPfWaves), lds, s, a);
     } else {
-        constexpr int lds = kPfSlots * 2 * G64::kStage;
-        static_assert(lds <= 65536, "no attribute needed");
+        constexpr int lds = kPfSlots * 2 * G64::kStage + 256 * kPfWaves;
+        hipError_t e = hipFuncSetAttribute((const void *)prefill_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
         hipLaunchKernelGGL(prefill_kernel<64>, dim3((unsigned)blocks), dim3(64 * kPfWaves), lds, s, a);
     }
     return hipGetLastError();

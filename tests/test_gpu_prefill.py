@@ -93,6 +93,20 @@ def test_large_scores_and_an_outlier_key(dec):
     check_all(dec, b, "outlier keys")
 
 
+@pytest.mark.parametrize("D", [64, 128])
+def test_keys_a_thousand_times_larger_than_the_rest(dec, D):
+    # A key whose scores dwarf all others makes any disagreement between the reference point of the exponent and the
+    # scores it is applied to overflow at once (the reference point comes from a maximum over fresh MFMA results; the
+    # weights from the same results a little later).  One such key in the first stage, one at a stage edge, one in the
+    # middle of a later block.
+    b = workload.build_prefill("pf", 8, 2, D, [100, 700], seed=11)
+    k = bf16_bits_to_f32(b.k).copy()
+    for t in (6, 100 + 31, 100 + 32, 100 + 300, 100 + 511):
+        k[t] *= 1000.0
+    b.k = workload.f32_to_bf16_bits(k)
+    check_all(dec, b, "dominant keys, D=%d" % D)
+
+
 def test_no_prompts_and_empty_prompts(dec):
     b = workload.build_prefill("pf", 8, 2, 64, [0, 0], seed=1)
     d = DevicePrefill(b, max_len=0)
