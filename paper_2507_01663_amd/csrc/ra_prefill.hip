@@ -203,17 +203,24 @@ __device__ __forceinline__ void pf_step(PfState<D> &st, const uint8_t *k_next, u
 #undef PF_FENCE
 }
 
-// Scores of a stage for the wave's rows (no vector work to overlap with: used once, for the first stage).
+// Scores of a stage for the wave's rows (no vector work to overlap with: used once, for the first stage).  All K
+// operands are read first and the products go to two accumulators in turn, so that neither the LDS latency nor the
+// MFMA latency is paid once per k-step.
 template <int D>
 __device__ __forceinline__ void pf_scores(const uint8_t *k_stage, const PfLane<D> &pl, const bf16x8 (&qf)[D / 16], f32x16 &sn)
 {
+    bf16x8 kf[D / 16];
 #pragma unroll
-    for (int e = 0; e < 16; e++) sn[e] = 0.f;
+    for (int i = 0; i < D / 16; i++) kf[i] = *(const bf16x8 *)(k_stage + pf_k_off(pl, i));
+    f32x16 s2;
 #pragma unroll
-    for (int i = 0; i < D / 16; i++) {
-        const bf16x8 kf = *(const bf16x8 *)(k_stage + pf_k_off(pl, i));
-        sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[i], sn, 0, 0, 0);
+    for (int e = 0; e < 16; e++) sn[e] = s2[e] = 0.f;
+#pragma unroll
+    for (int i = 0; i < D / 16; i += 2) {
+        sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], qf[i], sn, 0, 0, 0);
+        s2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i + 1], qf[i + 1], s2, 0, 0, 0);
     }
+    sn += s2;
 }
 
 // One workgroup per (prompt, head, block of 256 query rows).  max_len is the host's upper bound of a prompt's
