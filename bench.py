@@ -27,7 +27,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 def kernel_source_hash():
     import hashlib
     h = hashlib.sha256()
-    for f in ("ra_kernels.hip", "ra_internal.h"):
+    for f in ("ra_kernels.hip", "ra_device.h", "ra_internal.h"):
         h.update(open(os.path.join(ROOT, "paper_2507_01663_amd", "csrc", f), "rb").read())
     return h.hexdigest()[:16]
 
