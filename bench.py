@@ -40,7 +40,7 @@ def recorded_traffic(workload_name):
         rec = json.load(open(path))
     except (OSError, ValueError):
         return None
-    ent = rec.get(workload_name)
+    ent = rec.get(workload_name)   # keyed by workload and variant, e.g. "grpo7b", "grpo7b_fp8"
     if not ent or ent.get("kernel_source_hash") != kernel_source_hash():
         return None
     return ent.get("hbm_bytes_per_launch")
@@ -181,7 +181,8 @@ def main():
                       "merge": round(float(phase[2]), 5)},
         "roofline": {"bound": "hbm", "kernel": "attention_kernel", "achieved": round(att_gbps, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(att_gbps / HBM_PEAK_GBPS, 4),
-                     "traffic": recorded_traffic(args.workload)},
+                     "traffic": recorded_traffic(args.workload + ("" if args.kv_dtype == "bf16" else "_fp8") +
+                                                  ("_noshare" if args.no_sharing else ""))},
     }
 
     if copy_info:
@@ -210,8 +211,13 @@ def main():
         d.set(flags)
     del wss
 
+    # instance 0's result for the parity check at the end, taken before anything below writes to the pools
+    dec.decode(devs[0].c, stream)
+    gpu_out0, gpu_lse0 = devs[0].results()
+
     # The KV append that precedes each decode step's attention, timed on its own (it is not part of `value`):
-    # all-zero rows, so the pools' contents that the attention reads stay what they were.
+    # all-zero rows, written past the ends of the sequences.  (Where the instances share one pool under different
+    # block tables, these rows can land on pages that another instance reads; nothing is measured on them afterwards.)
     zero_rows = torch.zeros(probs[0].B, probs[0].Hkv, probs[0].D, dtype=torch.bfloat16, device="cuda:0")
     for _ in range(10):
         dec.append(devs[0].c, zero_rows, zero_rows, stream)
@@ -271,8 +277,7 @@ def main():
                                          % (probs[0].B * probs[0].Hq, reps)}
         # the timed GPU result of instance 0 must agree with what was just computed
         from gpu_util import compare
-        dec.decode(devs[0].c, stream)
-        errs = compare(*devs[0].results(), ref_out, ref_lse, "bench instance 0")
+        errs = compare(gpu_out0, gpu_lse0, ref_out, ref_lse, "bench instance 0")
         out["parity"] = {"max_abs": float("%.3g" % errs[0]), "max_row_rel": float("%.3g" % errs[1]), "max_lse": float("%.3g" % errs[2])}
     print(json.dumps(out))
 
