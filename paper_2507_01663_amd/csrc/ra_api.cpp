@@ -18,7 +18,7 @@ struct ra_ctx {
     int cost_item;   // ... of a segment, on top of its pages
     int static_pct;  // share of the work that is assigned to waves up front
     int dyn_pages;   // pages per dynamically scheduled span
-    int xcd_w[8];    // relative speed of the accelerator dies
+    int xcd_w[2][8]; // relative speed of the accelerator dies, measured in the launch shape of [e4m3 KV]
     void *zeros;  // 256 bytes of zeros on the device
     int32_t *host_flags; // pinned, for RA_FLAG_VALIDATE
     int timing;          // record events around the phases
@@ -111,9 +111,10 @@ void fill_launch(ra::Launch &a, const ra_ctx *ctx, const ra_problem *p)
         long W = 0;
         int acc = 0;
         const bool use = ctx && a.waves % 8 == 0;
-        for (int x = 0; x < 8; x++) W += use ? ctx->xcd_w[x] : 1000;
+        const int *xw = ctx ? ctx->xcd_w[a.kv_fp8] : nullptr;
+        for (int x = 0; x < 8; x++) W += use ? xw[x] : 1000;
         for (int x = 0; x < 8; x++) {
-            a.xcd_w[x] = x < 7 ? (int)(((use ? ctx->xcd_w[x] : 1000) * 8192L + W / 2) / W) : 8192 - acc;
+            a.xcd_w[x] = x < 7 ? (int)(((use ? xw[x] : 1000) * 8192L + W / 2) / W) : 8192 - acc;
             acc += a.xcd_w[x];
         }
     }
@@ -138,7 +139,7 @@ uint32_t rollout_attn_abi_version(void) { return ROLLOUT_ATTN_ABI_VERSION; }
 // Measures the dies' relative streaming speed (see calibrate_kernel) and turns it into span weights, per mille
 // of the mean.  Needs a quarter of a gigabyte of device memory for a moment; on any failure, or when the
 // workgroups are not dealt to the dies round-robin as the schedule assumes, the weights are left alone.
-static void calibrate_dies(ra_ctx *c, int waves)
+static void calibrate_dies(int waves, int *weights)
 {
     if (waves <= 0 || waves % 8) return;
     const int stages = 16;
@@ -168,7 +169,7 @@ static void calibrate_dies(ra_ctx *c, int waves)
     for (int x = 0; x < 8; x++) mean_speed += 1.0 / dur[x] / 8;
     for (int x = 0; x < 8; x++) {
         int w = (int)(1024.0 / dur[x] / mean_speed + 0.5);
-        c->xcd_w[x] = w < 800 ? 800 : (w > 1250 ? 1250 : w);
+        weights[x] = w < 800 ? 800 : (w > 1250 ? 1250 : w);
     }
 }
 
@@ -191,7 +192,7 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
     // Share of the memory bandwidth each accelerator die gets when all eight stream at once (per mille of the
     // mean).  This is what a typical MI355X shows; the context measures its own device below.
     static const int kXcdSpeed[8] = {1024, 944, 1089, 978, 1064, 973, 1013, 936};
-    for (int x = 0; x < 8; x++) c->xcd_w[x] = kXcdSpeed[x];
+    for (int x = 0; x < 8; x++) c->xcd_w[0][x] = c->xcd_w[1][x] = kXcdSpeed[x];
     bool calibrate = true;
     if (const char *ev = getenv("ROLLOUT_ATTN_CALIBRATE")) calibrate = atoi(ev) != 0;
     if (const char *ev = getenv("ROLLOUT_ATTN_XCD_WEIGHTS")) {
@@ -200,7 +201,7 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
             bool ok = true;
             for (int x = 0; x < 8; x++) ok = ok && v[x] >= 700 && v[x] <= 1400; // no span under half the mean
             if (ok) {
-                for (int x = 0; x < 8; x++) c->xcd_w[x] = v[x];
+                for (int x = 0; x < 8; x++) c->xcd_w[0][x] = c->xcd_w[1][x] = v[x];
                 calibrate = false;
             }
         }
@@ -235,10 +236,14 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
     for (int f = 0; f < 2; f++)
         for (int d = 0; d < 2; d++)
             if (e == hipSuccess) e = ra::attention_config(d ? 128 : 64, f, c->num_cus, &c->stages[f][d], &c->waves[f][d]);
-    if (e == hipSuccess && calibrate) calibrate_dies(c, c->waves[0][1]);
+    if (e == hipSuccess && calibrate) {
+        calibrate_dies(c->waves[0][1], c->xcd_w[0]);
+        calibrate_dies(c->waves[1][1], c->xcd_w[1]);
+    }
     if (getenv("ROLLOUT_ATTN_VERBOSE"))
-        fprintf(stderr, "rollout_attn: die weights %d %d %d %d %d %d %d %d\n", c->xcd_w[0], c->xcd_w[1], c->xcd_w[2], c->xcd_w[3],
-                c->xcd_w[4], c->xcd_w[5], c->xcd_w[6], c->xcd_w[7]);
+        for (int f = 0; f < 2; f++)
+            fprintf(stderr, "rollout_attn: die weights (%s KV) %d %d %d %d %d %d %d %d\n", f ? "e4m3" : "bf16", c->xcd_w[f][0],
+                    c->xcd_w[f][1], c->xcd_w[f][2], c->xcd_w[f][3], c->xcd_w[f][4], c->xcd_w[f][5], c->xcd_w[f][6], c->xcd_w[f][7]);
     (void)hipSetDevice(prev);
     if (e != hipSuccess) {
         set_err(nullptr, "context set-up on device %d: %s", device, hipGetErrorString(e));

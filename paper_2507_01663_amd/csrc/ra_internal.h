@@ -79,8 +79,8 @@ int prefix_rows_max(int B, int G, int num_groups);
 // Carves the workspace; returns the bytes needed.  base may be null (size query).
 size_t carve_workspace(Workspace &ws, void *base, int B, int Hkv, int G, int D, int num_groups, int waves);
 
-// LDS ring depth of the attention kernel and the number of its waves (= workgroups) that are resident at once
-// on the current device, for head dim D.
+// LDS ring depth of the attention kernel and the number of its waves (= workgroups = spans of the page stream) to
+// launch on the current device, for head dim D: as many as are resident at once for bf16 pools, twice that for e4m3.
 hipError_t attention_config(int D, int kv_fp8, int num_cus, int *stages, int *waves);
 
 // Streams nblocks * 16 KB of buf (nblocks a power of two, = waves * stages) through the attention kernel's ring
