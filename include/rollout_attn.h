@@ -209,7 +209,7 @@ ra_status rollout_attn_append(ra_ctx *ctx, const ra_problem *problem, const void
  * Layouts: q, out bf16 [T][Hq][D]; k, v bf16 [T][Hkv][D]; lse fp32 [T][Hq]; all contiguous, 16-byte aligned,
  * T = total_tokens = cu_seqlens[num_prompts].  cu_seqlens: dev int32 [num_prompts + 1], starts at 0,
  * non-decreasing.  max_prompt_len is a HOST-side upper bound of every prompt's length (the launch is sized by
- * it; tokens of a prompt at or past it are not processed).
+ * it; a prompt's tokens at or past it may be left unprocessed, in whole blocks of query rows and whole pages).
  * Cache write (k_pool != NULL): token i of prompt g goes to page pages[page_offsets[g] + i / page_size], slot
  * i % page_size, every kv head, of pools laid out as in ra_problem (same strides, kv_dtype, scales); a prompt
  * with more tokens than its pages hold has the rest left unwritten, and so has a page id outside

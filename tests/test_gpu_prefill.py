@@ -116,6 +116,22 @@ def test_no_prompts_and_empty_prompts(dec):
     check_all(dec, b, "empty prompts around one")
 
 
+def test_bound_on_the_prompt_length_sizes_the_launch(dec):
+    # a bound above the real lengths costs nothing but idle workgroups; one below them leaves the tail of a prompt
+    # untouched (whole blocks of 256 query rows), and what is computed is still right
+    b = workload.build_prefill("pf", 8, 2, 128, [300, 40], seed=2)
+    ref_out, ref_lse = oracle.prefill(b.q, b.k, b.v, b.cu_seqlens, b.softmax_scale)
+    d = DevicePrefill(b, max_len=2000)
+    dec.prefill(d.c)
+    compare(*d.results(), ref_out, ref_lse, "generous bound")
+    d = DevicePrefill(b, max_len=200)
+    dec.prefill(d.c)
+    out, lse = d.results()
+    compare(out[:256], lse[:256], ref_out[:256], ref_lse[:256], "first block of the long prompt")
+    compare(out[300:], lse[300:], ref_out[300:], ref_lse[300:], "the short prompt")
+    assert np.isnan(out[256:300]).all() and np.isnan(lse[256:300]).all()
+
+
 def test_benchmark_size_whole_prompts(dec):
     # the launch bench.py times (32 prompts of 512, 7B head shape); three prompts in full against the oracle
     b = workload.make_prefill("grpo7b", seed=0)
