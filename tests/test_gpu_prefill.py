@@ -218,6 +218,30 @@ def test_cache_write_is_bit_exact(dec, kv_dtype, D):
     compare(out, lse, ref_out, ref_lse, "prefill with cache write")
 
 
+@pytest.mark.parametrize("kv_dtype", ["bf16", "fp8_e4m3"])
+def test_cache_write_into_pools_that_are_views(dec, kv_dtype):
+    # K and V interleaved per page in one allocation, with room between the token rows: the write goes through the strides
+    b = workload.build_prefill("pf", 8, 2, 128, [70, 33], seed=13)
+    d = DevicePrefill(b, kv_dtype=kv_dtype)
+    pad = 32 if kv_dtype == "bf16" else 64
+    both = torch.zeros((b.num_pages, 2, b.Hkv, PAGE, b.D + pad), dtype=d.k_pool.dtype, device=DEV)
+    both[..., :b.D] = torch.stack([d.k_pool, d.v_pool], dim=1)
+    kp, vp = both[:, 0, :, :, :b.D], both[:, 1, :, :, :b.D]
+    d.c = ra.prefill_from_tensors(d.q, d.k, d.v, d.cu, int(b.lens.max()), d.out, d.lse, float(b.softmax_scale), k_pool=kp, v_pool=vp,
+                                  k_scale=d.k_scale, v_scale=d.v_scale, page_offsets=d.page_off, pages=d.pages)
+    assert d.c.kv_stride_token == b.D + pad and d.c.kv_stride_page == 2 * b.Hkv * PAGE * (b.D + pad)
+    dec.prefill(d.c)
+    torch.cuda.synchronize()
+    ek, ev, eks, evs = expected_pools(b, kv_dtype)
+    view = (lambda t: t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)) if kv_dtype == "bf16" else (lambda t: t.contiguous().cpu().numpy())
+    np.testing.assert_array_equal(view(kp), ek)
+    np.testing.assert_array_equal(view(vp), ev)
+    assert (both[..., b.D:] == 0).all()          # nothing landed between the rows
+    if kv_dtype != "bf16":
+        np.testing.assert_array_equal(d.k_scale.cpu().numpy().view(np.uint32), eks.view(np.uint32))
+        np.testing.assert_array_equal(d.v_scale.cpu().numpy().view(np.uint32), evs.view(np.uint32))
+
+
 def test_cache_write_skips_missing_and_invalid_pages(dec):
     b = workload.build_prefill("pf", 4, 2, 64, [50, 50], seed=9)
     # prompt 0 keeps only two of its four pages; prompt 1 has one page id out of range
