@@ -241,6 +241,11 @@ typedef struct {
     const int32_t *pages;        /* dev int32 [page_offsets[num_prompts]] */
 } ra_prefill;
 
+/* Host-only check of the scalars, strides and pointers of a prefill (device data is not read): what
+ * rollout_attn_prefill would return for them before touching the device.  msg (may be NULL) receives a
+ * NUL-terminated explanation of at most msg_len bytes. */
+ra_status rollout_attn_check_prefill(const ra_prefill *prefill, char *msg, size_t msg_len);
+
 /* Enqueues the cache write (if asked for) and the causal attention of the packed prompts on hip_stream and
  * returns without waiting.  Needs no workspace.  Deterministic.  RA_ERR_INVALID_ARG / RA_ERR_UNSUPPORTED as
  * for rollout_attn_decode; nothing is enqueued then. */

@@ -90,6 +90,8 @@ def load_library():
                                                 P(ra_schedule_info)]
     lib.rollout_attn_append.restype = ctypes.c_int
     lib.rollout_attn_append.argtypes = [ctypes.c_void_p, P(ra_problem), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    lib.rollout_attn_check_prefill.restype = ctypes.c_int
+    lib.rollout_attn_check_prefill.argtypes = [P(ra_prefill), ctypes.c_char_p, ctypes.c_size_t]
     lib.rollout_attn_prefill.restype = ctypes.c_int
     lib.rollout_attn_prefill.argtypes = [ctypes.c_void_p, P(ra_prefill), ctypes.c_void_p]
     lib.rollout_attn_balance.restype = ctypes.c_int
@@ -159,6 +161,13 @@ def rollout_attn_debug_schedule(ctx, problem, workspace_ptr, workspace_bytes, hi
 
 def rollout_attn_append(ctx, problem, k_new_ptr, v_new_ptr, hip_stream=None):
     _check(load_library().rollout_attn_append(ctx, ctypes.byref(problem), k_new_ptr, v_new_ptr, hip_stream), ctx)
+
+
+def rollout_attn_check_prefill(prefill):
+    """Returns (status, message) of the host-side argument check of a prefill."""
+    buf = ctypes.create_string_buffer(512)
+    st = load_library().rollout_attn_check_prefill(ctypes.byref(prefill) if prefill is not None else None, buf, 512)
+    return int(st), buf.value.decode()
 
 
 def rollout_attn_prefill(ctx, prefill, hip_stream=None):

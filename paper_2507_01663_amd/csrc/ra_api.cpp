@@ -411,16 +411,18 @@ ra_status rollout_attn_append(ra_ctx *c, const ra_problem *p, const void *k_new,
     return RA_OK;
 }
 
-ra_status rollout_attn_prefill(ra_ctx *c, const ra_prefill *p, void *stream)
+static ra_status check_prefill(const ra_prefill *p, char *msg, size_t n)
 {
-    if (!c) { set_err(nullptr, "ctx is NULL"); return RA_ERR_INVALID_ARG; }
     auto fail = [&](ra_status st, const char *fmt, ...) {
-        va_list ap;
-        va_start(ap, fmt);
-        vsnprintf(c->err, sizeof c->err, fmt, ap);
-        va_end(ap);
+        if (msg && n) {
+            va_list ap;
+            va_start(ap, fmt);
+            vsnprintf(msg, n, fmt, ap);
+            va_end(ap);
+        }
         return st;
     };
+    if (msg && n) msg[0] = 0;
     if (!p) return fail(RA_ERR_INVALID_ARG, "prefill is NULL");
     if (p->num_prompts < 0 || p->total_tokens < 0 || p->max_prompt_len < 0 || p->Hq <= 0 || p->Hkv <= 0 || p->D <= 0)
         return fail(RA_ERR_INVALID_ARG, "negative or zero dimension (num_prompts=%d total_tokens=%d max_prompt_len=%d Hq=%d "
@@ -435,13 +437,6 @@ ra_status rollout_attn_prefill(ra_ctx *c, const ra_prefill *p, void *stream)
         return fail(RA_ERR_INVALID_ARG, "a required pointer (q, k, v, cu_seqlens, out, lse) is NULL");
     if (((uintptr_t)p->q | (uintptr_t)p->k | (uintptr_t)p->v | (uintptr_t)p->out) % 16 || (uintptr_t)p->lse % 4)
         return fail(RA_ERR_INVALID_ARG, "q, k, v and out must be 16-byte aligned, lse 4-byte aligned");
-    ra::PrefillLaunch a;
-    memset(&a, 0, sizeof a);
-    a.num_prompts = p->num_prompts; a.max_len = p->max_prompt_len; a.Hq = p->Hq; a.Hkv = p->Hkv; a.D = p->D; a.G = p->Hq / p->Hkv;
-    a.q = (const uint16_t *)p->q; a.k = (const uint16_t *)p->k; a.v = (const uint16_t *)p->v;
-    a.cu = p->cu_seqlens;
-    a.scale_log2 = p->softmax_scale * 1.4426950408889634f;
-    a.out = (uint16_t *)p->out; a.lse = p->lse; a.zeros = c->zeros;
     if (p->k_pool) {
         if (p->kv_dtype != RA_KV_BF16 && p->kv_dtype != RA_KV_FP8_E4M3)
             return fail(RA_ERR_INVALID_ARG, "kv_dtype=%d is not a ra_kv_dtype", p->kv_dtype);
@@ -457,6 +452,27 @@ ra_status rollout_attn_prefill(ra_ctx *c, const ra_prefill *p, void *stream)
         if (((uintptr_t)p->k_pool | (uintptr_t)p->v_pool) % 16)
             return fail(RA_ERR_INVALID_ARG, "k_pool and v_pool must be 16-byte aligned");
         if (es == 1 && (!p->k_scale || !p->v_scale)) return fail(RA_ERR_INVALID_ARG, "fp8 KV needs k_scale and v_scale");
+    }
+    return RA_OK;
+}
+
+ra_status rollout_attn_check_prefill(const ra_prefill *p, char *msg, size_t n) { return check_prefill(p, msg, n); }
+
+ra_status rollout_attn_prefill(ra_ctx *c, const ra_prefill *p, void *stream)
+{
+    if (!c) { set_err(nullptr, "ctx is NULL"); return RA_ERR_INVALID_ARG; }
+    ra_status st = check_prefill(p, c->err, sizeof c->err);
+    if (st != RA_OK) return st;
+    if (p->num_prompts == 0 || p->total_tokens == 0 || p->max_prompt_len == 0) return RA_OK;
+    ra::PrefillLaunch a;
+    memset(&a, 0, sizeof a);
+    a.num_prompts = p->num_prompts; a.max_len = p->max_prompt_len; a.Hq = p->Hq; a.Hkv = p->Hkv; a.D = p->D; a.G = p->Hq / p->Hkv;
+    a.q = (const uint16_t *)p->q; a.k = (const uint16_t *)p->k; a.v = (const uint16_t *)p->v;
+    a.cu = p->cu_seqlens;
+    a.scale_log2 = p->softmax_scale * 1.4426950408889634f;
+    a.out = (uint16_t *)p->out; a.lse = p->lse; a.zeros = c->zeros;
+    if (p->k_pool) {
+        const int es = p->kv_dtype == RA_KV_FP8_E4M3 ? 1 : 2;
         a.kv_fp8 = es == 1; a.num_pages = p->num_pages;
         a.k_pool = (uint8_t *)p->k_pool; a.v_pool = (uint8_t *)p->v_pool;
         a.stride_page_b = p->kv_stride_page * es; a.stride_head_b = p->kv_stride_head * es;
