@@ -80,7 +80,8 @@ int prefix_rows_max(int B, int G, int num_groups);
 size_t carve_workspace(Workspace &ws, void *base, int B, int Hkv, int G, int D, int num_groups, int waves);
 
 // LDS ring depth of the attention kernel and the number of its waves (= workgroups = spans of the page stream) to
-// launch on the current device, for head dim D: as many as are resident at once for bf16 pools, twice that for e4m3.
+// launch on the current device, for head dim D: as many as are resident at once (bf16 pools: one per SIMD; e4m3 pools:
+// up to two per SIMD, as many as the ring's LDS lets in).
 hipError_t attention_config(int D, int kv_fp8, int num_cus, int *stages, int *waves);
 
 // Streams nblocks * 16 KB of buf (nblocks a power of two, = waves * stages) through the attention kernel's ring

@@ -741,7 +741,7 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
         const int32_t *__restrict__ hdr, const uint32_t *__restrict__ seg_rec, const int32_t *__restrict__ members
 #define RA_ATTN_ARGS a, q, block_table, pfx_pages, hdr, seg_rec, members
 
-template <int D, int KVB, int NST> __device__ __forceinline__ void attention_body(RA_ATTN_PARAMS, int32_t *next_span)
+template <int D, int KVB, int NST, int NPEND> __device__ __forceinline__ void attention_body(RA_ATTN_PARAMS, int32_t *next_span)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     const uint32_t lds_addr = (uint32_t)(uintptr_t)lds;
@@ -753,7 +753,7 @@ template <int D, int KVB, int NST> __device__ __forceinline__ void attention_bod
     LaneConst<D, KVB> lc;
     lane_setup<D, KVB>(lc, lane, a.stride_token_b);
     Ring ring = {0, 0, 0};
-    Pending<D> pend[3], fresh;
+    Pending<D> pend[NPEND], fresh; // finished partials wait in registers for the end of the wave
     int npend = 0;
 
     // ---- walker: yields this wave's segments in stream order, span after span ----
@@ -827,15 +827,15 @@ template <int D, int KVB, int NST> __device__ __forceinline__ void attention_bod
         if (!cur.prefix) {
             run_segment<D, KVB, 1, NST>(a, q, members, cur, has_nxt, nxt, ring, lc, lds, lds_addr, fresh);
             fresh.slot = cur.slot;
-            if (npend == 3) { // full: write the oldest out
+            if (npend == NPEND) { // full: write the oldest out
                 store_pending<D>(a, pend[0], lane);
-                pend[0] = pend[1];
-                pend[1] = pend[2];
-                npend = 2;
+#pragma unroll
+                for (int k = 1; k < NPEND; k++) pend[k - 1] = pend[k];
+                npend = NPEND - 1;
             }
-            if (npend == 0) pend[0] = fresh;
-            else if (npend == 1) pend[1] = fresh;
-            else pend[2] = fresh;
+#pragma unroll
+            for (int k = 0; k < NPEND; k++)
+                if (k == npend) pend[k] = fresh;
             npend++;
         } else {
             run_segment<D, KVB, kPrefixTiles, NST>(a, q, members, cur, has_nxt, nxt, ring, lc, lds, lds_addr, fresh);
@@ -843,28 +843,29 @@ template <int D, int KVB, int NST> __device__ __forceinline__ void attention_bod
         cur = nxt;
         has_cur = has_nxt;
     }
-    if (npend > 0) store_pending<D>(a, pend[0], lane);
-    if (npend > 1) store_pending<D>(a, pend[1], lane);
-    if (npend > 2) store_pending<D>(a, pend[2], lane);
+#pragma unroll
+    for (int k = 0; k < NPEND; k++)
+        if (k < npend) store_pending<D>(a, pend[k], lane);
 }
 
 // Ring depths (in stages of two pages).  bf16 KV: two stages (32 KB + 8 KB of query slots, four waves per
-// compute unit) or three.  e4m3 KV: pages are half the size: three stages, or two.
+// compute unit) or three.  e4m3 KV: pages are half the size: three stages, or two; these kernels keep one finished
+// partial in registers instead of three and are held to half the register file, so that two waves share a SIMD.
 template <int D> __global__ __launch_bounds__(64) void attention_kernel_s3(RA_ATTN_PARAMS, int32_t *next_span)
 {
-    attention_body<D, 2, 3>(RA_ATTN_ARGS, next_span);
+    attention_body<D, 2, 3, 3>(RA_ATTN_ARGS, next_span);
 }
 template <int D> __global__ __launch_bounds__(64) void attention_kernel_s2(RA_ATTN_PARAMS, int32_t *next_span)
 {
-    attention_body<D, 2, 2>(RA_ATTN_ARGS, next_span);
+    attention_body<D, 2, 2, 3>(RA_ATTN_ARGS, next_span);
 }
-template <int D> __global__ __launch_bounds__(64) void attention_kernel_fp8(RA_ATTN_PARAMS, int32_t *next_span)
+template <int D> __global__ __launch_bounds__(64, 2) void attention_kernel_fp8(RA_ATTN_PARAMS, int32_t *next_span)
 {
-    attention_body<D, 1, 3>(RA_ATTN_ARGS, next_span);
+    attention_body<D, 1, 3, 1>(RA_ATTN_ARGS, next_span);
 }
-template <int D> __global__ __launch_bounds__(64) void attention_kernel_fp8_s2(RA_ATTN_PARAMS, int32_t *next_span)
+template <int D> __global__ __launch_bounds__(64, 2) void attention_kernel_fp8_s2(RA_ATTN_PARAMS, int32_t *next_span)
 {
-    attention_body<D, 1, 2>(RA_ATTN_ARGS, next_span);
+    attention_body<D, 1, 2, 1>(RA_ATTN_ARGS, next_span);
 }
 
 static size_t attention_lds_bytes(int D, int kv_fp8, int stages)
@@ -895,11 +896,11 @@ hipError_t attention_config(int D, int kv_fp8, int num_cus, int *stages, int *wa
     }
     size_t lds = attention_lds_bytes(D, kv_fp8, st);
     per_cu = (int)((160u * 1024u) / lds);
-    if (per_cu > 4) per_cu = 4; // one wave per SIMD
-    // e4m3 tiles are half the size, a wave spends a larger share of its time on arithmetic, and six workgroups fit a
-    // compute unit: twice as many, smaller spans (eight per compute unit, handed to the compute units as they free up)
-    // measured 8 % faster than four
-    if (kv_fp8 && per_cu == 4) per_cu = 8;
+    // bf16 pools: one wave per SIMD.  e4m3 pools: a wave spends a larger share of its time converting and multiplying,
+    // which a second wave on the same SIMD covers; those kernels are built to fit two waves per SIMD in the register
+    // file, so the ring's LDS decides how many are resident (six per compute unit for head dim 128)
+    const int cap = kv_fp8 ? 8 : 4;
+    if (per_cu > cap) per_cu = cap;
     if (const char *ev = getenv("ROLLOUT_ATTN_WAVES_PER_CU")) {
         int v = atoi(ev);
         if (v >= 1 && v <= 16) per_cu = v;
