@@ -236,6 +236,7 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
     for (int f = 0; f < 2; f++)
         for (int d = 0; d < 2; d++)
             if (e == hipSuccess) e = ra::attention_config(d ? 128 : 64, f, c->num_cus, &c->stages[f][d], &c->waves[f][d]);
+    if (e == hipSuccess) e = ra::prefill_config();
     if (e == hipSuccess && calibrate) {
         calibrate_dies(c->waves[0][1], c->xcd_w[0]);
         calibrate_dies(c->waves[1][1], c->xcd_w[1]);

@@ -94,6 +94,8 @@ hipError_t launch_merge(const Launch &a, hipStream_t s);
 // Writes the new K and V rows (bf16 [B][Hkv][D]) at position seq_lens[b] of every sequence; see append_kernel.
 hipError_t launch_append(const Launch &a, const void *k_new, const void *v_new, hipStream_t s);
 // Causal attention of the packed prompts (prefill_kernel) and the write of their K/V rows into pages.
+// Once per device, before the first launch_prefill: lets the prefill kernels have the LDS they ask for.
+hipError_t prefill_config();
 hipError_t launch_prefill(const PrefillLaunch &a, hipStream_t s);
 hipError_t launch_prefill_write(const PrefillLaunch &a, hipStream_t s);
 hipError_t launch_gather(const Launch &a, int b, int kvh, void *k_out, void *v_out, int64_t cap, hipStream_t s);

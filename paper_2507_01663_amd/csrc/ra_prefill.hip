@@ -406,26 +406,28 @@ template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel
     if (row < len && hh == 0) a.lse[rh] = (st.m + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
 }
 
+// LDS of a prefill workgroup: the ring and a scrap area
+template <int D> constexpr int prefill_lds_bytes() { return kPfSlots * 2 * Geo<D, 2>::kStage + 256 * kPfWaves; }
+
+hipError_t prefill_config()
+{
+    hipError_t e = hipFuncSetAttribute((const void *)prefill_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       prefill_lds_bytes<128>());
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute((const void *)prefill_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, prefill_lds_bytes<64>());
+}
+
 hipError_t launch_prefill(const PrefillLaunch &a, hipStream_t s)
 {
-    using G128 = Geo<128, 2>;
-    using G64 = Geo<64, 2>;
     const int nqb = (a.max_len + kPfBlock - 1) / kPfBlock;
     const int64_t pairs = (int64_t)a.num_prompts * a.Hkv; // dealt to eight dies, see the kernel
     const int64_t blocks = 8 * ((pairs + 7) / 8) * nqb * a.G;
     if (blocks == 0) return hipSuccess;
     if (blocks > INT32_MAX) return hipErrorInvalidValue;
-    if (a.D == 128) {
-        constexpr int lds = kPfSlots * 2 * G128::kStage + 256 * kPfWaves; // ring + scrap
-        hipError_t e = hipFuncSetAttribute((const void *)prefill_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(prefill_kernel<128>, dim3((unsigned)blocks), dim3(64 * kPfWaves), lds, s, a);
-    } else {
-        constexpr int lds = kPfSlots * 2 * G64::kStage + 256 * kPfWaves;
-        hipError_t e = hipFuncSetAttribute((const void *)prefill_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(prefill_kernel<64>, dim3((unsigned)blocks), dim3(64 * kPfWaves), lds, s, a);
-    }
+    if (a.D == 128)
+        hipLaunchKernelGGL(prefill_kernel<128>, dim3((unsigned)blocks), dim3(64 * kPfWaves), prefill_lds_bytes<128>(), s, a);
+    else
+        hipLaunchKernelGGL(prefill_kernel<64>, dim3((unsigned)blocks), dim3(64 * kPfWaves), prefill_lds_bytes<64>(), s, a);
     return hipGetLastError();
 }
 
