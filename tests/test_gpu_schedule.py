@@ -111,6 +111,47 @@ def dec():
     d.close()
 
 
+@pytest.fixture(scope="module")
+def dec_tail():
+    """A context whose schedule hands the last 30 % of the page stream out at run time, in spans of 8 pages (the
+    settings are read when the context is made)."""
+    import os
+    keys = {"ROLLOUT_ATTN_STATIC_PCT": "70", "ROLLOUT_ATTN_DYN_PAGES": "8"}
+    old = {k: os.environ.get(k) for k in keys}
+    os.environ.update(keys)
+    try:
+        d = ra.Decoder(0)
+    finally:
+        for k, v in old.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = v
+    yield d
+    d.close()
+
+
+@pytest.mark.parametrize("name", ["tiny", "mid7b", "mid72b", "grpo7b"])
+def test_schedule_with_a_tail_handed_out_at_run_time(dec_tail, name):
+    p = workload.make_problem(name, seed=2)
+    nspans = check_schedule(dec_tail, p, True, name + " (tail)")
+    info, _ = dec_tail.schedule(DeviceProblem(p).c)
+    if name == "grpo7b":
+        assert nspans > info.waves, "the tail was not cut into spans of its own"
+
+
+@pytest.mark.parametrize("name", ["tiny", "mid7b", "mid32b", "mid72b"])
+def test_parity_with_a_tail_handed_out_at_run_time(dec_tail, name):
+    import oracle
+    from gpu_util import compare
+    p = workload.make_problem(name, seed=0)
+    ref = oracle.decode(p)
+    for hint in (True, False):
+        dp = DeviceProblem(p, use_hint=hint)
+        dec_tail.decode(dp.c)
+        compare(*dp.results(), *ref, "%s (tail, hint %s)" % (name, hint))
+
+
 @pytest.mark.parametrize("name", ["tiny", "mid7b", "mid32b", "mid72b", "grpo7b"])
 def test_schedule_of_the_configurations(dec, name):
     p = workload.make_problem(name, seed=1)
