@@ -23,6 +23,11 @@
  * (out, lse, workspace) while the enqueued work runs, and is never retained
  * after that.  The library allocates device memory only in
  * rollout_attn_create() and frees it in rollout_attn_destroy().
+ * rollout_attn_decode (without RA_FLAG_VALIDATE and with timing off),
+ * rollout_attn_append and rollout_attn_prefill do nothing on the stream but
+ * launch kernels: no allocation, no memset, no copy, no synchronisation.  A
+ * caller may therefore record them into a HIP graph and replay it; the
+ * replays read whatever the buffers hold then (lengths, tables, queries).
  * No function throws or aborts; every failure is a status code, and
  * rollout_attn_last_error() describes the last one on that context.
  */
