@@ -72,7 +72,7 @@ size_t carve_workspace(Workspace &ws, void *base, int B, int Hkv, int G, int D, 
 }
 
 // ------------------------------------------------------------------------------------------------------
-// schedule (one workgroup): work rows, their cost, the scan, and each span's work list
+// schedule: work rows, their cost, the scan, and each span's work list
 //
 // Work rows: first the shared-prefix rows (one per group and block of kPrefixRows/G members), then one row
 // per sequence for its own pages.  A row of n pages costs a fixed amount plus weight*n per kv head, and the
@@ -166,40 +166,48 @@ struct Cuts {
     }
 };
 
-__global__ __launch_bounds__(kPlanThreads) void plan_rows_kernel(Launch a)
+// LDS of the rows phase (inputs and intermediates of batches of up to kPlanCap sequences and groups).
+struct RowsLds {
+    int32_t scan_tmp[34];
+    int32_t len[kPlanCap], grp[kPlanCap], poff[kPlanCap + 1];
+    int32_t grp_count[kPlanCap], grp_rowbase[kPlanCap + 1], grp_membase[kPlanCap + 1];
+    int32_t seq_rank[kPlanCap], row_start[2 * kPlanCap + 1];
+};
+
+// The rows phase: membership, the rows with their costs (scanned in place in row_start), the row table.  Returns
+// the number of rows and of shared-prefix rows among them.  `small` keeps everything in LDS (L), else the
+// intermediates live in the workspace.  Which rank a member gets inside its group depends on the order in which
+// the threads arrive, so only one workgroup may publish what depends on it (publish: the members' list and each
+// sequence's prefix row and place in it); the rows, their costs and the row table depend on counts alone and come out
+// the same in every workgroup that runs this.  tab: where the row table goes (LDS or the workspace).
+__device__ __forceinline__ void rows_phase(const Launch &a, RowsLds &L, bool small, bool publish, int4 *tab, int32_t *&row_start_out,
+                                           int &nR_out, int &nPR_out)
 {
-    touch_args(a);
-    __shared__ int32_t scan_tmp[34];
-    __shared__ int32_t l_len[kPlanCap], l_grp[kPlanCap], l_poff[kPlanCap + 1];
-    __shared__ int32_t l_grp_count[kPlanCap], l_grp_rowbase[kPlanCap + 1], l_grp_membase[kPlanCap + 1];
-    __shared__ int32_t l_seq_rank[kPlanCap], l_row_start[2 * kPlanCap + 1];
     const int tid = threadIdx.x;
     const Workspace &w = a.ws;
     const int B = a.B;
     const int NG = a.share ? a.num_groups : 0;
     const int MPR = a.members_per_row;
-    // inputs and intermediates live in LDS when they fit (the usual case), else in the workspace
-    const bool small = B <= kPlanCap && NG <= kPlanCap;
-    int32_t *grp_count = small ? l_grp_count : w.grp_count;
-    int32_t *grp_rowbase = small ? l_grp_rowbase : w.grp_rowbase;
-    int32_t *grp_membase = small ? l_grp_membase : w.grp_membase;
-    int32_t *seq_rank = small ? l_seq_rank : w.seq_rank;
-    int32_t *row_start = small ? l_row_start : w.row_start;
+    int32_t *grp_count = small ? L.grp_count : w.grp_count;
+    int32_t *grp_rowbase = small ? L.grp_rowbase : w.grp_rowbase;
+    int32_t *grp_membase = small ? L.grp_membase : w.grp_membase;
+    int32_t *seq_rank = small ? L.seq_rank : w.seq_rank;
+    int32_t *row_start = small ? L.row_start : w.row_start;
     const int32_t *len_src = a.seq_lens, *grp_src = a.seq_group, *poff = a.pfx_off;
     // one trip to memory for everything the schedule depends on
     if (small) {
         for (int b = tid; b < B; b += kPlanThreads) {
-            l_len[b] = a.seq_lens[b];
-            l_grp[b] = NG ? a.seq_group[b] : -1;
+            L.len[b] = a.seq_lens[b];
+            L.grp[b] = NG ? a.seq_group[b] : -1;
         }
-        for (int g = tid; g <= NG; g += kPlanThreads) l_poff[g] = NG ? a.pfx_off[g] : 0;
-        len_src = l_len, grp_src = l_grp, poff = l_poff;
+        for (int g = tid; g <= NG; g += kPlanThreads) L.poff[g] = NG ? a.pfx_off[g] : 0;
+        len_src = L.len, grp_src = L.grp, poff = L.poff;
     }
     for (int g = tid; g < NG; g += kPlanThreads) grp_count[g] = 0;
     __syncthreads();
     auto len_of = [&](int b) { // never walk past the table row
-        const int L = len_src[b];
-        return L < 0 ? 0 : (L > a.max_pages * kPage ? a.max_pages * kPage : L);
+        const int Lb = len_src[b];
+        return Lb < 0 ? 0 : (Lb > a.max_pages * kPage ? a.max_pages * kPage : Lb);
     };
     auto grp_of = [&](int b) {
         const int g = NG ? grp_src[b] : -1;
@@ -223,7 +231,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_rows_kernel(Launch a)
             grp_rowbase[g] = (grp_count[g] + MPR - 1) / MPR;
         }
         __syncthreads();
-        block_scan(grp_membase, grp_rowbase, NG, scan_tmp);
+        block_scan(grp_membase, grp_rowbase, NG, L.scan_tmp);
         nPR = grp_rowbase[NG];
     }
     // Rows and their cost per kv head (staged in row_start, scanned in place): an item of n > 0 pages costs
@@ -235,28 +243,47 @@ __global__ __launch_bounds__(kPlanThreads) void plan_rows_kernel(Launch a)
         for (int k = 0; k * MPR < cnt; k++) {
             const int left = cnt - k * MPR;
             row_start[r0 + k] = a.cost_item + np * a.cost_prefix;
-            w.row_tab[r0 + k] = make_int4(poff[g], grp_membase[g] + k * MPR, left < MPR ? left : MPR, np);
+            tab[r0 + k] = make_int4(poff[g], grp_membase[g] + k * MPR, left < MPR ? left : MPR, np);
         }
     }
     for (int b = tid; b < B; b += kPlanThreads) {
-        const int L = len_of(b);
+        const int Lb = len_of(b);
         const int rank = seq_rank[b];
         int skip = 0, prow = -1;
         if (rank >= 0) {
             const int g = grp_of(b);
             skip = poff[g + 1] - poff[g];
             prow = grp_rowbase[g] + rank / MPR;
-            w.members[grp_membase[g] + rank] = b;
+            if (publish) w.members[grp_membase[g] + rank] = b;
         }
-        w.seq_pfx_row[b] = prow;
-        w.seq_rank_in_row[b] = rank >= 0 ? rank % MPR : -1;
-        const int pages = L > 0 ? (L + kPage - 1) / kPage - skip : 0;
+        if (publish) {
+            w.seq_pfx_row[b] = prow;
+            w.seq_rank_in_row[b] = rank >= 0 ? rank % MPR : -1;
+        }
+        seq_rank[b] = prow; // from here on: the sequence's prefix row
+        const int pages = Lb > 0 ? (Lb + kPage - 1) / kPage - skip : 0;
         row_start[nPR + b] = pages > 0 ? a.cost_item + pages * kCostSuffix : 0;
-        w.row_tab[nPR + b] = make_int4(b, skip, L - skip * kPage, pages);
+        tab[nPR + b] = make_int4(b, skip, Lb - skip * kPage, pages);
     }
     __syncthreads();
     const int nR = B + nPR;
-    block_scan(row_start, nullptr, nR, scan_tmp);
+    block_scan(row_start, nullptr, nR, L.scan_tmp);
+    row_start_out = row_start;
+    nR_out = nR;
+    nPR_out = nPR;
+}
+
+__global__ __launch_bounds__(kPlanThreads) void plan_rows_kernel(Launch a)
+{
+    touch_args(a);
+    __shared__ RowsLds L;
+    const int tid = threadIdx.x;
+    const Workspace &w = a.ws;
+    // inputs and intermediates live in LDS when they fit (the usual case), else in the workspace
+    const bool small = a.B <= kPlanCap && (a.share ? a.num_groups : 0) <= kPlanCap;
+    int32_t *row_start;
+    int nR, nPR;
+    rows_phase(a, L, small, true, w.row_tab, row_start, nR, nPR);
 
     // hand over to the second kernel: the scanned row costs and the counts
     for (int r = tid; r <= nR; r += kPlanThreads) w.row_start[r] = row_start[r];
@@ -264,12 +291,125 @@ __global__ __launch_bounds__(kPlanThreads) void plan_rows_kernel(Launch a)
         w.hdr[0] = a.Hkv * row_start[nR];
         w.hdr[2] = nR;
         w.hdr[3] = nPR;
-        w.hdr[8] = 0; // overflow chunks in use
     }
 }
 
-// Second half of the schedule, spread over many compute units: the cuts, every span's work list, and the merge
-// descriptors.  Each workgroup first copies the scanned row costs and the row table into LDS.
+// Second half of the schedule: the cuts, every span's work list, and the merge descriptors.
+
+__device__ __forceinline__ void make_cuts(const Launch &a, int U, Cuts &cut)
+{
+    cut.U = U;
+    cut.waves = a.waves;
+    // no span is shorter than a few pages, and none is shorter than one page of either kind, so that every
+    // span between the first and the last one of an item holds at least one of its pages
+    int min_span = kMinUnitsPerWave * kCostSuffix;
+    if (min_span < 4 * a.cost_prefix) min_span = 4 * a.cost_prefix; // (a die's share is at least half the mean)
+    cut.S0 = a.static_pct >= 100 ? (int)(((unsigned)cut.U + a.waves - 1) / (unsigned)a.waves)
+                                 : (int)((unsigned)cut.U / (unsigned)a.waves) * a.static_pct / 100;
+    if (cut.S0 < min_span) cut.S0 = min_span;
+    cut.cd = a.dyn_pages * kCostSuffix;
+    if (cut.cd < min_span) cut.cd = min_span;
+    int ndyn = 0;
+    const long Ud = (long)cut.U - (long)cut.S0 * a.waves;
+    if (Ud > 0) {
+        const int most = kDynSpansPerWave * a.waves;
+        if (((unsigned)Ud + cut.cd - 1) / (unsigned)cut.cd > (unsigned)most) cut.cd = (int)(((unsigned)Ud + most - 1) / (unsigned)most);
+        ndyn = (int)(((unsigned)Ud + cut.cd - 1) / (unsigned)cut.cd);
+    }
+    cut.nspans = a.waves + ndyn;
+    cut.acc[0] = 0;
+#pragma unroll
+    for (int x = 0; x < 8; x++) cut.acc[x + 1] = cut.acc[x] + a.xcd_w[x];
+}
+
+// The work list of spans first, first + stride, ...: one record per segment (the pages of one (row, kv head) item
+// that lie in the span), so that the attention waves find their work with one load instead of walking the tables.
+// A record is {index of the row's first page id in its table, first page, end page, token limit,
+// kv head | prefix << 16, sequence (own pages) or first member slot (shared pages), query rows, partial slot}.
+// A span with more than kChunkSegs segments chains further chunks behind the spans' own: chunk number
+// nspans + (its first item) / kChunkSegs + 0, 1, ...  Items (row * Hkv + kv head) run in stream order, a span's
+// segments are different items and the next span starts at or after this one's last item, so no two spans reach
+// the same chunk, and there are at most (2 B Hkv) / kChunkSegs + 1 of them.
+__device__ __forceinline__ void spans_phase(const Launch &a, const Cuts &cut, const int32_t *row_start, const int4 *row_tab, int nR,
+                                            int nPR, int first, int stride)
+{
+    const Workspace &w = a.ws;
+    const int nspans = cut.nspans;
+    for (int c = first; c < nspans; c += stride) {
+        const int lo = cut.lo(c), hi = cut.lo(c + 1);
+        int chunk = c, n = 0, chain = -1;
+        if (lo < hi) {
+            // first row of the span: the last row that starts at or before the span's first unit
+            int r = 0, rhi = nR; // invariant: Hkv*row_start[r] <= lo < Hkv*row_start[rhi]
+            while (rhi - r > 1) {
+                const int mid = (r + rhi) >> 1;
+                if ((long)a.Hkv * row_start[mid] <= lo) r = mid;
+                else rhi = mid;
+            }
+            for (; r < nR; r++) {
+                const int rs = a.Hkv * row_start[r];
+                if (rs >= hi) break;
+                const int ic = row_start[r + 1] - row_start[r]; // cost of one item of the row
+                if (ic == 0) continue;
+                const int4 info = row_tab[r];
+                const bool prefix = r < nPR;
+                const int cw = prefix ? a.cost_prefix : kCostSuffix;
+                for (int kvh = lo > rs ? (lo - rs) / ic : 0; kvh < a.Hkv; kvh++) {
+                    const int S = rs + kvh * ic;
+                    if (S >= hi) break;
+                    int p_lo, p_hi;
+                    span_pages(S + a.cost_item, cw, info.w, lo, hi, p_lo, p_hi);
+                    if (p_lo >= p_hi) continue;
+                    if (chain < 0) chain = nspans + (r * a.Hkv + kvh) / kChunkSegs; // where this span's further chunks go
+                    if (n == kChunkSegs) { // chain another chunk
+                        const int nc = chain++;
+                        w.seg_rec[(size_t)chunk * 16] = make_int4(n, nc, 0, 0);
+                        chunk = nc;
+                        n = 0;
+                    }
+                    int4 *rec = w.seg_rec + (size_t)chunk * 16 + 2 * (1 + n);
+                    if (!prefix) {
+                        rec[0] = make_int4(info.x * a.max_pages + info.y, p_lo, p_hi, min(info.z, p_hi * kPage));
+                        rec[1] = make_int4(kvh, info.x, a.G, info.x * a.Hkv + kvh + c);
+                    } else {
+                        rec[0] = make_int4(info.x, p_lo, p_hi, p_hi * kPage);
+                        rec[1] = make_int4(kvh | (1 << 16), info.y, info.z * a.G, r * a.Hkv + kvh + c);
+                    }
+                    n++;
+                }
+            }
+        }
+        w.seg_rec[(size_t)chunk * 16] = make_int4(n, -1, 0, 0);
+    }
+}
+
+// For the merge: the spans that hold pages of (sequence, kv head) item i's own row and of its prefix row prow (or -1),
+// {pages, first span, last span, unused}.  Every span in that range holds at least one of the pages.
+__device__ __forceinline__ void merge_desc_of(const Launch &a, const Cuts &cut, const int32_t *row_start, int nPR, int i, int prow)
+{
+    const int b = i / a.Hkv, kvh = i - b * a.Hkv;
+    int4 own = make_int4(0, 0, -1, 0), pfx = make_int4(0, 0, -1, 0);
+    {
+        const int r = nPR + b;
+        const int ic = row_start[r + 1] - row_start[r];
+        if (ic > 0) {
+            const int n = (ic - a.cost_item) / kCostSuffix;
+            const int S = a.Hkv * row_start[r] + kvh * ic + a.cost_item;
+            own = make_int4(n, cut.span_of(S), cut.span_of(S + kCostSuffix * (n - 1)), 0);
+        }
+    }
+    if (prow >= 0) {
+        const int ic = row_start[prow + 1] - row_start[prow];
+        const int n = (ic - a.cost_item) / a.cost_prefix;
+        const int S = a.Hkv * row_start[prow] + kvh * ic + a.cost_item;
+        pfx = make_int4(n, cut.span_of(S), cut.span_of(S + a.cost_prefix * (n - 1)), 0);
+    }
+    a.ws.merge_desc[2 * i] = own;
+    a.ws.merge_desc[2 * i + 1] = pfx;
+}
+
+// The second kernel of the two-kernel schedule (batches too large for the one below), spread over many compute units.
+// Each workgroup first copies the scanned row costs and the row table into LDS if they fit.
 constexpr int kSpanThreads = 128;
 
 __global__ __launch_bounds__(kSpanThreads) void plan_spans_kernel(Launch a)
@@ -295,115 +435,56 @@ __global__ __launch_bounds__(kSpanThreads) void plan_spans_kernel(Launch a)
     __syncthreads();
 
     Cuts cut;
-    cut.U = U;
-    cut.waves = a.waves;
-    // no span is shorter than a few pages, and none is shorter than one page of either kind, so that every
-    // span between the first and the last one of an item holds at least one of its pages
-    int min_span = kMinUnitsPerWave * kCostSuffix;
-    if (min_span < 4 * a.cost_prefix) min_span = 4 * a.cost_prefix; // (a die's share is at least half the mean)
-    cut.S0 = a.static_pct >= 100 ? (int)(((unsigned)cut.U + a.waves - 1) / (unsigned)a.waves)
-                                 : (int)((unsigned)cut.U / (unsigned)a.waves) * a.static_pct / 100;
-    if (cut.S0 < min_span) cut.S0 = min_span;
-    cut.cd = a.dyn_pages * kCostSuffix;
-    if (cut.cd < min_span) cut.cd = min_span;
-    int ndyn = 0;
-    const long Ud = (long)cut.U - (long)cut.S0 * a.waves;
-    if (Ud > 0) {
-        const int most = kDynSpansPerWave * a.waves;
-        if (((unsigned)Ud + cut.cd - 1) / (unsigned)cut.cd > (unsigned)most) cut.cd = (int)(((unsigned)Ud + most - 1) / (unsigned)most);
-        ndyn = (int)(((unsigned)Ud + cut.cd - 1) / (unsigned)cut.cd);
-    }
-    cut.nspans = a.waves + ndyn;
-    cut.acc[0] = 0;
-#pragma unroll
-    for (int x = 0; x < 8; x++) cut.acc[x + 1] = cut.acc[x] + a.xcd_w[x];
-    const int nspans = cut.nspans;
+    make_cuts(a, U, cut);
     if (gtid == 0) {
         w.hdr[5] = a.waves; // next span to hand out
-        w.hdr[7] = nspans;
+        w.hdr[7] = cut.nspans;
     }
-    // The work list of every span: one record per segment (the pages of one (row, kv head) item that lie in
-    // the span), so that the attention waves find their work with one load instead of walking these tables.
-    // A record is {index of the row's first page id in its table, first page, end page, token limit,
-    // kv head | prefix << 16, sequence (own pages) or first member slot (shared pages), query rows, partial slot}.
-    for (int c = gtid; c < nspans; c += gstride) {
-        const int lo = cut.lo(c), hi = cut.lo(c + 1);
-        int chunk = c, n = 0;
-        if (lo < hi) {
-            // first row of the span: the last row that starts at or before the span's first unit
-            int r = 0, rhi = nR; // invariant: Hkv*row_start[r] <= lo < Hkv*row_start[rhi]
-            while (rhi - r > 1) {
-                const int mid = (r + rhi) >> 1;
-                if ((long)a.Hkv * row_start[mid] <= lo) r = mid;
-                else rhi = mid;
-            }
-            for (; r < nR; r++) {
-                const int rs = a.Hkv * row_start[r];
-                if (rs >= hi) break;
-                const int ic = row_start[r + 1] - row_start[r]; // cost of one item of the row
-                if (ic == 0) continue;
-                const int4 info = row_tab[r];
-                const bool prefix = r < nPR;
-                const int cw = prefix ? a.cost_prefix : kCostSuffix;
-                for (int kvh = lo > rs ? (lo - rs) / ic : 0; kvh < a.Hkv; kvh++) {
-                    const int S = rs + kvh * ic;
-                    if (S >= hi) break;
-                    int p_lo, p_hi;
-                    span_pages(S + a.cost_item, cw, info.w, lo, hi, p_lo, p_hi);
-                    if (p_lo >= p_hi) continue;
-                    if (n == kChunkSegs) { // chain another chunk
-                        const int nc = nspans + atomicAdd(&w.hdr[8], 1);
-                        w.seg_rec[(size_t)chunk * 16] = make_int4(n, nc, 0, 0);
-                        chunk = nc;
-                        n = 0;
-                    }
-                    int4 *rec = w.seg_rec + (size_t)chunk * 16 + 2 * (1 + n);
-                    if (!prefix) {
-                        rec[0] = make_int4(info.x * a.max_pages + info.y, p_lo, p_hi, min(info.z, p_hi * kPage));
-                        rec[1] = make_int4(kvh, info.x, a.G, info.x * a.Hkv + kvh + c);
-                    } else {
-                        rec[0] = make_int4(info.x, p_lo, p_hi, p_hi * kPage);
-                        rec[1] = make_int4(kvh | (1 << 16), info.y, info.z * a.G, r * a.Hkv + kvh + c);
-                    }
-                    n++;
-                }
-            }
+    spans_phase(a, cut, row_start, row_tab, nR, nPR, gtid, gstride);
+    for (int i = gtid; i < a.B * a.Hkv; i += gstride) merge_desc_of(a, cut, row_start, nPR, i, i == gtid ? my_prow : w.seq_pfx_row[i / a.Hkv]);
+}
+
+// The whole schedule in one launch, for batches whose tables fit in LDS (up to kPlanCap sequences and groups): every
+// workgroup works the rows out for itself, which costs less than a second launch and a trip through memory.
+// Workgroup 0 publishes what the other kernels read (members, prefix rows, counts) and writes the merge descriptors;
+// the others write the spans' work lists.
+__global__ __launch_bounds__(kPlanThreads) void plan_fused_kernel(Launch a)
+{
+    touch_args(a);
+    __shared__ RowsLds L;
+    __shared__ int4 l_row_tab[2 * kPlanCap];
+    const int tid = threadIdx.x;
+    const Workspace &w = a.ws;
+    int32_t *row_start;
+    int nR, nPR;
+    rows_phase(a, L, true, blockIdx.x == 0, l_row_tab, row_start, nR, nPR);
+    Cuts cut;
+    make_cuts(a, a.Hkv * row_start[nR], cut);
+    if (blockIdx.x == 0) {
+        if (tid == 0) {
+            w.hdr[0] = cut.U;
+            w.hdr[2] = nR;
+            w.hdr[3] = nPR;
+            w.hdr[5] = a.waves; // next span to hand out
+            w.hdr[7] = cut.nspans;
         }
-        w.seg_rec[(size_t)chunk * 16] = make_int4(n, -1, 0, 0);
-    }
-    // For the merge: the spans that hold pages of each (sequence, kv head)'s own row and of its prefix row,
-    // {pages, first span, last span, unused}.  Every span in that range holds at least one of the pages.
-    for (int i = gtid; i < a.B * a.Hkv; i += gstride) {
-        const int b = i / a.Hkv, kvh = i - b * a.Hkv;
-        int4 own = make_int4(0, 0, -1, 0), pfx = make_int4(0, 0, -1, 0);
-        {
-            const int r = nPR + b;
-            const int ic = row_start[r + 1] - row_start[r];
-            if (ic > 0) {
-                const int n = (ic - a.cost_item) / kCostSuffix;
-                const int S = a.Hkv * row_start[r] + kvh * ic + a.cost_item;
-                own = make_int4(n, cut.span_of(S), cut.span_of(S + kCostSuffix * (n - 1)), 0);
-            }
-        }
-        const int r = i == gtid ? my_prow : w.seq_pfx_row[b];
-        if (r >= 0) {
-            const int ic = row_start[r + 1] - row_start[r];
-            const int n = (ic - a.cost_item) / a.cost_prefix;
-            const int S = a.Hkv * row_start[r] + kvh * ic + a.cost_item;
-            pfx = make_int4(n, cut.span_of(S), cut.span_of(S + a.cost_prefix * (n - 1)), 0);
-        }
-        w.merge_desc[2 * i] = own;
-        w.merge_desc[2 * i + 1] = pfx;
+        for (int i = tid; i < a.B * a.Hkv; i += kPlanThreads) merge_desc_of(a, cut, row_start, nPR, i, L.seq_rank[i / a.Hkv]);
+    } else {
+        spans_phase(a, cut, row_start, l_row_tab, nR, nPR, (blockIdx.x - 1) * kPlanThreads + tid, (gridDim.x - 1) * kPlanThreads);
     }
 }
 
 hipError_t launch_plan(const Launch &a, hipStream_t s)
 {
-    hipLaunchKernelGGL(plan_rows_kernel, dim3(1), dim3(kPlanThreads), 0, s, a);
-    // one thread per span and per (sequence, kv head); the span count is only known on the device, so the grid
-    // covers the most there can be
+    // one thread per span; the span count is only known on the device, so the grid covers the most there can be
     const int most = (1 + kDynSpansPerWave) * a.waves;
     const int work = a.static_pct >= 100 ? a.waves : most;
+    if (a.B <= kPlanCap && (a.share ? a.num_groups : 0) <= kPlanCap) {
+        hipLaunchKernelGGL(plan_fused_kernel, dim3(1 + (work + kPlanThreads - 1) / kPlanThreads), dim3(kPlanThreads), 0, s, a);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(plan_rows_kernel, dim3(1), dim3(kPlanThreads), 0, s, a);
+    // ... and per (sequence, kv head)
     const int n = work > a.B * a.Hkv ? work : a.B * a.Hkv;
     hipLaunchKernelGGL(plan_spans_kernel, dim3((n + kSpanThreads - 1) / kSpanThreads), dim3(kSpanThreads), 0, s, a);
     return hipGetLastError();
