@@ -124,7 +124,19 @@ uint32_t rollout_attn_abi_version(void);
  * memory that the context keeps, and measures for about a millisecond how the memory bandwidth is shared
  * among the device's dies (the attention kernel balances its work by that; the measurement borrows 256 MiB
  * of device memory and returns it before the call ends, and is skipped when that much is not free).
- * *ctx is NULL on failure.  RA_ERR_DEVICE when the device cannot be used. */
+ * *ctx is NULL on failure.  RA_ERR_DEVICE when the device cannot be used.
+ *
+ * Tuning knobs, read from the environment here and nowhere else (none changes a result beyond rounding; values
+ * out of range are ignored):
+ *   ROLLOUT_ATTN_CALIBRATE=0        skip the measurement and use built-in die weights
+ *   ROLLOUT_ATTN_XCD_WEIGHTS=a,..,h the eight die weights, per mille of the mean (700..1400); implies the above
+ *   ROLLOUT_ATTN_STAGES=2|3, ROLLOUT_ATTN_FP8_STAGES=2|3   depth of the LDS ring for bf16 / e4m3 pools
+ *   ROLLOUT_ATTN_WAVES_PER_CU=1..16 attention workgroups per compute unit (default: as many as are resident)
+ *   ROLLOUT_ATTN_STATIC_PCT=0..100  share of the work assigned to workgroups up front (default 100); the rest is
+ *                                   handed out at run time in spans of ROLLOUT_ATTN_DYN_PAGES=1..4096 pages
+ *   ROLLOUT_ATTN_COST_PREFIX=1..16, ROLLOUT_ATTN_COST_ITEM=0..256   scheduling weights of a shared-prefix page and
+ *                                   of a segment (a page of a sequence's own weighs 4)
+ *   ROLLOUT_ATTN_VERBOSE            print the die weights to stderr */
 ra_status rollout_attn_create(ra_ctx **ctx, int device_ordinal);
 
 /* Frees the context's device memory.  NULL is accepted.  Work already enqueued must have finished. */
