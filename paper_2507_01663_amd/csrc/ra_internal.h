@@ -19,7 +19,7 @@ constexpr int kCostItem = 16;       // ... of a segment, on top of its pages
 // Device pointers into the caller's workspace.  All offsets are fixed by the shape alone.
 struct Workspace {
     int32_t *hdr;            // [16]: 0 total cost units, 2 rows, 3 prefix rows, 4 error flags, 5 next span to hand out,
-                             //       7 spans, 8 overflow chunks of the work lists in use
+                             //       7 spans
     int32_t *grp_count;      // [num_groups]      members that use the shared pass
     int32_t *grp_rowbase;    // [num_groups + 1]  first prefix row of the group (relative)
     int32_t *grp_membase;    // [num_groups + 1]  first slot of the group in members[]

@@ -96,44 +96,52 @@ constexpr int kPlanThreads = 256;
 constexpr int kPlanCap = 2048; // sequences / groups whose intermediate arrays fit in LDS; beyond, the workspace is used
 
 // Exclusive scans of a[0..n) and b[0..n) in place, a[n] and b[n] = totals (b may be null).  All threads call it.
+// A thread sums a run of consecutive elements, the threads' sums are scanned (shuffles inside a wave, the waves'
+// totals through tmp), and each thread writes its run back: three barriers whatever n is.
 __device__ void block_scan(int32_t *a, int32_t *b, int n, int32_t *tmp /*[34], LDS*/)
 {
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    int carry_a = 0, carry_b = 0;
-    for (int base = 0; base < n; base += kPlanThreads) {
-        const int i = base + tid;
-        const int va = i < n ? a[i] : 0, vb = b && i < n ? b[i] : 0;
-        int xa = va, xb = vb;
+    const int per = (n + kPlanThreads - 1) / kPlanThreads;
+    const int i0 = tid * per < n ? tid * per : n, i1 = i0 + per < n ? i0 + per : n;
+    int sa = 0, sb = 0;
+    for (int i = i0; i < i1; i++) {
+        sa += a[i];
+        if (b) sb += b[i];
+    }
+    int xa = sa, xb = sb;
 #pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const int ya = __shfl_up(xa, d), yb = __shfl_up(xb, d);
-            if (lane >= d) xa += ya, xb += yb;
-        }
-        if (lane == 63) tmp[wv] = xa, tmp[17 + wv] = xb;
-        __syncthreads();
-        if (wv == 0) {
-            const int ta = lane < kPlanThreads / 64 ? tmp[lane] : 0, tb = lane < kPlanThreads / 64 ? tmp[17 + lane] : 0;
-            int sa = ta, sb = tb;
+    for (int d = 1; d < 64; d <<= 1) {
+        const int ya = __shfl_up(xa, d), yb = __shfl_up(xb, d);
+        if (lane >= d) xa += ya, xb += yb;
+    }
+    if (lane == 63) tmp[wv] = xa, tmp[17 + wv] = xb;
+    __syncthreads();
+    if (wv == 0) {
+        const int ta = lane < kPlanThreads / 64 ? tmp[lane] : 0, tb = lane < kPlanThreads / 64 ? tmp[17 + lane] : 0;
+        int ua = ta, ub = tb;
 #pragma unroll
-            for (int d = 1; d < 16; d <<= 1) {
-                const int ya = __shfl_up(sa, d), yb = __shfl_up(sb, d);
-                if (lane >= d) sa += ya, sb += yb;
-            }
-            if (lane < kPlanThreads / 64) tmp[lane] = sa - ta, tmp[17 + lane] = sb - tb;
-            if (lane == kPlanThreads / 64 - 1) tmp[16] = sa, tmp[33] = sb;
+        for (int d = 1; d < 16; d <<= 1) {
+            const int ya = __shfl_up(ua, d), yb = __shfl_up(ub, d);
+            if (lane >= d) ua += ya, ub += yb;
         }
-        __syncthreads();
-        if (i < n) {
-            a[i] = carry_a + tmp[wv] + xa - va;
-            if (b) b[i] = carry_b + tmp[17 + wv] + xb - vb;
+        if (lane < kPlanThreads / 64) tmp[lane] = ua - ta, tmp[17 + lane] = ub - tb;
+        if (lane == kPlanThreads / 64 - 1) tmp[16] = ua, tmp[33] = ub;
+    }
+    __syncthreads();
+    int ea = tmp[wv] + xa - sa, eb = tmp[17 + wv] + xb - sb; // what precedes this thread's run
+    for (int i = i0; i < i1; i++) {
+        const int va = a[i];
+        a[i] = ea;
+        ea += va;
+        if (b) {
+            const int vb = b[i];
+            b[i] = eb;
+            eb += vb;
         }
-        carry_a += tmp[16];
-        carry_b += tmp[33];
-        __syncthreads();
     }
     if (tid == 0) {
-        a[n] = carry_a;
-        if (b) b[n] = carry_b;
+        a[n] = tmp[16];
+        if (b) b[n] = tmp[33];
     }
     __syncthreads();
 }
