@@ -37,6 +37,18 @@ def test_no_scratch_and_no_full_drain_in_the_page_loop(isa):
 
 
 
+def test_e4m3_kernels_fit_two_waves_per_simd(isa):
+    """The e4m3 decode kernels are scheduled for two waves on a SIMD (six workgroups per compute unit at head dim
+    128): that holds only while they stay within half of the 512 registers a lane has, without scratch."""
+    seen = 0
+    for m in re.finditer(r"\.amdhsa_kernel (_ZN2ra\d+attention_kernel_fp8\w+)\n(.*?)\.end_amdhsa_kernel", isa, flags=re.S):
+        regs = int(re.search(r"\.amdhsa_next_free_vgpr (\d+)", m.group(2)).group(1))
+        scratch = int(re.search(r"\.amdhsa_private_segment_fixed_size (\d+)", m.group(2)).group(1))
+        assert regs <= 256 and scratch == 0, (m.group(1), regs, scratch)
+        seen += 1
+    assert seen == 4    # two ring depths, two head dims
+
+
 def test_prefill_kernels_keep_their_accumulators_in_registers():
     import tempfile
     from paper_2507_01663_amd import build
