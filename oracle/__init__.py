@@ -11,7 +11,8 @@ Sec. 2.1.1; groups of responses to one prompt, Sec. 7.1; highly variable
 response lengths, Sec. 7.4) but prints no formula for it; the definition
 used is textbook scaled-dot-product attention with grouped query heads and a
 paged cache, as written out at the top of the C file.  The same C file holds
-the oracle of the KV append (``append`` below); ``oracle/balance.py`` is the
+the oracle of the KV append (``append`` below) and of the prompt prefill and
+its cache write (``prefill``, ``prefill_write``); ``oracle/balance.py`` is the
 oracle of the token-balanced dispatch.
 """
 import ctypes
@@ -59,6 +60,10 @@ def _lib():
         lib.oracle_prefill.restype = ctypes.c_int
         lib.oracle_prefill.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int,
                                        ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
+        lib.oracle_prefill_write.restype = ctypes.c_int
+        lib.oracle_prefill_write.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                             ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         lib.oracle_append.restype = ctypes.c_int
         lib.oracle_append.argtypes = [ctypes.POINTER(_CProblem), ctypes.c_void_p, ctypes.c_void_p]
         _LIB = lib
@@ -217,3 +222,28 @@ def prefill(q, k, v, cu_seqlens, softmax_scale, nthreads=0):
     _raise(_lib().oracle_prefill(q.ctypes.data, k.ctypes.data, v.ctypes.data, cu.ctypes.data, cu.size - 1, Hq, Hkv, D,
                                  float(np.float32(softmax_scale)), out.ctypes.data, lse.ctypes.data, nthreads))
     return out, lse
+
+
+def prefill_write(k, v, cu_seqlens, page_offsets, pages, k_pool, v_pool, k_scale=None, v_scale=None):
+    """Cache write of the prompt prefill (see the C file): the prompts' K and V rows (bf16 bits, uint16
+    [T, Hkv, D]) go into the pages listed per prompt.  ``k_pool``, ``v_pool``: C-contiguous
+    [num_pages, Hkv, page, D], uint16 (bit patterns are copied) or uint8 (e4m3 codes, one scale per (page, head)
+    written to ``k_scale``, ``v_scale``: float32 [num_pages, Hkv]); all modified in place, everything that
+    receives no token is left as it was."""
+    k = np.ascontiguousarray(k, dtype=np.uint16)
+    v = np.ascontiguousarray(v, dtype=np.uint16)
+    cu = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
+    po = np.ascontiguousarray(page_offsets, dtype=np.int32)
+    pg = np.ascontiguousarray(pages, dtype=np.int32)
+    fp8 = k_pool.dtype == np.uint8
+    for a in (k_pool, v_pool):
+        assert a.dtype == (np.uint8 if fp8 else np.uint16) and a.flags["C_CONTIGUOUS"] and a.flags["WRITEABLE"]
+    num_pages, Hkv, page, D = k_pool.shape
+    assert v_pool.shape == k_pool.shape and k.shape[1:] == (Hkv, D) and v.shape == k.shape
+    assert po.size == cu.size and (pg.size == 0 or po[-1] <= pg.size)
+    if fp8:
+        for a in (k_scale, v_scale):
+            assert a.dtype == np.float32 and a.shape == (num_pages, Hkv) and a.flags["C_CONTIGUOUS"] and a.flags["WRITEABLE"]
+    _raise(_lib().oracle_prefill_write(k.ctypes.data, v.ctypes.data, cu.ctypes.data, cu.size - 1, Hkv, D, page, po.ctypes.data,
+                                       pg.ctypes.data if pg.size else None, num_pages, 1 if fp8 else 0, k_pool.ctypes.data,
+                                       v_pool.ctypes.data, k_scale.ctypes.data if fp8 else None, v_scale.ctypes.data if fp8 else None))

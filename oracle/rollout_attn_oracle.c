@@ -397,9 +397,9 @@ int oracle_append(const oracle_problem *p, const uint16_t *k_new, const uint16_t
  *     s_j  = scale * <q[t,h,:], k[cu[g]+j, kv, :]>        j = 0..i   (causal)
  *     out[t,h,:] = sum_j softmax(s)_j * v[cu[g]+j, kv, :],  lse[t,h] = ln sum_j exp(s_j)
  * in fp64, two passes, no tiling.  Writing K and V into the group's pages is
- * a copy (bf16) or the whole-page quantisation the input generator uses
- * (e4m3) and is checked by the tests directly; this function is the
- * arithmetic.
+ * oracle_prefill_write below; this function is the arithmetic.  Returns 0,
+ * 1 for bad arguments, 3 when memory for a row's scores could not be had
+ * (that row's outputs are then undefined).
  * ------------------------------------------------------------------------ */
 int oracle_prefill(const uint16_t *q, const uint16_t *k, const uint16_t *v, const int32_t *cu, int ngroups, int Hq, int Hkv,
                    int D, float softmax_scale, double *out, double *lse, int nthreads)
@@ -426,8 +426,11 @@ int oracle_prefill(const uint16_t *q, const uint16_t *k, const uint16_t *v, cons
             for (int h = 0; h < Hq; h++) {
                 const int kv = h / G, n = t - t0 + 1;
                 double *s = (double *)malloc((size_t)n * sizeof(double));
-                if (!s)
+                if (!s) {
+#pragma omp atomic write
+                    rc = 3;
                     continue;
+                }
                 const uint16_t *qr = q + ((int64_t)t * Hq + h) * D;
                 double M = -INFINITY;
                 for (int j = 0; j < n; j++) {
@@ -456,4 +459,70 @@ int oracle_prefill(const uint16_t *q, const uint16_t *k, const uint16_t *v, cons
             }
     }
     return rc;
+}
+
+/* ------------------------------------------------------------------------
+ * Cache write of the prompt prefill: the K and V rows of every prompt go
+ * into the pages listed for it, token i of prompt g to page
+ * pages[page_off[g] + i / page], slot i % page, every kv head (the pages the
+ * members of a prompt group then share, paper Sec. 7.1; the paper does not
+ * define the write).  Pools are contiguous [num_pages][Hkv][page][D].
+ *   bf16 pools: the 16-bit patterns are copied.
+ *   e4m3 pools, one (page, kv head) at a time, K and V alike, in IEEE
+ *   binary32: a = largest |x| over the rows written to the page;
+ *   scale = a > 0 ? a / 448 : 1; code = nearest E4M3 of x / scale (ties to
+ *   the even code); the scale goes to scale[page][kv].
+ * Slots of a last, partly filled page that receive no token, pages that no
+ * prompt lists and their scales are left untouched.  A page id outside
+ * [0, num_pages) is skipped, and so are tokens beyond the listed pages.
+ * ------------------------------------------------------------------------ */
+int oracle_prefill_write(const uint16_t *k, const uint16_t *v, const int32_t *cu, int ngroups, int Hkv, int D, int page_size,
+                         const int32_t *page_off, const int32_t *pages, int num_pages, int kv_dtype, void *k_pool, void *v_pool,
+                         float *k_scale, float *v_scale)
+{
+    if (ngroups < 0 || Hkv <= 0 || D <= 0 || page_size <= 0 || (kv_dtype != 0 && kv_dtype != 1))
+        return 1;
+    if (kv_dtype == 1 && (!k_scale || !v_scale))
+        return 1;
+    for (int g = 0; g < ngroups; g++) {
+        const int t0 = cu[g], len = cu[g + 1] - cu[g];
+        const int npages = page_off[g + 1] - page_off[g];
+        for (int pi = 0; pi < npages; pi++) {
+            const int pid = pages[page_off[g] + pi];
+            const int first = pi * page_size;
+            int n = len - first; /* rows that land in this page */
+            if (n > page_size)
+                n = page_size;
+            if (n <= 0 || pid < 0 || pid >= num_pages)
+                continue;
+            for (int kv = 0; kv < Hkv; kv++)
+                for (int which = 0; which < 2; which++) {
+                    const uint16_t *src = which ? v : k;
+                    void *pool = which ? v_pool : k_pool;
+                    float *scales = which ? v_scale : k_scale;
+                    const int64_t tile = (((int64_t)pid * Hkv + kv) * page_size) * D;
+                    if (kv_dtype == 0) {
+                        for (int r = 0; r < n; r++)
+                            for (int d = 0; d < D; d++)
+                                ((uint16_t *)pool)[tile + (int64_t)r * D + d] = src[((int64_t)(t0 + first + r) * Hkv + kv) * D + d];
+                        continue;
+                    }
+                    float a = 0.0f;
+                    for (int r = 0; r < n; r++)
+                        for (int d = 0; d < D; d++) {
+                            const float x = fabsf(bf16_to_f32(src[((int64_t)(t0 + first + r) * Hkv + kv) * D + d]));
+                            if (x > a)
+                                a = x;
+                        }
+                    const float s = a > 0.0f ? a / 448.0f : 1.0f;
+                    for (int r = 0; r < n; r++)
+                        for (int d = 0; d < D; d++) {
+                            const float x = bf16_to_f32(src[((int64_t)(t0 + first + r) * Hkv + kv) * D + d]);
+                            ((uint8_t *)pool)[tile + (int64_t)r * D + d] = oracle_e4m3_encode(x / s);
+                        }
+                    scales[(int64_t)pid * Hkv + kv] = s;
+                }
+        }
+    }
+    return 0;
 }
