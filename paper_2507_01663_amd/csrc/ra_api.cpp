@@ -14,10 +14,8 @@ struct ra_ctx {
     int num_cus;
     int waves[2][2];  // resident attention waves, [e4m3 KV][D == 128]
     int stages[2][2]; // LDS ring depth, same indices
-    int cost_prefix; // scheduling weight of a shared-prefix page
+    int cost_prefix[2]; // scheduling weight of a shared-prefix page, [e4m3 KV]
     int cost_item;   // ... of a segment, on top of its pages
-    int static_pct;  // share of the work that is assigned to waves up front
-    int dyn_pages;   // pages per dynamically scheduled span
     int xcd_w[2][8]; // relative speed of the accelerator dies, measured in the launch shape of [e4m3 KV]
     void *zeros;  // 256 bytes of zeros on the device
     int32_t *host_flags; // pinned, for RA_FLAG_VALIDATE
@@ -101,11 +99,11 @@ void fill_launch(ra::Launch &a, const ra_ctx *ctx, const ra_problem *p)
     a.share = p->num_groups > 0 && !(p->flags & RA_FLAG_NO_PREFIX_SHARING);
     a.waves = ctx ? ctx->waves[a.kv_fp8][p->D == 128] : 2048;
     a.stages = ctx ? ctx->stages[a.kv_fp8][p->D == 128] : 4;
-    a.members_per_row = ra::kPrefixRows / a.G;
-    a.cost_prefix = ctx ? ctx->cost_prefix : ra::kCostPrefix;
+    a.prefix_rows = ra::prefix_rows(a.kv_fp8);
+    a.members_per_row = a.prefix_rows / a.G;
+    a.recip_g = (65536 + a.G - 1) / a.G;
+    a.cost_prefix = ctx ? ctx->cost_prefix[a.kv_fp8] : (a.kv_fp8 ? ra::kCostPrefixFp8 : ra::kCostPrefix);
     a.cost_item = ctx ? ctx->cost_item : ra::kCostItem;
-    a.static_pct = ctx ? ctx->static_pct : 100;
-    a.dyn_pages = ctx ? ctx->dyn_pages : 16;
     {
         // normalised so that the eight weights add up to 8192 (the schedule divides by a shift)
         long W = 0;
@@ -185,10 +183,9 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
     if (!c) { set_err(nullptr, "out of host memory"); return RA_ERR_DEVICE; }
     memset(c, 0, sizeof *c);
     c->device = device;
-    c->cost_prefix = ra::kCostPrefix;
+    c->cost_prefix[0] = ra::kCostPrefix;
+    c->cost_prefix[1] = ra::kCostPrefixFp8;
     c->cost_item = ra::kCostItem;
-    c->static_pct = 100;
-    c->dyn_pages = 16;
     // Share of the memory bandwidth each accelerator die gets when all eight stream at once (per mille of the
     // mean).  This is what a typical MI355X shows; the context measures its own device below.
     static const int kXcdSpeed[8] = {1024, 944, 1089, 978, 1064, 973, 1013, 936};
@@ -206,17 +203,9 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
             }
         }
     }
-    if (const char *ev = getenv("ROLLOUT_ATTN_STATIC_PCT")) {
-        int v = atoi(ev);
-        if (v >= 0 && v <= 100) c->static_pct = v;
-    }
-    if (const char *ev = getenv("ROLLOUT_ATTN_DYN_PAGES")) {
-        int v = atoi(ev);
-        if (v >= 1 && v <= 4096) c->dyn_pages = v;
-    }
     if (const char *ev = getenv("ROLLOUT_ATTN_COST_PREFIX")) {
         int v = atoi(ev);
-        if (v >= 1 && v <= 16) c->cost_prefix = v;
+        if (v >= 1 && v <= 16) c->cost_prefix[0] = c->cost_prefix[1] = v;
     }
     if (const char *ev = getenv("ROLLOUT_ATTN_COST_ITEM")) {
         int v = atoi(ev);
@@ -289,25 +278,15 @@ ra_status rollout_attn_workspace_size(const ra_ctx *c, const ra_problem *p, size
     }
     ra::Workspace ws;
     int waves = c ? c->waves[p->kv_dtype == RA_KV_FP8_E4M3][p->D == 128] : 2048;
-    *bytes = ra::carve_workspace(ws, nullptr, p->B, p->Hkv, p->Hq / p->Hkv, p->D, p->num_groups, waves);
+    *bytes = ra::carve_workspace(ws, nullptr, p->B, p->Hkv, p->Hq / p->Hkv, p->D, p->num_groups, waves,
+                                     ra::prefix_rows(p->kv_dtype == RA_KV_FP8_E4M3));
     return RA_OK;
 }
 
-ra_status rollout_attn_decode(ra_ctx *c, const ra_problem *p, void *workspace, size_t workspace_bytes, void *stream)
+// The decode step on a checked problem whose workspace has been carved: validation (if asked for), schedule,
+// attention, merge.
+static ra_status enqueue_decode(ra_ctx *c, const ra_problem *p, const ra::Launch &a, hipStream_t s)
 {
-    if (!c) { set_err(nullptr, "ctx is NULL"); return RA_ERR_INVALID_ARG; }
-    ra_status st = check(p, c->err, sizeof c->err);
-    if (st != RA_OK) return st;
-    if (p->B == 0) return RA_OK;
-    ra::Launch a;
-    fill_launch(a, c, p);
-    size_t need = ra::carve_workspace(a.ws, workspace, a.B, a.Hkv, a.G, a.D, a.num_groups, a.waves);
-    if (!workspace || ((uintptr_t)workspace & 255)) { set_err(c, "workspace is NULL or not 256-byte aligned"); return RA_ERR_INVALID_ARG; }
-    if (workspace_bytes < need) {
-        set_err(c, "workspace of %zu bytes given, %zu needed", workspace_bytes, need);
-        return RA_ERR_WORKSPACE_TOO_SMALL;
-    }
-    hipStream_t s = (hipStream_t)stream;
     int prev = 0;
     hipError_t e = hipGetDevice(&prev);
     if (e == hipSuccess && prev != c->device) e = hipSetDevice(c->device);
@@ -326,8 +305,7 @@ ra_status rollout_attn_decode(ra_ctx *c, const ra_problem *p, void *workspace, s
     }
     const bool tm = c->timing != 0;
     if (e == hipSuccess && tm) e = hipEventRecord(c->ev[0], s);
-    // (a schedule with a dynamically scheduled tail carries a counter that the attention kernel uses up)
-    const bool reuse = (p->flags & RA_FLAG_REUSE_SCHEDULE) && a.static_pct >= 100;
+    const bool reuse = (p->flags & RA_FLAG_REUSE_SCHEDULE) != 0;
     if (e == hipSuccess && !reuse) e = ra::launch_plan(a, s);
     if (e == hipSuccess && tm) e = hipEventRecord(c->ev[1], s);
     if (e == hipSuccess) e = ra::launch_attention(a, s);
@@ -338,6 +316,23 @@ ra_status rollout_attn_decode(ra_ctx *c, const ra_problem *p, void *workspace, s
     if (prev != c->device) (void)hipSetDevice(prev);
     if (e != hipSuccess) { set_err(c, "HIP: %s", hipGetErrorString(e)); return RA_ERR_DEVICE; }
     return RA_OK;
+}
+
+ra_status rollout_attn_decode(ra_ctx *c, const ra_problem *p, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!c) { set_err(nullptr, "ctx is NULL"); return RA_ERR_INVALID_ARG; }
+    ra_status st = check(p, c->err, sizeof c->err);
+    if (st != RA_OK) return st;
+    if (p->B == 0) return RA_OK;
+    ra::Launch a;
+    fill_launch(a, c, p);
+    size_t need = ra::carve_workspace(a.ws, workspace, a.B, a.Hkv, a.G, a.D, a.num_groups, a.waves, a.prefix_rows);
+    if (!workspace || ((uintptr_t)workspace & 255)) { set_err(c, "workspace is NULL or not 256-byte aligned"); return RA_ERR_INVALID_ARG; }
+    if (workspace_bytes < need) {
+        set_err(c, "workspace of %zu bytes given, %zu needed", workspace_bytes, need);
+        return RA_ERR_WORKSPACE_TOO_SMALL;
+    }
+    return enqueue_decode(c, p, a, (hipStream_t)stream);
 }
 
 ra_status rollout_attn_debug_gather(ra_ctx *c, const ra_problem *p, int32_t b, int32_t kvh, void *k_out, void *v_out,
@@ -370,7 +365,7 @@ ra_status rollout_attn_debug_schedule(ra_ctx *c, const ra_problem *p, void *work
     if (!info) { set_err(c, "info is NULL"); return RA_ERR_INVALID_ARG; }
     ra::Launch a;
     fill_launch(a, c, p);
-    size_t need = ra::carve_workspace(a.ws, workspace, a.B, a.Hkv, a.G, a.D, a.num_groups, a.waves);
+    size_t need = ra::carve_workspace(a.ws, workspace, a.B, a.Hkv, a.G, a.D, a.num_groups, a.waves, a.prefix_rows);
     if (!workspace || ((uintptr_t)workspace & 255)) { set_err(c, "workspace is NULL or not 256-byte aligned"); return RA_ERR_INVALID_ARG; }
     if (workspace_bytes < need) {
         set_err(c, "workspace of %zu bytes given, %zu needed", workspace_bytes, need);

@@ -7,19 +7,16 @@
 namespace ra {
 
 constexpr int kPage = 16;           // tokens per page
-constexpr int kPrefixTiles = 2;     // 16-row query tiles one shared-prefix work row carries
-constexpr int kPrefixRows = 16 * kPrefixTiles; // = members x heads-per-kv-head at most
 constexpr int kMinUnitsPerWave = 8; // do not cut the page stream finer than this many pages
-constexpr int kDynSpansPerWave = 4; // at most this many dynamically scheduled spans per resident wave
 constexpr int kCostSuffix = 4;      // scheduling weight of a page of a sequence's own KV
 constexpr int kChunkSegs = 7;       // segment records per chunk of a span's work list (plus one header record)
-constexpr int kCostPrefix = 5;      // ... of a shared-prefix page (more query rows per byte, so more time per page)
+constexpr int kCostPrefix = 8;      // ... of a shared-prefix page of a bf16 pool (64 query rows per byte read: more time per page)
+constexpr int kCostPrefixFp8 = 5;   // ... of an e4m3 pool (32 query rows)
 constexpr int kCostItem = 16;       // ... of a segment, on top of its pages
 
 // Device pointers into the caller's workspace.  All offsets are fixed by the shape alone.
 struct Workspace {
-    int32_t *hdr;            // [16]: 0 total cost units, 2 rows, 3 prefix rows, 4 error flags, 5 next span to hand out,
-                             //       7 spans
+    int32_t *hdr;            // [16]: 0 total cost units, 2 rows, 3 prefix rows, 4 error flags, 7 spans
     int32_t *grp_count;      // [num_groups]      members that use the shared pass
     int32_t *grp_rowbase;    // [num_groups + 1]  first prefix row of the group (relative)
     int32_t *grp_membase;    // [num_groups + 1]  first slot of the group in members[]
@@ -35,13 +32,16 @@ struct Workspace {
                              //       chunk is {segments in the chunk (<= 7), next chunk of the span or -1}, then the segments
     float *suf_o;            // [(B*Hkv + spans)][G][D]   partial outputs (normalised); slot = item + span
     float *suf_lse;          // [(B*Hkv + spans)][G]      partial log2-sum-exp
-    float *pfx_o;            // [(prefix_rows_max*Hkv + spans)][kPrefixRows][D]
-    float *pfx_lse;          // [(prefix_rows_max*Hkv + spans)][kPrefixRows]
+    float *pfx_o;            // [(prefix_rows_max*Hkv + spans)][prefix_rows][D]
+    float *pfx_lse;          // [(prefix_rows_max*Hkv + spans)][prefix_rows]
 };
 
 struct Launch {
     int32_t B, Hq, Hkv, D, G, num_pages, max_pages, num_groups;
-    int32_t kv_fp8, share, waves, members_per_row, stages, cost_prefix, cost_item, static_pct, dyn_pages;
+    int32_t kv_fp8, share, waves, stages, cost_prefix, cost_item;
+    int32_t prefix_rows;     // query rows a shared-prefix work row carries (members x heads per kv head, at most)
+    int32_t members_per_row; // = prefix_rows / G
+    int32_t recip_g;         // ceil(2^16 / G): (x * recip_g) >> 16 == x / G for 0 <= x <= 64
     int32_t xcd_w[8]; // relative speed of the eight accelerator dies, adding up to 8192
     const uint16_t *q;
     const uint8_t *k_pool, *v_pool;
@@ -74,10 +74,12 @@ struct PrefillLaunch {
     const int32_t *page_off, *pages;      // [num_prompts + 1], [page_off[num_prompts]]
 };
 
+// Query rows of a shared-prefix work row for bf16 (0) or e4m3 (1) pools.
+int prefix_rows(int kv_fp8);
 // Upper bound on prefix rows for a shape.
-int prefix_rows_max(int B, int G, int num_groups);
+int prefix_rows_max(int B, int G, int num_groups, int prefix_rows);
 // Carves the workspace; returns the bytes needed.  base may be null (size query).
-size_t carve_workspace(Workspace &ws, void *base, int B, int Hkv, int G, int D, int num_groups, int waves);
+size_t carve_workspace(Workspace &ws, void *base, int B, int Hkv, int G, int D, int num_groups, int waves, int prefix_rows);
 
 // LDS ring depth of the attention kernel and the number of its waves (= workgroups = spans of the page stream) to
 // launch on the current device, for head dim D: as many as are resident at once (bf16 pools: one per SIMD; e4m3 pools:

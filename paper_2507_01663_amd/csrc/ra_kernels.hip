@@ -28,15 +28,15 @@ __device__ __forceinline__ void touch_args(const Launch &a)
 // workspace
 // ------------------------------------------------------------------------------------------------------
 
-int prefix_rows_max(int B, int G, int num_groups)
+int prefix_rows_max(int B, int G, int num_groups, int prefix_rows)
 {
     if (num_groups <= 0) return 0;
-    int mpr = kPrefixRows / G;
+    int mpr = prefix_rows / G;
     long v = (long)num_groups + B / mpr;
     return (int)(v < B ? v : B);
 }
 
-size_t carve_workspace(Workspace &ws, void *base, int B, int Hkv, int G, int D, int num_groups, int waves)
+size_t carve_workspace(Workspace &ws, void *base, int B, int Hkv, int G, int D, int num_groups, int waves, int prefix_rows)
 {
     size_t off = 0;
     char *p = (char *)base;
@@ -46,7 +46,7 @@ size_t carve_workspace(Workspace &ws, void *base, int B, int Hkv, int G, int D, 
         return r;
     };
     int ng = num_groups > 0 ? num_groups : 0;
-    int prm = prefix_rows_max(B, G, num_groups);
+    int prm = prefix_rows_max(B, G, num_groups, prefix_rows);
     ws.hdr = (int32_t *)take(16 * 4);
     ws.grp_count = (int32_t *)take((size_t)(ng + 1) * 4);
     ws.grp_rowbase = (int32_t *)take((size_t)(ng + 1) * 4);
@@ -58,7 +58,7 @@ size_t carve_workspace(Workspace &ws, void *base, int B, int Hkv, int G, int D, 
     ws.members = (int32_t *)take((size_t)B * 4);
     ws.row_start = (int32_t *)take(((size_t)2 * B + 1) * 4);
     ws.row_tab = (int4 *)take((size_t)2 * B * 16);
-    const size_t spans = (size_t)(1 + kDynSpansPerWave) * waves; // upper bound on spans of the cost stream
+    const size_t spans = (size_t)waves; // one span of the cost stream per resident wave
     // every (item, span) pair that shares pages is one segment: at most items + spans of them
     const size_t chunks = spans + ((size_t)2 * B * Hkv + spans) / kChunkSegs + 2;
     ws.seg_rec = (int4 *)take(chunks * 16 * sizeof(int4));
@@ -66,15 +66,15 @@ size_t carve_workspace(Workspace &ws, void *base, int B, int Hkv, int G, int D, 
     ws.suf_o = (float *)take(nsuf * G * D * 4);
     ws.suf_lse = (float *)take(nsuf * G * 4);
     size_t npfx = prm ? (size_t)prm * Hkv + spans : 0;
-    ws.pfx_o = (float *)take(npfx * kPrefixRows * D * 4);
-    ws.pfx_lse = (float *)take(npfx * kPrefixRows * 4);
+    ws.pfx_o = (float *)take(npfx * prefix_rows * D * 4);
+    ws.pfx_lse = (float *)take(npfx * prefix_rows * 4);
     return off;
 }
 
 // ------------------------------------------------------------------------------------------------------
 // schedule: work rows, their cost, the scan, and each span's work list
 //
-// Work rows: first the shared-prefix rows (one per group and block of kPrefixRows/G members), then one row
+// Work rows: first the shared-prefix rows (one per group and block of members_per_row members), then one row
 // per sequence for its own pages.  A row of n pages costs a fixed amount plus weight*n per kv head, and the
 // rows, each repeated for every kv head, form one stream of cost units that is cut into spans, one per
 // resident wave: the ragged lengths (paper Sec. 7.4) never leave a compute unit idle.  A page belongs to the
@@ -146,24 +146,21 @@ __device__ void block_scan(int32_t *a, int32_t *b, int n, int32_t *tmp /*[34], L
     __syncthreads();
 }
 
-// Where the cost stream is cut.  The first `waves` spans are static, one per resident wave.  Workgroups are
-// dealt round-robin to the eight accelerator dies, which do not all get the same share of the memory
-// bandwidth, so within each block of eight consecutive static spans (8*S0 units) span x gets a share
-// proportional to the relative speed xcd_w[x] of its die (the weights add up to 8192).  The rest of the
-// stream, if any, is cut into spans of cd units that the waves take from a counter as they finish.
+// Where the cost stream is cut: into one span per resident wave.  Workgroups are dealt round-robin to the eight
+// accelerator dies, which do not all get the same share of the memory bandwidth, so within each block of eight
+// consecutive spans (8*S0 units) span x gets a share proportional to the relative speed xcd_w[x] of its die (the
+// weights add up to 8192).
 struct Cuts {
-    int U, S0, cd; // the stream has fewer than 2^31 units (checked on the host); divisions stay 32 bits wide
-    int waves, nspans;
+    int U, S0; // the stream has fewer than 2^31 units (checked on the host); divisions stay 32 bits wide
+    int waves;
     int acc[9]; // running sums of the die weights
     __device__ int lo(int c) const
     {
-        const long v = c < waves ? (long)(c >> 3) * 8 * S0 + ((8L * S0 * acc[c & 7]) >> 13) : (long)waves * S0 + (long)(c - waves) * cd;
+        const long v = (long)(c >> 3) * 8 * S0 + ((8L * S0 * acc[c & 7]) >> 13);
         return v < U ? (int)v : U;
     }
     __device__ int span_of(int pos) const // the span that holds cost unit pos < U
     {
-        const long stat = (long)waves * S0;
-        if (pos >= stat) return waves + (int)((unsigned)(pos - (int)stat) / (unsigned)cd);
         const unsigned blk = (unsigned)pos / (unsigned)(8 * S0);
         const int rem = pos - (int)blk * 8 * S0;
         int x = 0;
@@ -184,10 +181,9 @@ struct RowsLds {
 
 // The rows phase: membership, the rows with their costs (scanned in place in row_start), the row table.  Returns
 // the number of rows and of shared-prefix rows among them.  `small` keeps everything in LDS (L), else the
-// intermediates live in the workspace.  Which rank a member gets inside its group depends on the order in which
-// the threads arrive, so only one workgroup may publish what depends on it (publish: the members' list and each
-// sequence's prefix row and place in it); the rows, their costs and the row table depend on counts alone and come out
-// the same in every workgroup that runs this.  tab: where the row table goes (LDS or the workspace).
+// intermediates live in the workspace.  Everything here is a function of the inputs alone and comes out the same in
+// every workgroup that runs this; one of them publishes what the other kernels read (publish: the members' list and
+// each sequence's prefix row and place in it).  tab: where the row table goes (LDS or the workspace).
 __device__ __forceinline__ void rows_phase(const Launch &a, RowsLds &L, bool small, bool publish, int4 *tab, int32_t *&row_start_out,
                                            int &nR_out, int &nPR_out)
 {
@@ -221,17 +217,44 @@ __device__ __forceinline__ void rows_phase(const Launch &a, RowsLds &L, bool sma
         const int g = NG ? grp_src[b] : -1;
         return g >= 0 && g < NG ? g : -1;
     };
-    // membership: a sequence uses the shared pass when its group has shared pages and it holds all of them
-    for (int b = tid; b < B; b += kPlanThreads) {
-        int rank = -1;
-        const int g = grp_of(b);
-        if (g >= 0) {
-            const int np = poff[g + 1] - poff[g];
-            if (np > 0 && len_of(b) >= np * kPage) rank = atomicAdd(&grp_count[g], 1);
+    // membership: a sequence uses the shared pass when its group has shared pages and it holds all of them.  Its rank
+    // in the group is the number of members before it (smaller b), a function of the inputs alone, because the rank
+    // decides which shared-prefix row the member joins and with it the partials its result is merged from: sequences
+    // are taken in ascending blocks, a lane finds its place among the lanes of its wave with the same group by
+    // ballots, and the waves add their counts to the group's total one after the other.
+    for (int base = 0; base < B; base += kPlanThreads) {
+        const int b = base + tid, lane = tid & 63, wv = tid >> 6;
+        int g = -1;
+        if (b < B) {
+            const int gb = grp_of(b);
+            if (gb >= 0) {
+                const int np = poff[gb + 1] - poff[gb];
+                if (np > 0 && len_of(b) >= np * kPage) g = gb;
+            }
         }
-        seq_rank[b] = rank;
+        int pos = 0, cnt = 0;
+        unsigned long long todo = __ballot(g >= 0);
+        while (todo) {
+            const int gl = __shfl(g, __ffsll((long long)todo) - 1);
+            const unsigned long long same = __ballot(g == gl);
+            if (g == gl) {
+                pos = __popcll(same & ((1ull << lane) - 1ull));
+                cnt = __popcll(same);
+            }
+            todo &= ~same;
+        }
+        int rank = -1;
+        for (int w = 0; w < kPlanThreads / 64; w++) {
+            if (wv == w && g >= 0) {
+                const int before = grp_count[g]; // the same for all lanes of the group: read by all, then written by one
+                rank = before + pos;
+                __builtin_amdgcn_wave_barrier();
+                if (pos == 0) grp_count[g] = before + cnt;
+            }
+            __syncthreads();
+        }
+        if (b < B) seq_rank[b] = rank;
     }
-    __syncthreads();
     int nPR = 0;
     if (NG) {
         for (int g = tid; g < NG; g += kPlanThreads) {
@@ -312,19 +335,8 @@ __device__ __forceinline__ void make_cuts(const Launch &a, int U, Cuts &cut)
     // span between the first and the last one of an item holds at least one of its pages
     int min_span = kMinUnitsPerWave * kCostSuffix;
     if (min_span < 4 * a.cost_prefix) min_span = 4 * a.cost_prefix; // (a die's share is at least half the mean)
-    cut.S0 = a.static_pct >= 100 ? (int)(((unsigned)cut.U + a.waves - 1) / (unsigned)a.waves)
-                                 : (int)((unsigned)cut.U / (unsigned)a.waves) * a.static_pct / 100;
+    cut.S0 = (int)(((unsigned)cut.U + a.waves - 1) / (unsigned)a.waves);
     if (cut.S0 < min_span) cut.S0 = min_span;
-    cut.cd = a.dyn_pages * kCostSuffix;
-    if (cut.cd < min_span) cut.cd = min_span;
-    int ndyn = 0;
-    const long Ud = (long)cut.U - (long)cut.S0 * a.waves;
-    if (Ud > 0) {
-        const int most = kDynSpansPerWave * a.waves;
-        if (((unsigned)Ud + cut.cd - 1) / (unsigned)cut.cd > (unsigned)most) cut.cd = (int)(((unsigned)Ud + most - 1) / (unsigned)most);
-        ndyn = (int)(((unsigned)Ud + cut.cd - 1) / (unsigned)cut.cd);
-    }
-    cut.nspans = a.waves + ndyn;
     cut.acc[0] = 0;
 #pragma unroll
     for (int x = 0; x < 8; x++) cut.acc[x + 1] = cut.acc[x] + a.xcd_w[x];
@@ -342,7 +354,7 @@ __device__ __forceinline__ void spans_phase(const Launch &a, const Cuts &cut, co
                                             int nPR, int first, int stride)
 {
     const Workspace &w = a.ws;
-    const int nspans = cut.nspans;
+    const int nspans = cut.waves;
     for (int c = first; c < nspans; c += stride) {
         const int lo = cut.lo(c), hi = cut.lo(c + 1);
         int chunk = c, n = 0, chain = -1;
@@ -444,10 +456,7 @@ __global__ __launch_bounds__(kSpanThreads) void plan_spans_kernel(Launch a)
 
     Cuts cut;
     make_cuts(a, U, cut);
-    if (gtid == 0) {
-        w.hdr[5] = a.waves; // next span to hand out
-        w.hdr[7] = cut.nspans;
-    }
+    if (gtid == 0) w.hdr[7] = cut.waves;
     spans_phase(a, cut, row_start, row_tab, nR, nPR, gtid, gstride);
     for (int i = gtid; i < a.B * a.Hkv; i += gstride) merge_desc_of(a, cut, row_start, nPR, i, i == gtid ? my_prow : w.seq_pfx_row[i / a.Hkv]);
 }
@@ -473,8 +482,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_fused_kernel(Launch a)
             w.hdr[0] = cut.U;
             w.hdr[2] = nR;
             w.hdr[3] = nPR;
-            w.hdr[5] = a.waves; // next span to hand out
-            w.hdr[7] = cut.nspans;
+            w.hdr[7] = cut.waves;
         }
         for (int i = tid; i < a.B * a.Hkv; i += kPlanThreads) merge_desc_of(a, cut, row_start, nPR, i, L.seq_rank[i / a.Hkv]);
     } else {
@@ -484,9 +492,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_fused_kernel(Launch a)
 
 hipError_t launch_plan(const Launch &a, hipStream_t s)
 {
-    // one thread per span; the span count is only known on the device, so the grid covers the most there can be
-    const int most = (1 + kDynSpansPerWave) * a.waves;
-    const int work = a.static_pct >= 100 ? a.waves : most;
+    const int work = a.waves; // one thread per span
     if (a.B <= kPlanCap && (a.share ? a.num_groups : 0) <= kPlanCap) {
         hipLaunchKernelGGL(plan_fused_kernel, dim3(1 + (work + kPlanThreads - 1) / kPlanThreads), dim3(kPlanThreads), 0, s, a);
         return hipGetLastError();
@@ -502,7 +508,8 @@ hipError_t launch_plan(const Launch &a, hipStream_t s)
 // attention
 // ------------------------------------------------------------------------------------------------------
 
-// One unit of work of a wave: pages [pg_lo, pg_hi) of one (work row, kv head) item.  All fields are wave-uniform.
+// One unit of work of a wave: pages [pg_lo, pg_hi) of one (work row, kv head) item.  All fields but mvec are
+// wave-uniform.
 struct Segment {
     const int32_t *pages; // page ids of the work row (read with uniform_load)
     int pg_lo, pg_hi;
@@ -512,22 +519,34 @@ struct Segment {
     int b;                // the sequence (own pages)
     int moff, nrows;      // shared pages: first slot in members[], query rows in use
     int64_t slot;         // partial-result slot
+    uint32_t mvec;        // shared pages: lane i holds the sequence of the work row's member i
     __device__ __forceinline__ int stages() const { return (pg_hi - pg_lo + 1) >> 1; }
+    // ring entries: a shared-pages segment leads with one entry that carries its query rows
+    __device__ __forceinline__ int entries() const { return stages() + prefix; }
 };
 
-// The wave's LDS ring: stages (two pages each) are numbered in the order the wave streams them, across
-// segments; stage n lives in ring slot n % NST.
+// The wave's LDS ring: entries (two pages each, or the query rows of a shared-pages segment) are numbered in the
+// order the wave streams them, across segments; entry n lives in ring slot n % NST.
 struct Ring {
-    int issued; // stages whose loads have been issued
-    int waited; // stages whose loads have been waited for (and consumed)
+    int issued; // entries whose loads have been issued
+    int waited; // entries whose loads have been waited for (and consumed)
     int qslot;  // the query slot of the current segment; alternates with every segment
 };
+
+// 16-row query tiles that a shared-prefix work row carries: four for bf16 pools (64 rows fill a ring entry of two
+// pages exactly), two for e4m3 pools, whose ring entries are half the size.
+template <int KVB> struct PrefixTiles {
+    static constexpr int value = KVB == 2 ? 4 : 2;
+};
+int prefix_rows(int kv_fp8) { return 16 * (kv_fp8 ? PrefixTiles<1>::value : PrefixTiles<2>::value); }
 
 template <int D, int KVB, int NST> struct LdsMap {
     using G = Geo<D, KVB>;
     static constexpr int kQTile = kPage * D * 2;   // 16 query rows of bf16
     static constexpr int kQBase = NST * G::kStage; // two query slots follow the ring
     static constexpr int kBytes = NST * G::kStage + 2 * kQTile;
+    static_assert(PrefixTiles<KVB>::value * kQTile <= G::kStage, "the query rows of a shared-prefix row fill one ring entry");
+    static_assert(PrefixTiles<KVB>::value * (D * 2 / 64) <= G::kDmaPerStage, "... with no more loads than two pages take");
 };
 
 // A finished partial of an own-pages segment, kept in registers.  Stores share the vector-memory counter with the
@@ -591,6 +610,39 @@ __device__ __forceinline__ void issue_q(const Launch &a, const uint16_t *__restr
     }
 }
 
+// Query rows of a shared-pages segment, as a ring entry of their own: row = member * G + head of the kv head's
+// group, a gather of whole rows of q (one per lane quarter), in 16-row tiles laid out like a query slot.  Rows past
+// the ones in use read zeros.  Issues exactly as many loads as a stage of two pages, so that the ring's
+// bookkeeping does not tell the two kinds of entry apart.
+template <int D, int KVB, int NST>
+__device__ __forceinline__ void issue_qrows(const Launch &a, const uint16_t *__restrict__ q, const LaneConst<D, KVB> &lc,
+                                            const Segment &sg, int ring_slot, uint32_t lds_addr)
+{
+    using G = Geo<D, KVB>;
+    using M = LdsMap<D, KVB, NST>;
+    constexpr int NQT = PrefixTiles<KVB>::value, PER = D * 2 / 64, QU = D * 2 / 16;
+    const uint32_t sb = lds_addr + ring_slot * G::kStage;
+    // (every address below is a function of the lane alone, which the compiler would otherwise work out once and
+    // keep in registers for the whole kernel, dozens of them; this happens once per segment, so recompute)
+    int lane = threadIdx.x;
+    asm volatile("" : "+v"(lane));
+    const int r0 = lane / QU, cp = lane % QU;
+#pragma unroll
+    for (int t = 0; t < NQT; t++) {
+#pragma unroll
+        for (int n = 0; n < PER; n++) {
+            const int r = (64 / QU) * n + r0, row = 16 * t + r; // row r of tile t lands where a query slot keeps it
+            const int mi = (row * a.recip_g) >> 16;             // row / G (exact for rows below 64)
+            const int seq = __builtin_amdgcn_ds_bpermute(4 * mi, (int)sg.mvec);
+            const int head = sg.kvh * a.G + (row - mi * a.G);
+            const uint8_t *src = (const uint8_t *)(q + ((int64_t)seq * a.Hq + head) * D) + (cp ^ (swz(r) & (QU - 1))) * 16;
+            dma16(row < sg.nrows ? (const void *)src : a.zeros, sb + t * M::kQTile + 1024 * n);
+        }
+    }
+#pragma unroll
+    for (int k = NQT * PER; k < G::kDmaPerStage; k++) dma4(a.zeros, sb + 4 * G::kTile);
+}
+
 // Attention of NQT*16 query rows over one segment.  Two pages (32 keys) per ring stage:
 //   S^T[key, row] = K_tile . Q^T      (16x16x32 MFMA over D, per page; A = K rows straight from LDS, B = Q in
 //                                      registers)
@@ -601,69 +653,51 @@ __device__ __forceinline__ void issue_q(const Launch &a, const uint16_t *__restr
 // In both products a lane owns one query row (lane % 16), so the running max, the rescale factor and the
 // row sum are per-lane scalars; only the row max needs a cross-lane step (lanes l, l^16, l^32, l^48).
 //
-// The ring does not run dry at a segment boundary: while the last stages of this segment are consumed, the
-// first stages (and the query rows) of the next one are already being loaded.  On entry, the first
-// min(NST-1, stages) stages of this segment are in flight; on exit the same holds for `nxt`.
+// The ring does not run dry at a segment boundary: while the last entries of this segment are consumed, the
+// first entries (and the query rows) of the next one are already being loaded.  On entry, the first
+// min(NST-1, entries) entries of this segment are in flight; on exit the same holds for `nxt`.  Query rows of an
+// own-pages segment (NQT == 1) wait in a query slot; those of a shared-pages segment are its first ring entry.
 // A one-tile partial goes back in `ret` (normalised, with its log2-sum-exp); a shared-prefix partial is stored.
 template <int D, int KVB, int NQT, int NST>
-__device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__restrict__ q, const int32_t *__restrict__ members,
-                                            const Segment &cur, bool has_nxt, const Segment &nxt, Ring &ring,
-                                            const LaneConst<D, KVB> &lc, uint8_t *lds, uint32_t lds_addr, Pending<D> &ret)
+__device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__restrict__ q, const Segment &cur, bool has_nxt,
+                                            const Segment &nxt, Ring &ring, const LaneConst<D, KVB> &lc, uint8_t *lds,
+                                            uint32_t lds_addr, Pending<D> &ret)
 {
     using G = Geo<D, KVB>;
     using M = LdsMap<D, KVB, NST>;
     static_assert((NST - 1) * G::kDmaPerStage < 64, "the vector-memory counter holds 6 bits");
+    static_assert(NQT == 1 || NQT == PrefixTiles<KVB>::value, "one tile, or a shared-prefix row");
+    constexpr int QL = NQT > 1 ? 1 : 0; // this segment's first ring entry carries its query rows
     const int lane = threadIdx.x, j = lane >> 4;
-    const int niter = cur.stages();
-    const int base = ring.waited; // ring number of this segment's first stage
-    int nxt_pre = 0;
+    const int niter = cur.stages() + QL;
+    const int base = ring.waited; // ring number of this segment's first entry
+    int nxt_pre = 0, nxt_ql = 0;
     if (has_nxt) {
-        nxt_pre = nxt.stages();
+        nxt_ql = nxt.prefix;
+        nxt_pre = nxt.stages() + nxt_ql;
         nxt_pre = nxt_pre < NST - 1 ? nxt_pre : NST - 1;
     }
     const int total = niter + nxt_pre;
+    const int ntiles = NQT > 1 ? (cur.nrows + 15) >> 4 : 1; // tiles in use (the others hold zeros and are skipped)
 
-    // page id of page h of the stage with number base + rel (this segment's stages first, then the next one's)
+    // page id of page h of the entry with number base + rel (this segment's entries first, then the next one's)
     auto page_id = [&](int rel, int h) {
         int id = 0;
         if (rel < niter) {
-            const int p = cur.pg_lo + 2 * rel + h;
-            if (p < cur.pg_hi) id = uniform_load(cur.pages, p);
+            const int st = rel - QL, p = cur.pg_lo + 2 * st + h;
+            if (st >= 0 && p < cur.pg_hi) id = uniform_load(cur.pages, p);
         } else if (rel < total) {
-            const int p = nxt.pg_lo + 2 * (rel - niter) + h;
-            if (p < nxt.pg_hi) id = uniform_load(nxt.pages, p);
+            const int st = rel - niter - nxt_ql, p = nxt.pg_lo + 2 * st + h;
+            if (st >= 0 && p < nxt.pg_hi) id = uniform_load(nxt.pages, p);
         }
         return id;
     };
-    int nid0 = page_id(ring.issued - base, 0), nid1 = page_id(ring.issued - base, 1); // one stage ahead of their use
+    int nid0 = page_id(ring.issued - base, 0), nid1 = page_id(ring.issued - base, 1); // one entry ahead of their use
 
     // Q^T operand: for k-step i, lane (row = lane%16, j) holds the eight d values that its K operand holds.
     // bf16 K: d = 32*i + 8*j .. +7.  e4m3 K: one 16-byte K read carries 16 d values and feeds two k-steps, so
     // d = 16*(4*(i/2) + j) + 8*(i%2) .. +7 (the sum over d does not care about the order).
     bf16x8 qf[NQT][G::kKSteps];
-    if (NQT > 1) {
-        // shared pages: rows = members x G packed densely, gathered straight from global memory; the compiler's
-        // wait for these loads drains the ring once per such segment, and they are few
-#pragma unroll
-        for (int t = 0; t < NQT; t++) {
-            const int row = 16 * t + (lane & 15);
-            const int mi = row / a.G;
-            const int seq = row < cur.nrows ? members[cur.moff + mi] : -1;
-            const int head = cur.kvh * a.G + (row - mi * a.G);
-#pragma unroll
-            for (int i = 0; i < G::kKSteps; i++) {
-                const int d0 = KVB == 2 ? 32 * i + 8 * j : 16 * (4 * (i / 2) + j) + 8 * (i % 2);
-                bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-                if (seq >= 0) v = *(const bf16x8 *)(q + ((int64_t)seq * a.Hq + head) * D + d0);
-                qf[t][i] = v;
-            }
-        }
-#pragma unroll
-        for (int t = 0; t < NQT; t++) {
-#pragma unroll
-            for (int i = 0; i < G::kKSteps; i++) asm volatile("" ::"v"(qf[t][i]));
-        }
-    }
 
     f32x4 o[NQT][G::kDTiles];
     float m[NQT], lsum[NQT];
@@ -675,33 +709,53 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
         for (int dt = 0; dt < G::kDTiles; dt++) o[t][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    for (int it = 0; it < niter; it++) {
-        // keep NST-1 stages in flight beyond this one
+    // keeps NST-1 entries in flight beyond entry `it` (this segment's own first entries were issued before it began)
+    auto issue_ahead = [&](int it) {
         int want = it + NST;
         want = want < total ? want : total;
         while (ring.issued - base < want) {
             const int rel = ring.issued - base;
             if (rel < niter) {
-                issue_stage<D, KVB, NST>(a, lc, cur, rel, nid0, nid1, ring.issued % NST, lds_addr);
+                issue_stage<D, KVB, NST>(a, lc, cur, rel - QL, nid0, nid1, ring.issued % NST, lds_addr);
+            } else if (rel == niter && nxt_ql) {
+                issue_qrows<D, KVB, NST>(a, q, lc, nxt, ring.issued % NST, lds_addr);
             } else {
-                if (rel == niter && !nxt.prefix) issue_q<D, KVB, NST>(a, q, lc, nxt, ring.qslot ^ 1, lds_addr);
-                issue_stage<D, KVB, NST>(a, lc, nxt, rel - niter, nid0, nid1, ring.issued % NST, lds_addr);
+                if (rel == niter) issue_q<D, KVB, NST>(a, q, lc, nxt, ring.qslot ^ 1, lds_addr);
+                issue_stage<D, KVB, NST>(a, lc, nxt, rel - niter - nxt_ql, nid0, nid1, ring.issued % NST, lds_addr);
             }
             ring.issued++;
             nid0 = page_id(ring.issued - base, 0);
             nid1 = page_id(ring.issued - base, 1);
         }
-        // Loads complete in order.  Anything else issued after this stage (query rows, partial stores) only
-        // makes the wait stricter than needed.
+    };
+    if (QL) {
+        // the first ring entry holds the query rows
+        issue_ahead(0);
+        WaitTail<NST - 1, G::kDmaPerStage>::run(ring.issued - base - 1);
+        const uint8_t *qb = lds + (base % NST) * G::kStage;
+#pragma unroll
+        for (int t = 0; t < NQT; t++) {
+#pragma unroll
+            for (int i = 0; i < G::kKSteps; i++) qf[t][i] = *(const bf16x8 *)(qb + t * M::kQTile + lc.kq_off[i]);
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        ring.waited++;
+    }
+
+    for (int it = QL; it < niter; it++) {
+        issue_ahead(it);
+        // Loads complete in order, and every ring entry is the same number of them.  Anything else issued after
+        // this entry (query rows of an own-pages segment, partial stores) only makes the wait stricter than needed.
         WaitTail<NST - 1, G::kDmaPerStage>::run(ring.issued - base - 1 - it);
         const int rslot = (base + it) % NST;
         const uint8_t *st = lds + rslot * G::kStage;
-        if (NQT == 1 && it == 0) {
-            // the query rows were loaded ahead of this segment's first stage, so they have landed too
+        if (!QL && it == 0) {
+            // the query rows were loaded into the query slot ahead of this segment's first stage, so they have landed too
 #pragma unroll
             for (int i = 0; i < G::kKSteps; i++)
                 qf[0][i] = *(const bf16x8 *)(lds + M::kQBase + ring.qslot * M::kQTile + lc.kq_off[i]);
         }
+        const int pg0 = cur.pg_lo + 2 * (it - QL); // first page of this stage
 
         // scores of the 2 x 16 keys of this stage
         f32x4 s[NQT][2];
@@ -715,15 +769,16 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
                     bf16x8 kf = *(const bf16x8 *)(st + pg * G::kTile + lc.k_off[i]);
 #pragma unroll
                     for (int t = 0; t < NQT; t++)
-                        s[t][pg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[t][i], s[t][pg], 0, 0, 0);
+                        if (t < ntiles) s[t][pg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[t][i], s[t][pg], 0, 0, 0);
                 } else {
                     const int4 kc = *(const int4 *)(st + pg * G::kTile + lc.k_off[i]); // 16 codes: two k-steps
                     const bf16x8 k0 = fp8x8_to_bf16(kc.x, kc.y), k1 = fp8x8_to_bf16(kc.z, kc.w);
 #pragma unroll
-                    for (int t = 0; t < NQT; t++) {
-                        s[t][pg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[t][2 * i], s[t][pg], 0, 0, 0);
-                        s[t][pg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[t][2 * i + 1], s[t][pg], 0, 0, 0);
-                    }
+                    for (int t = 0; t < NQT; t++)
+                        if (t < ntiles) {
+                            s[t][pg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[t][2 * i], s[t][pg], 0, 0, 0);
+                            s[t][pg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[t][2 * i + 1], s[t][pg], 0, 0, 0);
+                        }
                 }
             }
         }
@@ -734,11 +789,12 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
             const f32x4 sc = *(const f32x4 *)(st + 4 * G::kTile);
             ks0 *= sc[0], vs0 = sc[1], ks1 *= sc[2], vs1 = sc[3];
         }
-        const int tok0 = (cur.pg_lo + 2 * it) * kPage + 4 * j; // this lane's first token in the stage's first page
-        const bool ragged = (cur.pg_lo + 2 * it + 2) * kPage > cur.limit;
+        const int tok0 = pg0 * kPage + 4 * j; // this lane's first token in the stage's first page
+        const bool ragged = (pg0 + 2) * kPage > cur.limit;
         bf16x8 pf[NQT];
 #pragma unroll
         for (int t = 0; t < NQT; t++) {
+            if (t >= ntiles) continue;
             float v[8];
 #pragma unroll
             for (int e = 0; e < 4; e++) {
@@ -794,13 +850,14 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
                 vf = fp8x8_to_bf16(vc[0], vc[1]);
             }
 #pragma unroll
-            for (int t = 0; t < NQT; t++) o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[t], o[t][dt], 0, 0, 0);
+            for (int t = 0; t < NQT; t++)
+                if (t < ntiles) o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[t], o[t][dt], 0, 0, 0);
         }
         // every LDS read of this stage has returned before a later load may overwrite it
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         ring.waited++;
     }
-    ring.qslot ^= 1; // the next segment's query rows, if it keeps them in LDS, went to the other slot
+    ring.qslot ^= 1; // the next segment's query rows, if it keeps them in a query slot, went to the other one
 
 #pragma unroll
     for (int t = 0; t < NQT; t++) {
@@ -814,10 +871,10 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
         } else {
             const int row = 16 * t + (lane & 15);
             if (row < cur.nrows) {
-                float *dst = a.ws.pfx_o + (cur.slot * kPrefixRows + row) * D + 4 * j;
+                float *dst = a.ws.pfx_o + (cur.slot * a.prefix_rows + row) * D + 4 * j;
 #pragma unroll
                 for (int dt = 0; dt < G::kDTiles; dt++) *(f32x4 *)(dst + 16 * dt) = o[t][dt] * inv;
-                if (j == 0) a.ws.pfx_lse[cur.slot * kPrefixRows + row] = lse2;
+                if (j == 0) a.ws.pfx_lse[cur.slot * a.prefix_rows + row] = lse2;
             }
         }
     }
@@ -830,7 +887,7 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
         const int32_t *__restrict__ hdr, const uint32_t *__restrict__ seg_rec, const int32_t *__restrict__ members
 #define RA_ATTN_ARGS a, q, block_table, pfx_pages, hdr, seg_rec, members
 
-template <int D, int KVB, int NST, int NPEND> __device__ __forceinline__ void attention_body(RA_ATTN_PARAMS, int32_t *next_span)
+template <int D, int KVB, int NST, int NPEND> __device__ __forceinline__ void attention_body(RA_ATTN_PARAMS)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     const uint32_t lds_addr = (uint32_t)(uintptr_t)lds;
@@ -845,14 +902,11 @@ template <int D, int KVB, int NST, int NPEND> __device__ __forceinline__ void at
     Pending<D> pend[NPEND], fresh; // finished partials wait in registers for the end of the wave
     int npend = 0;
 
-    // ---- walker: yields this wave's segments in stream order, span after span ----
+    // ---- walker: yields this wave's segments in stream order ----
     // A span's work list is a chain of chunks of eight 8-dword records (a header and up to seven segments).
     // A chunk is one dword per lane, so it is held in one register and a field is a cross-lane read.
     uint32_t chunk = 0;
     int wk_j = 0, wk_n = 0, wk_chain = -1;
-    int wk_next = 0; // lane 0: the span taken from the counter
-    bool wk_done = false;
-    const bool dynamic = nspans > a.waves;
     auto field = [&](int i) { return (int)__builtin_amdgcn_readlane(chunk, i); };
     auto load_chunk = [&](int c) {
         chunk = seg_rec[(int64_t)c * 64 + lane];
@@ -860,61 +914,62 @@ template <int D, int KVB, int NST, int NPEND> __device__ __forceinline__ void at
         wk_n = field(0);
         wk_chain = field(1);
     };
-    auto enter_span = [&](int c) {
-        load_chunk(c);
-        // take the span after this one now; the answer is needed only when this one is exhausted
-        if (dynamic && lane == 0) wk_next = atomicAdd(next_span, 1);
-    };
     auto advance = [&](Segment &out) -> bool {
-        for (;;) {
-            if (wk_done) return false;
-            if (wk_j == wk_n) {
-                if (wk_chain >= 0) {
-                    load_chunk(wk_chain);
-                    continue;
-                }
-                const int nx = dynamic ? __builtin_amdgcn_readfirstlane(wk_next) : nspans;
-                if (nx >= nspans) {
-                    wk_done = true;
-                    return false;
-                }
-                enter_span(nx);
-                continue;
-            }
-            const int f = 8 * (1 + wk_j++);
-            const int where = field(f + 4);
-            out.kvh = where & 0xffff;
-            out.prefix = where >> 16;
-            out.pages = (out.prefix ? pfx_pages : block_table) + field(f);
-            out.pg_lo = field(f + 1);
-            out.pg_hi = field(f + 2);
-            out.limit = field(f + 3);
-            out.b = out.prefix ? 0 : field(f + 5);
-            out.moff = out.prefix ? field(f + 5) : 0;
-            out.nrows = field(f + 6);
-            out.slot = field(f + 7);
-            return true;
+        while (wk_j == wk_n) {
+            if (wk_chain < 0) return false;
+            load_chunk(wk_chain);
         }
+        const int f = 8 * (1 + wk_j++);
+        const int where = field(f + 4);
+        out.kvh = where & 0xffff;
+        out.prefix = where >> 16;
+        out.pages = (out.prefix ? pfx_pages : block_table) + field(f);
+        out.pg_lo = field(f + 1);
+        out.pg_hi = field(f + 2);
+        out.limit = field(f + 3);
+        out.b = out.prefix ? 0 : field(f + 5);
+        out.moff = out.prefix ? field(f + 5) : 0;
+        out.nrows = field(f + 6);
+        out.slot = field(f + 7);
+        out.mvec = 0;
+        if (out.prefix) {
+            // the work row's members, one per lane (scalar loads four at a time: the ring's loads are not waited for)
+            const int nmem = (out.nrows * a.recip_g) >> 16;
+            for (int i = 0; i < nmem; i += 4) {
+                int v[4];
+#pragma unroll
+                for (int k = 0; k < 4; k++) v[k] = i + k < nmem ? uniform_load(members, out.moff + i + k) : 0;
+#pragma unroll
+                for (int k = 0; k < 4; k++)
+                    if (lane == i + k) out.mvec = (uint32_t)v[k];
+            }
+        }
+        return true;
     };
 
-    enter_span(blockIdx.x);
+    load_chunk(blockIdx.x);
     Segment cur, nxt;
     bool has_cur = advance(cur);
     if (has_cur) {
         // prime the ring with the first segment
         if (!cur.prefix) issue_q<D, KVB, NST>(a, q, lc, cur, ring.qslot, lds_addr);
-        const int n = min(NST - 1, cur.stages());
+        const int n = min(NST - 1, cur.entries());
         for (int k = 0; k < n; k++) {
-            const int p = cur.pg_lo + 2 * k;
-            const int id0 = uniform_load(cur.pages, p), id1 = p + 1 < cur.pg_hi ? uniform_load(cur.pages, p + 1) : 0;
-            issue_stage<D, KVB, NST>(a, lc, cur, k, id0, id1, ring.issued % NST, lds_addr);
+            const int st = k - cur.prefix;
+            if (st < 0) {
+                issue_qrows<D, KVB, NST>(a, q, lc, cur, ring.issued % NST, lds_addr);
+            } else {
+                const int p = cur.pg_lo + 2 * st;
+                const int id0 = uniform_load(cur.pages, p), id1 = p + 1 < cur.pg_hi ? uniform_load(cur.pages, p + 1) : 0;
+                issue_stage<D, KVB, NST>(a, lc, cur, st, id0, id1, ring.issued % NST, lds_addr);
+            }
             ring.issued++;
         }
     }
     while (has_cur) {
         const bool has_nxt = advance(nxt);
         if (!cur.prefix) {
-            run_segment<D, KVB, 1, NST>(a, q, members, cur, has_nxt, nxt, ring, lc, lds, lds_addr, fresh);
+            run_segment<D, KVB, 1, NST>(a, q, cur, has_nxt, nxt, ring, lc, lds, lds_addr, fresh);
             fresh.slot = cur.slot;
             if (npend == NPEND) { // full: write the oldest out
                 store_pending<D>(a, pend[0], lane);
@@ -927,7 +982,7 @@ template <int D, int KVB, int NST, int NPEND> __device__ __forceinline__ void at
                 if (k == npend) pend[k] = fresh;
             npend++;
         } else {
-            run_segment<D, KVB, kPrefixTiles, NST>(a, q, members, cur, has_nxt, nxt, ring, lc, lds, lds_addr, fresh);
+            run_segment<D, KVB, PrefixTiles<KVB>::value, NST>(a, q, cur, has_nxt, nxt, ring, lc, lds, lds_addr, fresh);
         }
         cur = nxt;
         has_cur = has_nxt;
@@ -940,21 +995,21 @@ template <int D, int KVB, int NST, int NPEND> __device__ __forceinline__ void at
 // Ring depths (in stages of two pages).  bf16 KV: two stages (32 KB + 8 KB of query slots, four waves per
 // compute unit) or three.  e4m3 KV: pages are half the size: three stages, or two; these kernels keep one finished
 // partial in registers instead of three and are held to half the register file, so that two waves share a SIMD.
-template <int D> __global__ __launch_bounds__(64) void attention_kernel_s3(RA_ATTN_PARAMS, int32_t *next_span)
+template <int D> __global__ __launch_bounds__(64) void attention_kernel_s3(RA_ATTN_PARAMS)
 {
-    attention_body<D, 2, 3, 3>(RA_ATTN_ARGS, next_span);
+    attention_body<D, 2, 3, 3>(RA_ATTN_ARGS);
 }
-template <int D> __global__ __launch_bounds__(64) void attention_kernel_s2(RA_ATTN_PARAMS, int32_t *next_span)
+template <int D> __global__ __launch_bounds__(64) void attention_kernel_s2(RA_ATTN_PARAMS)
 {
-    attention_body<D, 2, 2, 3>(RA_ATTN_ARGS, next_span);
+    attention_body<D, 2, 2, 3>(RA_ATTN_ARGS);
 }
-template <int D> __global__ __launch_bounds__(64, 2) void attention_kernel_fp8(RA_ATTN_PARAMS, int32_t *next_span)
+template <int D> __global__ __launch_bounds__(64, 2) void attention_kernel_fp8(RA_ATTN_PARAMS)
 {
-    attention_body<D, 1, 3, 1>(RA_ATTN_ARGS, next_span);
+    attention_body<D, 1, 3, 1>(RA_ATTN_ARGS);
 }
-template <int D> __global__ __launch_bounds__(64, 2) void attention_kernel_fp8_s2(RA_ATTN_PARAMS, int32_t *next_span)
+template <int D> __global__ __launch_bounds__(64, 2) void attention_kernel_fp8_s2(RA_ATTN_PARAMS)
 {
-    attention_body<D, 1, 2, 1>(RA_ATTN_ARGS, next_span);
+    attention_body<D, 1, 2, 1>(RA_ATTN_ARGS);
 }
 
 static size_t attention_lds_bytes(int D, int kv_fp8, int stages)
@@ -1007,7 +1062,7 @@ hipError_t launch_attention(const Launch &a, hipStream_t s)
     const Workspace &w = a.ws;
 #define RA_LAUNCH(K)                                                                                                      \
     hipLaunchKernelGGL(K, dim3(a.waves), dim3(64), lds, s, a, a.q, a.block_table, a.pfx_pages, w.hdr,                       \
-                       (const uint32_t *)w.seg_rec, w.members, w.hdr + 5)
+                       (const uint32_t *)w.seg_rec, w.members)
     if (a.kv_fp8 && a.stages == 2) {
         if (a.D == 128) RA_LAUNCH(attention_kernel_fp8_s2<128>);
         else RA_LAUNCH(attention_kernel_fp8_s2<64>);
@@ -1115,10 +1170,10 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(Launch a, const in
         PartList &p = pl[0];
         p.c_lo = pfx.y, p.c_hi = pfx.z;
         const int64_t pitem = (int64_t)(prow < 0 ? 0 : prow) * a.Hkv + kvh;
-        p.o = w.pfx_o + (pitem * kPrefixRows + row0) * D;
-        p.lse = w.pfx_lse + pitem * kPrefixRows + row0;
-        p.ostride = (int64_t)kPrefixRows * D;
-        p.lstride = kPrefixRows;
+        p.o = w.pfx_o + (pitem * a.prefix_rows + row0) * D;
+        p.lse = w.pfx_lse + pitem * a.prefix_rows + row0;
+        p.ostride = (int64_t)a.prefix_rows * D;
+        p.lstride = a.prefix_rows;
     }
     const int npfx = pl[0].c_hi - pl[0].c_lo + 1, nown = pl[1].c_hi - pl[1].c_lo + 1;
     for (int hl = threadIdx.x / tpr; hl < a.G; hl += kMergeThreads / tpr) {

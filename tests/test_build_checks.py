@@ -28,25 +28,35 @@ def kernels(isa):
     return out
 
 
+def descriptors(isa, prefix):
+    """name -> (vector registers, scratch bytes) from each kernel's own descriptor."""
+    out = {}
+    for m in re.finditer(r"\.amdhsa_kernel (%s\w+)\n(.*?)\.end_amdhsa_kernel" % prefix, isa, flags=re.S):
+        regs = int(re.search(r"\.amdhsa_next_free_vgpr (\d+)", m.group(2)).group(1))
+        scratch = int(re.search(r"\.amdhsa_private_segment_fixed_size (\d+)", m.group(2)).group(1))
+        out[m.group(1)] = (regs, scratch)
+    return out
+
+
 def test_no_scratch_and_no_full_drain_in_the_page_loop(isa):
-    for name, body in kernels(isa).items():
-        assert ".private_segment_fixed_size: 0" in isa
+    desc = descriptors(isa, r"_ZN2ra\d+attention_kernel")
+    bodies = kernels(isa)
+    assert len(bodies) == 8 and set(desc) == set(bodies)     # bf16 and e4m3, two ring depths, two head dims
+    for name, body in bodies.items():
+        regs, scratch = desc[name]
+        assert scratch == 0 and regs <= 512, (name, regs, scratch)
         assert "scratch_" not in body, name
         # the LDS ring is paced by hand-written waits with a non-zero count; they must be there
         assert re.search(r"s_waitcnt vmcnt\([1-9][0-9]*\)", body), name
 
 
-
 def test_e4m3_kernels_fit_two_waves_per_simd(isa):
     """The e4m3 decode kernels are scheduled for two waves on a SIMD (six workgroups per compute unit at head dim
     128): that holds only while they stay within half of the 512 registers a lane has, without scratch."""
-    seen = 0
-    for m in re.finditer(r"\.amdhsa_kernel (_ZN2ra\d+attention_kernel_fp8\w+)\n(.*?)\.end_amdhsa_kernel", isa, flags=re.S):
-        regs = int(re.search(r"\.amdhsa_next_free_vgpr (\d+)", m.group(2)).group(1))
-        scratch = int(re.search(r"\.amdhsa_private_segment_fixed_size (\d+)", m.group(2)).group(1))
-        assert regs <= 256 and scratch == 0, (m.group(1), regs, scratch)
-        seen += 1
-    assert seen == 4    # two ring depths, two head dims
+    desc = descriptors(isa, r"_ZN2ra\d+attention_kernel_fp8")
+    assert len(desc) == 4    # two ring depths, two head dims
+    for name, (regs, scratch) in desc.items():
+        assert regs <= 256 and scratch == 0, (name, regs, scratch)
 
 
 def test_prefill_kernels_keep_their_accumulators_in_registers():

@@ -28,7 +28,7 @@ def check_schedule(dec, p, use_hint=True, label=""):
     dp = DeviceProblem(p, use_hint=use_hint)
     info, hdr, rec, md = read_schedule(dec, dp)
     nspans, nPR = int(hdr[7]), int(hdr[3])
-    assert nspans >= info.waves and int(hdr[2]) == p.B + nPR
+    assert nspans == info.waves and int(hdr[2]) == p.B + nPR
     G = p.Hq // p.Hkv
     max_pages = p.block_table.shape[1]
     npages = (p.seq_lens.astype(np.int64) + 15) // 16
@@ -56,7 +56,7 @@ def check_schedule(dec, p, use_hint=True, label=""):
                     own.setdefault((b, kvh), []).append((c, lo, hi, skip))
                 else:
                     assert 0 <= idx and idx + hi <= p.prefix_pages.size and lim == 16 * hi, (label, "shared pages past the list")
-                    assert 0 < nrows <= 32 and nrows % G == 0 and 0 <= who and who + nrows // G <= p.B
+                    assert 0 < nrows <= (64 if p.kv_dtype == "bf16" else 32) and nrows % G == 0 and 0 <= who and who + nrows // G <= p.B
                     row = (slot - c - kvh) // p.Hkv
                     assert 0 <= row < nPR and slot == row * p.Hkv + kvh + c
                     shared.setdefault((row, kvh), []).append((c, lo, hi, idx))
@@ -111,50 +111,14 @@ def dec():
     d.close()
 
 
-@pytest.fixture(scope="module")
-def dec_tail():
-    """A context whose schedule hands the last 30 % of the page stream out at run time, in spans of 8 pages (the
-    settings are read when the context is made)."""
-    import os
-    keys = {"ROLLOUT_ATTN_STATIC_PCT": "70", "ROLLOUT_ATTN_DYN_PAGES": "8"}
-    old = {k: os.environ.get(k) for k in keys}
-    os.environ.update(keys)
-    try:
-        d = ra.Decoder(0)
-    finally:
-        for k, v in old.items():
-            if v is None:
-                os.environ.pop(k, None)
-            else:
-                os.environ[k] = v
-    yield d
-    d.close()
-
-
-@pytest.mark.parametrize("name", ["tiny", "mid7b", "mid72b", "grpo7b"])
-def test_schedule_with_a_tail_handed_out_at_run_time(dec_tail, name):
-    p = workload.make_problem(name, seed=2)
-    nspans = check_schedule(dec_tail, p, True, name + " (tail)")
-    info, _ = dec_tail.schedule(DeviceProblem(p).c)
-    if name == "grpo7b":
-        assert nspans > info.waves, "the tail was not cut into spans of its own"
-
-
-@pytest.mark.parametrize("name", ["tiny", "mid7b", "mid32b", "mid72b"])
-def test_parity_with_a_tail_handed_out_at_run_time(dec_tail, name):
-    import oracle
-    from gpu_util import compare
-    p = workload.make_problem(name, seed=0)
-    ref = oracle.decode(p)
-    for hint in (True, False):
-        dp = DeviceProblem(p, use_hint=hint)
-        dec_tail.decode(dp.c)
-        compare(*dp.results(), *ref, "%s (tail, hint %s)" % (name, hint))
-
-
-@pytest.mark.parametrize("name", ["tiny", "mid7b", "mid32b", "mid72b", "grpo7b"])
+@pytest.mark.parametrize("name", ["tiny", "mid7b", "mid32b", "mid72b", "grpo7b", "tail32b", "stream72b"])
 def test_schedule_of_the_configurations(dec, name):
-    p = workload.make_problem(name, seed=1)
+    # (the schedule reads lengths, groups and prefix offsets only: the two largest configurations get one dummy page)
+    big = name in ("tail32b", "stream72b")
+    p = workload.make_problem(name, seed=1, make_values=not big)
+    if big:
+        p.q = np.zeros((p.B, p.Hq, p.D), dtype=np.uint16)
+        p.k_pool = p.v_pool = np.zeros((1, p.Hkv, 16, p.D), dtype=np.uint16)
     check_schedule(dec, p, True, name)
     check_schedule(dec, p, False, name + " (no hint)")
 
