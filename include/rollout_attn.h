@@ -164,6 +164,18 @@ ra_status rollout_attn_workspace_size(const ra_ctx *ctx, const ra_problem *shape
 ra_status rollout_attn_decode(ra_ctx *ctx, const ra_problem *problem, void *workspace, size_t workspace_bytes,
                               void *hip_stream);
 
+/* rollout_attn_decode for callers that cannot allocate device memory or have none to spare for a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same step with the same
+ * kernels and byte-identical results, on a workspace that is built into the library, a fixed 64 MiB array in
+ * device memory that every GPU the library is loaded on holds until the process ends.  Neither this call nor
+ * anything it launches allocates or frees memory.  RA_ERR_WORKSPACE_TOO_SMALL when the problem's shape needs more
+ * than 64 MiB (rollout_attn_workspace_size says how much a shape needs; the 7B-shaped batch of 256 sequences needs
+ * about 50 MiB); nothing is enqueued then.  All calls on one GPU share the one array, whatever their context or
+ * stream: calls that overlap in time on one GPU race, so order them on one stream or with events.  RA_FLAG_REUSE_SCHEDULE
+ * refers to the schedule the previous call on the GPU left in the array.  Everything else is as for
+ * rollout_attn_decode. */
+ra_status rollout_attn_decode_static(ra_ctx *ctx, const ra_problem *problem, void *hip_stream);
+
 /* Copies the stored K and V elements of sequence b, KV head kv_head, in logical token order, to k_out and
  * v_out (dev, [L_b][D] raw elements: 2 bytes each for bf16, 1 for e4m3), through the same block-table
  * arithmetic as the attention kernels.  capacity_tokens is the room in k_out / v_out; a longer sequence is

@@ -82,6 +82,8 @@ def load_library():
     lib.rollout_attn_workspace_size.argtypes = [ctypes.c_void_p, P(ra_problem), P(ctypes.c_size_t)]
     lib.rollout_attn_decode.restype = ctypes.c_int
     lib.rollout_attn_decode.argtypes = [ctypes.c_void_p, P(ra_problem), ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.rollout_attn_decode_static.restype = ctypes.c_int
+    lib.rollout_attn_decode_static.argtypes = [ctypes.c_void_p, P(ra_problem), ctypes.c_void_p]
     lib.rollout_attn_debug_gather.restype = ctypes.c_int
     lib.rollout_attn_debug_gather.argtypes = [ctypes.c_void_p, P(ra_problem), ctypes.c_int32, ctypes.c_int32,
                                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
@@ -145,6 +147,10 @@ def rollout_attn_workspace_size(ctx, problem):
 
 def rollout_attn_decode(ctx, problem, workspace_ptr, workspace_bytes, hip_stream=None):
     _check(load_library().rollout_attn_decode(ctx, ctypes.byref(problem), workspace_ptr, workspace_bytes, hip_stream), ctx)
+
+
+def rollout_attn_decode_static(ctx, problem, hip_stream=None):
+    _check(load_library().rollout_attn_decode_static(ctx, ctypes.byref(problem), hip_stream), ctx)
 
 
 def rollout_attn_debug_gather(ctx, problem, b, kv_head, k_out_ptr, v_out_ptr, capacity_tokens, hip_stream=None):
@@ -297,6 +303,12 @@ class Decoder:
         ws = self.workspace(problem)
         s = stream if stream is not None else torch.cuda.current_stream(self.device_ordinal)
         rollout_attn_decode(self.ctx, problem, ctypes.c_void_p(ws.data_ptr()), ws.numel(), ctypes.c_void_p(s.cuda_stream))
+
+    def decode_static(self, problem, stream=None):
+        """The same step on the library's built-in workspace (no allocation anywhere)."""
+        import torch
+        s = stream if stream is not None else torch.cuda.current_stream(self.device_ordinal)
+        rollout_attn_decode_static(self.ctx, problem, ctypes.c_void_p(s.cuda_stream))
 
     def schedule(self, problem, stream=None):
         """Runs only the schedule; returns (ra_schedule_info, the workspace tensor it was written to)."""

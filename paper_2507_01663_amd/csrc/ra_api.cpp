@@ -9,8 +9,14 @@
 #include <cstring>
 #include <vector>
 
+// Workspace of rollout_attn_decode_static: device memory that exists from the moment the library is loaded, one
+// copy per GPU.  The name is a host-side handle; the device address is asked for once per context (= per device).
+constexpr size_t kScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 struct ra_ctx {
     int device;
+    void *scratch_ptr; // device address of `scratch` on this context's device
     int num_cus;
     int waves[2][2];  // resident attention waves, [e4m3 KV][D == 128]
     int stages[2][2]; // LDS ring depth, same indices
@@ -226,6 +232,7 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
         for (int d = 0; d < 2; d++)
             if (e == hipSuccess) e = ra::attention_config(d ? 128 : 64, f, c->num_cus, &c->stages[f][d], &c->waves[f][d]);
     if (e == hipSuccess) e = ra::prefill_config();
+    if (e == hipSuccess) e = hipGetSymbolAddress(&c->scratch_ptr, HIP_SYMBOL(scratch)); // this device's copy
     if (e == hipSuccess && calibrate) {
         calibrate_dies(c->waves[0][1], c->xcd_w[0]);
         calibrate_dies(c->waves[1][1], c->xcd_w[1]);
@@ -330,6 +337,23 @@ ra_status rollout_attn_decode(ra_ctx *c, const ra_problem *p, void *workspace, s
     if (!workspace || ((uintptr_t)workspace & 255)) { set_err(c, "workspace is NULL or not 256-byte aligned"); return RA_ERR_INVALID_ARG; }
     if (workspace_bytes < need) {
         set_err(c, "workspace of %zu bytes given, %zu needed", workspace_bytes, need);
+        return RA_ERR_WORKSPACE_TOO_SMALL;
+    }
+    return enqueue_decode(c, p, a, (hipStream_t)stream);
+}
+
+ra_status rollout_attn_decode_static(ra_ctx *c, const ra_problem *p, void *stream)
+{
+    if (!c) { set_err(nullptr, "ctx is NULL"); return RA_ERR_INVALID_ARG; }
+    ra_status st = check(p, c->err, sizeof c->err);
+    if (st != RA_OK) return st;
+    if (p->B == 0) return RA_OK;
+    ra::Launch a;
+    fill_launch(a, c, p);
+    size_t need = ra::carve_workspace(a.ws, c->scratch_ptr, a.B, a.Hkv, a.G, a.D, a.num_groups, a.waves, a.prefix_rows);
+    if (need > kScratchBytes) {
+        set_err(c, "this problem needs a workspace of %zu bytes; the built-in one holds %zu (use rollout_attn_decode)", need,
+                kScratchBytes);
         return RA_ERR_WORKSPACE_TOO_SMALL;
     }
     return enqueue_decode(c, p, a, (hipStream_t)stream);
