@@ -61,7 +61,8 @@ enum {
     RA_FLAG_VALIDATE = 1u,          /* check device-side lengths / page ids / hint first (one extra kernel + a
                                        stream synchronisation) */
     RA_FLAG_NO_PREFIX_SHARING = 2u, /* ignore the prompt-group hint (for A/B comparison) */
-    RA_FLAG_REUSE_SCHEDULE = 4u     /* skip the schedule kernels and use the schedule that the previous
+    RA_FLAG_REUSE_SCHEDULE = 4u     /* skip the schedule kernels (when the batch is large enough for them to be launched
+                                       at all) and use the schedule that the previous
                                        rollout_attn_decode call on the same context left in the same workspace.
                                        For the layers of one decode step: the schedule depends only on B, the head
                                        counts, D, max_pages_per_seq, seq_lens, seq_group, prefix_page_offsets and
@@ -120,22 +121,20 @@ typedef struct {
 /* ROLLOUT_ATTN_ABI_VERSION of the library that was loaded. */
 uint32_t rollout_attn_abi_version(void);
 
-/* Creates a context on the given HIP device: queries the device, allocates a few hundred bytes of device
- * memory that the context keeps, and measures for about a millisecond how the memory bandwidth is shared
- * among the device's dies (the attention kernel balances its work by that; the measurement borrows 256 MiB
- * of device memory and returns it before the call ends, and is skipped when that much is not free).
- * *ctx is NULL on failure.  RA_ERR_DEVICE when the device cannot be used.
+/* Creates a context on the given HIP device: queries the device and allocates a few hundred bytes of device
+ * memory that the context keeps.  *ctx is NULL on failure.  RA_ERR_DEVICE when the device cannot be used.
  *
  * Tuning knobs, read from the environment here and nowhere else (none changes a result beyond rounding; values
  * out of range are ignored):
- *   ROLLOUT_ATTN_CALIBRATE=0        skip the measurement and use built-in die weights
- *   ROLLOUT_ATTN_XCD_WEIGHTS=a,..,h the eight die weights, per mille of the mean (700..1400); implies the above
+ *   ROLLOUT_ATTN_XCD_WEIGHTS=a,..,h the share of the work each of the eight dies' workgroups get, per mille of the
+ *                                   mean (700..1400; default: equal shares)
  *   ROLLOUT_ATTN_STAGES=2|3, ROLLOUT_ATTN_FP8_STAGES=2|3   depth of the LDS ring for bf16 / e4m3 pools
  *   ROLLOUT_ATTN_WAVES_PER_CU=1..16 attention workgroups per compute unit (default: as many as are resident)
- *   ROLLOUT_ATTN_STATIC_PCT=0..100  share of the work assigned to workgroups up front (default 100); the rest is
- *                                   handed out at run time in spans of ROLLOUT_ATTN_DYN_PAGES=1..4096 pages
  *   ROLLOUT_ATTN_COST_PREFIX=1..16, ROLLOUT_ATTN_COST_ITEM=0..256   scheduling weights of a shared-prefix page and
  *                                   of a segment (a page of a sequence's own weighs 4)
+ *   ROLLOUT_ATTN_SELF_PLAN=0        always launch the schedule kernels (default: batches of up to 512 sequences and
+ *                                   511 groups are scheduled by the attention workgroups themselves, each for its own
+ *                                   share of the work, which saves a kernel; the schedule is the same either way)
  *   ROLLOUT_ATTN_VERBOSE            print the die weights to stderr */
 ra_status rollout_attn_create(ra_ctx **ctx, int device_ordinal);
 
@@ -156,7 +155,8 @@ ra_status rollout_attn_check_problem(const ra_problem *problem, char *msg, size_
 ra_status rollout_attn_workspace_size(const ra_ctx *ctx, const ra_problem *shape_only, size_t *bytes);
 
 /* Enqueues the whole step (schedule, attention over shared prompt pages and over each sequence's own
- * pages, log-sum-exp merge) on hip_stream (a hipStream_t, NULL = default stream) and returns without
+ * pages, log-sum-exp merge: two kernels for batches of up to 512 sequences, where the attention workgroups schedule
+ * themselves, else three or four) on hip_stream (a hipStream_t, NULL = default stream) and returns without
  * waiting; out and lse are valid once the stream has reached that point.  workspace is dev memory of at
  * least rollout_attn_workspace_size() bytes, 256-byte aligned, contents irrelevant on entry and undefined
  * afterwards; calls that overlap in time need distinct workspaces.  Results are deterministic: the same
@@ -295,6 +295,18 @@ ra_status rollout_attn_prefill(ra_ctx *ctx, const ra_prefill *prefill, void *hip
  * runs out. */
 ra_status rollout_attn_balance(const int64_t *weights, int64_t n, int32_t k, int32_t equal_count, int32_t *part,
                                int64_t *part_sums);
+
+/* Streaming probe for benchmarks: what the memory system delivers to the attention kernel's access pattern when no
+ * arithmetic is done (the decode step is memory-bound, paper Sec. 2.1.1, so this is the practical ceiling its achieved
+ * bandwidth is judged against, beside the published peak).  Launches the attention kernel's grid (one wave per
+ * workgroup, all resident) with its LDS ring of 16 KB entries fed by direct global-to-LDS loads; every wave reads
+ * entries_per_wave entries, each as 16384 / granule_bytes pieces of granule_bytes (a power of two, 1024..16384; 4096
+ * is the K or V tile of one page and head at head dim 128 in bf16), each piece from a place of its own: a fixed
+ * permutation of the buffer's granules when scattered != 0, consecutive granules (the grid sweeps the buffer, wrapping
+ * around) otherwise.  buf: dev, read only, 16-byte aligned, buf_bytes a power of two >= 16384.  *bytes_read (may be
+ * NULL) receives the bytes the launch reads.  Enqueued on hip_stream; the caller times it. */
+ra_status rollout_attn_debug_stream(ra_ctx *ctx, const void *buf, size_t buf_bytes, int32_t granule_bytes, int32_t scattered,
+                                    int32_t entries_per_wave, void *hip_stream, size_t *bytes_read);
 
 /* Per-kernel timing for benchmarks.  While enabled, rollout_attn_decode records HIP events on its stream
  * around its three phases (schedule, attention, merge); rollout_attn_get_timing waits for the events of the

@@ -98,6 +98,9 @@ def load_library():
     lib.rollout_attn_prefill.argtypes = [ctypes.c_void_p, P(ra_prefill), ctypes.c_void_p]
     lib.rollout_attn_balance.restype = ctypes.c_int
     lib.rollout_attn_balance.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+    lib.rollout_attn_debug_stream.restype = ctypes.c_int
+    lib.rollout_attn_debug_stream.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32,
+                                              ctypes.c_int32, ctypes.c_void_p, P(ctypes.c_size_t)]
     lib.rollout_attn_set_timing.restype = ctypes.c_int
     lib.rollout_attn_set_timing.argtypes = [ctypes.c_void_p, ctypes.c_int]
     lib.rollout_attn_get_timing.restype = ctypes.c_int
@@ -189,6 +192,14 @@ def rollout_attn_balance(weights, k, equal_count=False):
     _check(load_library().rollout_attn_balance(w.ctypes.data, w.size, int(k), int(bool(equal_count)), part.ctypes.data,
                                                sums.ctypes.data), None)
     return part, sums
+
+
+def rollout_attn_debug_stream(ctx, buf_ptr, buf_bytes, granule_bytes, scattered, entries_per_wave, hip_stream=None):
+    """Enqueues the streaming probe; returns the bytes the launch reads."""
+    n = ctypes.c_size_t()
+    _check(load_library().rollout_attn_debug_stream(ctx, buf_ptr, buf_bytes, granule_bytes, int(bool(scattered)), entries_per_wave,
+                                                    hip_stream, ctypes.byref(n)), ctx)
+    return int(n.value)
 
 
 def rollout_attn_set_timing(ctx, enable):

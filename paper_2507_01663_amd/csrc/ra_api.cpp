@@ -22,8 +22,9 @@ struct ra_ctx {
     int stages[2][2]; // LDS ring depth, same indices
     int cost_prefix[2]; // scheduling weight of a shared-prefix page, [e4m3 KV]
     int cost_item;   // ... of a segment, on top of its pages
-    int xcd_w[2][8]; // relative speed of the accelerator dies, measured in the launch shape of [e4m3 KV]
+    int xcd_w[2][8]; // share of the page stream per accelerator die, [e4m3 KV]
     void *zeros;  // 256 bytes of zeros on the device
+    int self_plan; // attention waves may plan their spans themselves (no schedule kernel)
     int32_t *host_flags; // pinned, for RA_FLAG_VALIDATE
     int timing;          // record events around the phases
     int timed;           // a decode call has recorded them
@@ -132,6 +133,7 @@ void fill_launch(ra::Launch &a, const ra_ctx *ctx, const ra_problem *p)
     a.scale_log2 = p->softmax_scale * 1.4426950408889634f;
     a.out = (uint16_t *)p->out; a.lse = p->lse;
     a.zeros = ctx ? ctx->zeros : nullptr;
+    a.self_plan = ctx && ctx->self_plan && ra::can_self_plan(a.D, a.kv_fp8, a.stages, a.B, a.share ? a.num_groups : 0, a.members_per_row);
 }
 
 } // namespace
@@ -139,43 +141,6 @@ void fill_launch(ra::Launch &a, const ra_ctx *ctx, const ra_problem *p)
 extern "C" {
 
 uint32_t rollout_attn_abi_version(void) { return ROLLOUT_ATTN_ABI_VERSION; }
-
-// Measures the dies' relative streaming speed (see calibrate_kernel) and turns it into span weights, per mille
-// of the mean.  Needs a quarter of a gigabyte of device memory for a moment; on any failure, or when the
-// workgroups are not dealt to the dies round-robin as the schedule assumes, the weights are left alone.
-static void calibrate_dies(int waves, int *weights)
-{
-    if (waves <= 0 || waves % 8) return;
-    const int stages = 16;
-    int nblocks = 1;
-    while (nblocks < waves * stages) nblocks <<= 1;
-    void *buf = nullptr;
-    long long *dev = nullptr;
-    std::vector<long long> host((size_t)2 * waves);
-    double dur[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    bool ok = hipMalloc(&buf, (size_t)nblocks * 16384) == hipSuccess && hipMalloc((void **)&dev, host.size() * 8) == hipSuccess;
-    ok = ok && hipMemset(buf, 0, (size_t)nblocks * 16384) == hipSuccess;
-    for (int rep = 0; rep < 4 && ok; rep++) { // the first run warms up
-        ok = ra::launch_calibrate(buf, nblocks, stages, waves, dev, nullptr) == hipSuccess &&
-             hipMemcpy(host.data(), dev, host.size() * 8, hipMemcpyDeviceToHost) == hipSuccess;
-        for (int w = 0; w < waves && ok; w++) {
-            ok = host[2 * w + 1] == w % 8 && host[2 * w] > 0;
-            if (rep > 0) dur[w % 8] += (double)host[2 * w];
-        }
-    }
-    if (buf) (void)hipFree(buf);
-    if (dev) (void)hipFree(dev);
-    if (!ok) {
-        (void)hipGetLastError();
-        return;
-    }
-    double mean_speed = 0;
-    for (int x = 0; x < 8; x++) mean_speed += 1.0 / dur[x] / 8;
-    for (int x = 0; x < 8; x++) {
-        int w = (int)(1024.0 / dur[x] / mean_speed + 0.5);
-        weights[x] = w < 800 ? 800 : (w > 1250 ? 1250 : w);
-    }
-}
 
 ra_status rollout_attn_create(ra_ctx **out, int device)
 {
@@ -192,23 +157,21 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
     c->cost_prefix[0] = ra::kCostPrefix;
     c->cost_prefix[1] = ra::kCostPrefixFp8;
     c->cost_item = ra::kCostItem;
-    // Share of the memory bandwidth each accelerator die gets when all eight stream at once (per mille of the
-    // mean).  This is what a typical MI355X shows; the context measures its own device below.
-    static const int kXcdSpeed[8] = {1024, 944, 1089, 978, 1064, 973, 1013, 936};
-    for (int x = 0; x < 8; x++) c->xcd_w[0][x] = c->xcd_w[1][x] = kXcdSpeed[x];
-    bool calibrate = true;
-    if (const char *ev = getenv("ROLLOUT_ATTN_CALIBRATE")) calibrate = atoi(ev) != 0;
+    // Share of the page stream each accelerator die's workgroups get, per mille of the mean.  The dies do not stream
+    // equally fast, but the pattern changes from machine to machine and with the pools' placement, so the default is
+    // equal shares; ROLLOUT_ATTN_XCD_WEIGHTS is there for experiments.
+    for (int x = 0; x < 8; x++) c->xcd_w[0][x] = c->xcd_w[1][x] = 1000;
     if (const char *ev = getenv("ROLLOUT_ATTN_XCD_WEIGHTS")) {
         int v[8];
         if (sscanf(ev, "%d,%d,%d,%d,%d,%d,%d,%d", &v[0], &v[1], &v[2], &v[3], &v[4], &v[5], &v[6], &v[7]) == 8) {
             bool ok = true;
             for (int x = 0; x < 8; x++) ok = ok && v[x] >= 700 && v[x] <= 1400; // no span under half the mean
-            if (ok) {
+            if (ok)
                 for (int x = 0; x < 8; x++) c->xcd_w[0][x] = c->xcd_w[1][x] = v[x];
-                calibrate = false;
-            }
         }
     }
+    c->self_plan = 1;
+    if (const char *ev = getenv("ROLLOUT_ATTN_SELF_PLAN")) c->self_plan = atoi(ev) != 0;
     if (const char *ev = getenv("ROLLOUT_ATTN_COST_PREFIX")) {
         int v = atoi(ev);
         if (v >= 1 && v <= 16) c->cost_prefix[0] = c->cost_prefix[1] = v;
@@ -233,10 +196,6 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
             if (e == hipSuccess) e = ra::attention_config(d ? 128 : 64, f, c->num_cus, &c->stages[f][d], &c->waves[f][d]);
     if (e == hipSuccess) e = ra::prefill_config();
     if (e == hipSuccess) e = hipGetSymbolAddress(&c->scratch_ptr, HIP_SYMBOL(scratch)); // this device's copy
-    if (e == hipSuccess && calibrate) {
-        calibrate_dies(c->waves[0][1], c->xcd_w[0]);
-        calibrate_dies(c->waves[1][1], c->xcd_w[1]);
-    }
     if (getenv("ROLLOUT_ATTN_VERBOSE"))
         for (int f = 0; f < 2; f++)
             fprintf(stderr, "rollout_attn: die weights (%s KV) %d %d %d %d %d %d %d %d\n", f ? "e4m3" : "bf16", c->xcd_w[f][0],
@@ -312,8 +271,9 @@ static ra_status enqueue_decode(ra_ctx *c, const ra_problem *p, const ra::Launch
     }
     const bool tm = c->timing != 0;
     if (e == hipSuccess && tm) e = hipEventRecord(c->ev[0], s);
+    // no schedule kernel when the batch's tables fit in the attention waves' LDS (they plan their spans themselves)
     const bool reuse = (p->flags & RA_FLAG_REUSE_SCHEDULE) != 0;
-    if (e == hipSuccess && !reuse) e = ra::launch_plan(a, s);
+    if (e == hipSuccess && !reuse && !a.self_plan) e = ra::launch_plan(a, s);
     if (e == hipSuccess && tm) e = hipEventRecord(c->ev[1], s);
     if (e == hipSuccess) e = ra::launch_attention(a, s);
     if (e == hipSuccess && tm) e = hipEventRecord(c->ev[2], s);
@@ -507,6 +467,28 @@ ra_status rollout_attn_prefill(ra_ctx *c, const ra_prefill *p, void *stream)
     if (e == hipSuccess) e = ra::launch_prefill(a, (hipStream_t)stream);
     if (prev != c->device) (void)hipSetDevice(prev);
     if (e != hipSuccess) { set_err(c, "HIP: %s", hipGetErrorString(e)); return RA_ERR_DEVICE; }
+    return RA_OK;
+}
+
+ra_status rollout_attn_debug_stream(ra_ctx *c, const void *buf, size_t buf_bytes, int32_t granule_bytes, int32_t scattered,
+                                    int32_t entries_per_wave, void *stream, size_t *bytes_read)
+{
+    if (!c) { set_err(nullptr, "ctx is NULL"); return RA_ERR_INVALID_ARG; }
+    const bool pow2 = buf_bytes && !(buf_bytes & (buf_bytes - 1));
+    if (!buf || ((uintptr_t)buf & 15) || !pow2 || buf_bytes < 16384 || buf_bytes > ((size_t)1 << 40) || entries_per_wave < 1 ||
+        (granule_bytes != 1024 && granule_bytes != 2048 && granule_bytes != 4096 && granule_bytes != 8192 && granule_bytes != 16384)) {
+        set_err(c, "stream probe: buf must be 16-byte aligned, buf_bytes a power of two of at least 16384, granule_bytes a power "
+                   "of two in 1024..16384, entries_per_wave positive");
+        return RA_ERR_INVALID_ARG;
+    }
+    const int waves = c->waves[0][1];
+    int prev = 0;
+    hipError_t e = hipGetDevice(&prev);
+    if (e == hipSuccess && prev != c->device) e = hipSetDevice(c->device);
+    if (e == hipSuccess) e = ra::launch_stream_probe(buf, buf_bytes, granule_bytes, scattered != 0, entries_per_wave, waves, (hipStream_t)stream);
+    if (prev != c->device) (void)hipSetDevice(prev);
+    if (e != hipSuccess) { set_err(c, "HIP: %s", hipGetErrorString(e)); return RA_ERR_DEVICE; }
+    if (bytes_read) *bytes_read = (size_t)waves * entries_per_wave * 16384;
     return RA_OK;
 }
 

@@ -53,6 +53,7 @@ struct Launch {
     uint16_t *out;
     float *lse;
     const void *zeros;                    // >= 16 bytes of zeros
+    int32_t self_plan;                    // the attention waves plan their spans themselves: no schedule kernel
     Workspace ws;
 };
 
@@ -85,10 +86,12 @@ size_t carve_workspace(Workspace &ws, void *base, int B, int Hkv, int G, int D, 
 // launch on the current device, for head dim D: as many as are resident at once (bf16 pools: one per SIMD; e4m3 pools:
 // up to two per SIMD, as many as the ring's LDS lets in).
 hipError_t attention_config(int D, int kv_fp8, int num_cus, int *stages, int *waves);
+// Whether a batch's schedule tables fit in the LDS of an attention wave (then no schedule kernel is needed).
+bool can_self_plan(int D, int kv_fp8, int stages, int B, int num_groups, int members_per_row);
 
-// Streams nblocks * 16 KB of buf (nblocks a power of two, = waves * stages) through the attention kernel's ring
-// and writes {duration in 10 ns ticks, die} per wave to out[2 * waves].
-hipError_t launch_calibrate(const void *buf, int nblocks, int stages, int waves, long long *out, hipStream_t s);
+// Streams entries * 16 KB per wave from buf (a power of two of bytes) through the attention kernel's ring, in pieces of
+// `granule` bytes (1024 .. 16384, a power of two), scattered over the buffer or consecutive.
+hipError_t launch_stream_probe(const void *buf, size_t buf_bytes, int granule, int scattered, int entries, int waves, hipStream_t s);
 hipError_t launch_validate(const Launch &a, hipStream_t s);
 hipError_t launch_plan(const Launch &a, hipStream_t s);
 hipError_t launch_attention(const Launch &a, hipStream_t s);

@@ -95,15 +95,16 @@ __device__ __forceinline__ void span_pages(int S, int cw, int n, int lo, int hi,
 constexpr int kPlanThreads = 256;
 constexpr int kPlanCap = 2048; // sequences / groups whose intermediate arrays fit in LDS; beyond, the workspace is used
 
-// Exclusive scans of a[0..n) and b[0..n) in place, a[n] and b[n] = totals (b may be null).  All threads call it.
-// A thread sums a run of consecutive elements, the threads' sums are scanned (shuffles inside a wave, the waves'
-// totals through tmp), and each thread writes its run back: three barriers whatever n is.
-__device__ void block_scan(int32_t *a, int32_t *b, int n, int32_t *tmp /*[34], LDS*/)
+// Exclusive scans of a[0..n) and b[0..n) in place, a[n] and b[n] = totals (b may be null).  All THREADS threads of the
+// workgroup call it.  A thread sums a run of consecutive elements, the threads' sums are scanned (shuffles inside a
+// wave, the waves' totals through tmp), and each thread writes its run back: three barriers whatever n is.
+template <int THREADS> __device__ __forceinline__ void block_scan(int32_t *a, int32_t *b, int n, int32_t *tmp /*[34], LDS*/, int tid)
 {
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int per = (n + kPlanThreads - 1) / kPlanThreads;
+    const int lane = tid & 63, wv = tid >> 6;
+    const int per = (n + THREADS - 1) / THREADS;
     const int i0 = tid * per < n ? tid * per : n, i1 = i0 + per < n ? i0 + per : n;
     int sa = 0, sb = 0;
+#pragma unroll 1
     for (int i = i0; i < i1; i++) {
         sa += a[i];
         if (b) sb += b[i];
@@ -117,18 +118,19 @@ __device__ void block_scan(int32_t *a, int32_t *b, int n, int32_t *tmp /*[34], L
     if (lane == 63) tmp[wv] = xa, tmp[17 + wv] = xb;
     __syncthreads();
     if (wv == 0) {
-        const int ta = lane < kPlanThreads / 64 ? tmp[lane] : 0, tb = lane < kPlanThreads / 64 ? tmp[17 + lane] : 0;
+        const int ta = lane < THREADS / 64 ? tmp[lane] : 0, tb = lane < THREADS / 64 ? tmp[17 + lane] : 0;
         int ua = ta, ub = tb;
 #pragma unroll
         for (int d = 1; d < 16; d <<= 1) {
             const int ya = __shfl_up(ua, d), yb = __shfl_up(ub, d);
             if (lane >= d) ua += ya, ub += yb;
         }
-        if (lane < kPlanThreads / 64) tmp[lane] = ua - ta, tmp[17 + lane] = ub - tb;
-        if (lane == kPlanThreads / 64 - 1) tmp[16] = ua, tmp[33] = ub;
+        if (lane < THREADS / 64) tmp[lane] = ua - ta, tmp[17 + lane] = ub - tb;
+        if (lane == THREADS / 64 - 1) tmp[16] = ua, tmp[33] = ub;
     }
     __syncthreads();
     int ea = tmp[wv] + xa - sa, eb = tmp[17 + wv] + xb - sb; // what precedes this thread's run
+#pragma unroll 1
     for (int i = i0; i < i1; i++) {
         const int va = a[i];
         a[i] = ea;
@@ -148,15 +150,19 @@ __device__ void block_scan(int32_t *a, int32_t *b, int n, int32_t *tmp /*[34], L
 
 // Where the cost stream is cut: into one span per resident wave.  Workgroups are dealt round-robin to the eight
 // accelerator dies, which do not all get the same share of the memory bandwidth, so within each block of eight
-// consecutive spans (8*S0 units) span x gets a share proportional to the relative speed xcd_w[x] of its die (the
-// weights add up to 8192).
+// consecutive spans (8*S0 units) span x gets a share proportional to the weight xcd_w[x] of its die (the weights add
+// up to 8192; equal unless set otherwise).
 struct Cuts {
     int U, S0; // the stream has fewer than 2^31 units (checked on the host); divisions stay 32 bits wide
     int waves;
     int acc[9]; // running sums of the die weights
     __device__ int lo(int c) const
     {
-        const long v = (long)(c >> 3) * 8 * S0 + ((8L * S0 * acc[c & 7]) >> 13);
+        int w = 0; // acc[c & 7], without indexing (the table then stays in registers)
+#pragma unroll
+        for (int i = 1; i < 8; i++)
+            if ((c & 7) == i) w = acc[i];
+        const long v = (long)(c >> 3) * 8 * S0 + ((8L * S0 * w) >> 13);
         return v < U ? (int)v : U;
     }
     __device__ int span_of(int pos) const // the span that holds cost unit pos < U
@@ -171,43 +177,51 @@ struct Cuts {
     }
 };
 
-// LDS of the rows phase (inputs and intermediates of batches of up to kPlanCap sequences and groups).
-struct RowsLds {
-    int32_t scan_tmp[34];
-    int32_t len[kPlanCap], grp[kPlanCap], poff[kPlanCap + 1];
-    int32_t grp_count[kPlanCap], grp_rowbase[kPlanCap + 1], grp_membase[kPlanCap + 1];
-    int32_t seq_rank[kPlanCap], row_start[2 * kPlanCap + 1];
+// Buffers of the rows phase: the staged inputs, the groups' and sequences' intermediates, the scanned row costs and
+// the row table.  They live in LDS when the batch fits (the usual case), else in the workspace.
+struct RowsBuf {
+    int32_t *scan_tmp;                                // [34], LDS
+    int32_t *len, *grp, *poff;                        // LDS copies of the inputs to fill, or null: read the inputs in place
+    int32_t *grp_count, *grp_rowbase, *grp_membase;   // [NG], [NG + 1], [NG + 1]
+    int32_t *seq_rank;                                // [B]  rank in the group, later the sequence's prefix row
+    int32_t *row_start;                               // [rows + 1]
+    int4 *tab;                                        // [rows]
+    int32_t *members;                                 // [B]  sequences ordered by prefix row, or null
+    int32_t *seq_pfx_row, *seq_rank_in_row;           // [B]  for the merge kernel, or null
 };
 
-// The rows phase: membership, the rows with their costs (scanned in place in row_start), the row table.  Returns
-// the number of rows and of shared-prefix rows among them.  `small` keeps everything in LDS (L), else the
-// intermediates live in the workspace.  Everything here is a function of the inputs alone and comes out the same in
-// every workgroup that runs this; one of them publishes what the other kernels read (publish: the members' list and
-// each sequence's prefix row and place in it).  tab: where the row table goes (LDS or the workspace).
-__device__ __forceinline__ void rows_phase(const Launch &a, RowsLds &L, bool small, bool publish, int4 *tab, int32_t *&row_start_out,
-                                           int &nR_out, int &nPR_out)
+__host__ __device__ inline int rows_most(int B, int NG, int mpr) // upper bound on work rows
 {
-    const int tid = threadIdx.x;
-    const Workspace &w = a.ws;
+    const int pr = NG > 0 ? (NG + B / mpr < B ? NG + B / mpr : B) : 0;
+    return B + pr;
+}
+// The rows phase: membership, the rows with their costs (scanned in place in row_start), the row table.  Returns
+// the number of rows and of shared-prefix rows among them.  Everything here is a function of the inputs alone and
+// comes out the same in every workgroup (of THREADS threads) that runs this.
+template <int THREADS>
+__device__ __forceinline__ void rows_phase(const Launch &a, const RowsBuf &R, int &nR_out, int &nPR_out, int tid /* = threadIdx.x */)
+{
     const int B = a.B;
     const int NG = a.share ? a.num_groups : 0;
     const int MPR = a.members_per_row;
-    int32_t *grp_count = small ? L.grp_count : w.grp_count;
-    int32_t *grp_rowbase = small ? L.grp_rowbase : w.grp_rowbase;
-    int32_t *grp_membase = small ? L.grp_membase : w.grp_membase;
-    int32_t *seq_rank = small ? L.seq_rank : w.seq_rank;
-    int32_t *row_start = small ? L.row_start : w.row_start;
+    const int rMPR = ((1 << 20) + MPR - 1) / MPR; // (x * rMPR) >> 20 == x / MPR for x < 2^14
+    int32_t *grp_count = R.grp_count, *grp_rowbase = R.grp_rowbase, *grp_membase = R.grp_membase;
+    int32_t *seq_rank = R.seq_rank, *row_start = R.row_start;
+    int4 *tab = R.tab;
     const int32_t *len_src = a.seq_lens, *grp_src = a.seq_group, *poff = a.pfx_off;
     // one trip to memory for everything the schedule depends on
-    if (small) {
-        for (int b = tid; b < B; b += kPlanThreads) {
-            L.len[b] = a.seq_lens[b];
-            L.grp[b] = NG ? a.seq_group[b] : -1;
+    if (R.len) {
+#pragma unroll 1
+        for (int b = tid; b < B; b += THREADS) {
+            R.len[b] = a.seq_lens[b];
+            R.grp[b] = NG ? a.seq_group[b] : -1;
         }
-        for (int g = tid; g <= NG; g += kPlanThreads) L.poff[g] = NG ? a.pfx_off[g] : 0;
-        len_src = L.len, grp_src = L.grp, poff = L.poff;
+#pragma unroll 1
+        for (int g = tid; g <= NG; g += THREADS) R.poff[g] = NG ? a.pfx_off[g] : 0;
+        len_src = R.len, grp_src = R.grp, poff = R.poff;
     }
-    for (int g = tid; g < NG; g += kPlanThreads) grp_count[g] = 0;
+#pragma unroll 1
+    for (int g = tid; g < NG; g += THREADS) grp_count[g] = 0;
     __syncthreads();
     auto len_of = [&](int b) { // never walk past the table row
         const int Lb = len_src[b];
@@ -222,7 +236,8 @@ __device__ __forceinline__ void rows_phase(const Launch &a, RowsLds &L, bool sma
     // decides which shared-prefix row the member joins and with it the partials its result is merged from: sequences
     // are taken in ascending blocks, a lane finds its place among the lanes of its wave with the same group by
     // ballots, and the waves add their counts to the group's total one after the other.
-    for (int base = 0; base < B; base += kPlanThreads) {
+#pragma unroll 1
+    for (int base = 0; base < B; base += THREADS) {
         const int b = base + tid, lane = tid & 63, wv = tid >> 6;
         int g = -1;
         if (b < B) {
@@ -234,6 +249,7 @@ __device__ __forceinline__ void rows_phase(const Launch &a, RowsLds &L, bool sma
         }
         int pos = 0, cnt = 0;
         unsigned long long todo = __ballot(g >= 0);
+#pragma unroll 1
         while (todo) {
             const int gl = __shfl(g, __ffsll((long long)todo) - 1);
             const unsigned long long same = __ballot(g == gl);
@@ -244,7 +260,8 @@ __device__ __forceinline__ void rows_phase(const Launch &a, RowsLds &L, bool sma
             todo &= ~same;
         }
         int rank = -1;
-        for (int w = 0; w < kPlanThreads / 64; w++) {
+#pragma unroll 1
+        for (int w = 0; w < THREADS / 64; w++) {
             if (wv == w && g >= 0) {
                 const int before = grp_count[g]; // the same for all lanes of the group: read by all, then written by one
                 rank = before + pos;
@@ -257,39 +274,45 @@ __device__ __forceinline__ void rows_phase(const Launch &a, RowsLds &L, bool sma
     }
     int nPR = 0;
     if (NG) {
-        for (int g = tid; g < NG; g += kPlanThreads) {
+#pragma unroll 1
+        for (int g = tid; g < NG; g += THREADS) {
             grp_membase[g] = grp_count[g];
-            grp_rowbase[g] = (grp_count[g] + MPR - 1) / MPR;
+            grp_rowbase[g] = ((grp_count[g] + MPR - 1) * rMPR) >> 20;
         }
         __syncthreads();
-        block_scan(grp_membase, grp_rowbase, NG, L.scan_tmp);
+        block_scan<THREADS>(grp_membase, grp_rowbase, NG, R.scan_tmp, tid);
         nPR = grp_rowbase[NG];
     }
     // Rows and their cost per kv head (staged in row_start, scanned in place): an item of n > 0 pages costs
     // cost_item + weight*n.  The fixed part stands for what every segment costs a wave on top of its pages
     // (query rows, a partial result, a pipeline that restarts).
-    for (int g = tid; g < NG; g += kPlanThreads) {
+#pragma unroll 1
+    for (int g = tid; g < NG; g += THREADS) {
         const int cnt = grp_count[g], np = poff[g + 1] - poff[g];
         const int r0 = grp_rowbase[g];
+#pragma unroll 1
         for (int k = 0; k * MPR < cnt; k++) {
             const int left = cnt - k * MPR;
             row_start[r0 + k] = a.cost_item + np * a.cost_prefix;
             tab[r0 + k] = make_int4(poff[g], grp_membase[g] + k * MPR, left < MPR ? left : MPR, np);
         }
     }
-    for (int b = tid; b < B; b += kPlanThreads) {
+#pragma unroll 1
+    for (int b = tid; b < B; b += THREADS) {
         const int Lb = len_of(b);
         const int rank = seq_rank[b];
-        int skip = 0, prow = -1;
+        int skip = 0, prow = -1, in_row = -1;
         if (rank >= 0) {
             const int g = grp_of(b);
+            const int k = (rank * rMPR) >> 20; // rank / MPR
             skip = poff[g + 1] - poff[g];
-            prow = grp_rowbase[g] + rank / MPR;
-            if (publish) w.members[grp_membase[g] + rank] = b;
+            prow = grp_rowbase[g] + k;
+            in_row = rank - k * MPR;
+            if (R.members) R.members[grp_membase[g] + rank] = b;
         }
-        if (publish) {
-            w.seq_pfx_row[b] = prow;
-            w.seq_rank_in_row[b] = rank >= 0 ? rank % MPR : -1;
+        if (R.seq_pfx_row) {
+            R.seq_pfx_row[b] = prow;
+            R.seq_rank_in_row[b] = in_row;
         }
         seq_rank[b] = prow; // from here on: the sequence's prefix row
         const int pages = Lb > 0 ? (Lb + kPage - 1) / kPage - skip : 0;
@@ -298,10 +321,36 @@ __device__ __forceinline__ void rows_phase(const Launch &a, RowsLds &L, bool sma
     }
     __syncthreads();
     const int nR = B + nPR;
-    block_scan(row_start, nullptr, nR, L.scan_tmp);
-    row_start_out = row_start;
+    block_scan<THREADS>(row_start, nullptr, nR, R.scan_tmp, tid);
     nR_out = nR;
     nPR_out = nPR;
+}
+
+// LDS of the schedule kernels' rows phase (batches of up to kPlanCap sequences and groups).
+struct RowsLds {
+    int32_t scan_tmp[36];
+    int32_t len[kPlanCap], grp[kPlanCap], poff[kPlanCap + 1];
+    int32_t grp_count[kPlanCap], grp_rowbase[kPlanCap + 1], grp_membase[kPlanCap + 1];
+    int32_t seq_rank[kPlanCap], row_start[2 * kPlanCap + 1];
+};
+// The buffers of a schedule kernel: in LDS (L and tab) when the batch fits, else in the workspace; `publish` adds what
+// the other kernels read (the members' list, each sequence's prefix row and place in it).
+__device__ __forceinline__ void plan_rows_buf(RowsBuf &R, const Launch &a, RowsLds &L, bool small, int4 *tab, bool publish)
+{
+    const Workspace &w = a.ws;
+    R.scan_tmp = L.scan_tmp;
+    R.len = small ? L.len : nullptr;
+    R.grp = small ? L.grp : nullptr;
+    R.poff = small ? L.poff : nullptr;
+    R.grp_count = small ? L.grp_count : w.grp_count;
+    R.grp_rowbase = small ? L.grp_rowbase : w.grp_rowbase;
+    R.grp_membase = small ? L.grp_membase : w.grp_membase;
+    R.seq_rank = small ? L.seq_rank : w.seq_rank;
+    R.row_start = small ? L.row_start : w.row_start;
+    R.tab = tab;
+    R.members = publish ? w.members : nullptr;
+    R.seq_pfx_row = publish ? w.seq_pfx_row : nullptr;
+    R.seq_rank_in_row = publish ? w.seq_rank_in_row : nullptr;
 }
 
 __global__ __launch_bounds__(kPlanThreads) void plan_rows_kernel(Launch a)
@@ -312,14 +361,15 @@ __global__ __launch_bounds__(kPlanThreads) void plan_rows_kernel(Launch a)
     const Workspace &w = a.ws;
     // inputs and intermediates live in LDS when they fit (the usual case), else in the workspace
     const bool small = a.B <= kPlanCap && (a.share ? a.num_groups : 0) <= kPlanCap;
-    int32_t *row_start;
+    RowsBuf R;
+    plan_rows_buf(R, a, L, small, w.row_tab, true);
     int nR, nPR;
-    rows_phase(a, L, small, true, w.row_tab, row_start, nR, nPR);
+    rows_phase<kPlanThreads>(a, R, nR, nPR, tid);
 
     // hand over to the second kernel: the scanned row costs and the counts
-    for (int r = tid; r <= nR; r += kPlanThreads) w.row_start[r] = row_start[r];
+    for (int r = tid; r <= nR; r += kPlanThreads) w.row_start[r] = R.row_start[r];
     if (tid == 0) {
-        w.hdr[0] = a.Hkv * row_start[nR];
+        w.hdr[0] = a.Hkv * R.row_start[nR];
         w.hdr[2] = nR;
         w.hdr[3] = nPR;
     }
@@ -472,9 +522,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_fused_kernel(Launch a)
     __shared__ int4 l_row_tab[2 * kPlanCap];
     const int tid = threadIdx.x;
     const Workspace &w = a.ws;
-    int32_t *row_start;
+    RowsBuf R;
+    plan_rows_buf(R, a, L, true, l_row_tab, blockIdx.x == 0);
     int nR, nPR;
-    rows_phase(a, L, true, blockIdx.x == 0, l_row_tab, row_start, nR, nPR);
+    rows_phase<kPlanThreads>(a, R, nR, nPR, tid);
+    const int32_t *row_start = R.row_start;
     Cuts cut;
     make_cuts(a, a.Hkv * row_start[nR], cut);
     if (blockIdx.x == 0) {
@@ -530,7 +582,6 @@ struct Segment {
 struct Ring {
     int issued; // entries whose loads have been issued
     int waited; // entries whose loads have been waited for (and consumed)
-    int qslot;  // the query slot of the current segment; alternates with every segment
 };
 
 // 16-row query tiles that a shared-prefix work row carries: four for bf16 pools (64 rows fill a ring entry of two
@@ -543,8 +594,11 @@ int prefix_rows(int kv_fp8) { return 16 * (kv_fp8 ? PrefixTiles<1>::value : Pref
 template <int D, int KVB, int NST> struct LdsMap {
     using G = Geo<D, KVB>;
     static constexpr int kQTile = kPage * D * 2;   // 16 query rows of bf16
-    static constexpr int kQBase = NST * G::kStage; // two query slots follow the ring
-    static constexpr int kBytes = NST * G::kStage + 2 * kQTile;
+    static constexpr int kQBase = NST * G::kStage;    // the query slot follows the ring
+    static constexpr int kPlanBase = kQBase + kQTile; // then the work list of a wave that plans its span itself;
+    static constexpr int kPlanBytes = kQTile;         // everything before it is free while the wave plans
+    static constexpr int kRecCap = kPlanBytes / 32;   // records the work list holds
+    static constexpr int kBytes = kPlanBase + kPlanBytes;
     static_assert(PrefixTiles<KVB>::value * kQTile <= G::kStage, "the query rows of a shared-prefix row fill one ring entry");
     static_assert(PrefixTiles<KVB>::value * (D * 2 / 64) <= G::kDmaPerStage, "... with no more loads than two pages take");
 };
@@ -571,10 +625,9 @@ template <int D> __device__ __forceinline__ void store_pending(const Launch &a, 
 // Loads of one stage (two pages: K0 K1 V0 V1, and for e4m3 the four scales) of a segment into a ring slot.
 template <int D, int KVB, int NST>
 __device__ __forceinline__ void issue_stage(const Launch &a, const LaneConst<D, KVB> &lc, const Segment &sg, int st, int pid0,
-                                            int pid1, int ring_slot, uint32_t lds_addr)
+                                            int pid1, int ring_slot, uint32_t lds_addr, int lane)
 {
     using G = Geo<D, KVB>;
-    const int lane = threadIdx.x;
     const int p0 = sg.pg_lo + 2 * st;
     int nv0 = sg.limit - p0 * kPage, nv1 = nv0 - kPage;
     nv0 = nv0 > kPage ? kPage : nv0;
@@ -598,11 +651,11 @@ __device__ __forceinline__ void issue_stage(const Launch &a, const LaneConst<D, 
 // Query rows of an own-pages segment: the G heads of (b, kvh) are contiguous in q; rows G..15 read zeros.
 template <int D, int KVB, int NST>
 __device__ __forceinline__ void issue_q(const Launch &a, const uint16_t *__restrict__ q, const LaneConst<D, KVB> &lc,
-                                        const Segment &sg, int qslot, uint32_t lds_addr)
+                                        const Segment &sg, uint32_t lds_addr)
 {
     using M = LdsMap<D, KVB, NST>;
     const uint8_t *src = (const uint8_t *)(q + ((int64_t)sg.b * a.Hq + (int64_t)sg.kvh * a.G) * D);
-    const uint32_t dst = lds_addr + M::kQBase + qslot * M::kQTile;
+    const uint32_t dst = lds_addr + M::kQBase;
 #pragma unroll
     for (int n = 0; n < D * 2 / 64; n++) {
         const void *p = lc.q_row[n] < a.G ? (const void *)(src + lc.q_off[n]) : a.zeros;
@@ -656,19 +709,19 @@ __device__ __forceinline__ void issue_qrows(const Launch &a, const uint16_t *__r
 // The ring does not run dry at a segment boundary: while the last entries of this segment are consumed, the
 // first entries (and the query rows) of the next one are already being loaded.  On entry, the first
 // min(NST-1, entries) entries of this segment are in flight; on exit the same holds for `nxt`.  Query rows of an
-// own-pages segment (NQT == 1) wait in a query slot; those of a shared-pages segment are its first ring entry.
+// own-pages segment (NQT == 1) wait in the query slot; those of a shared-pages segment are its first ring entry.
 // A one-tile partial goes back in `ret` (normalised, with its log2-sum-exp); a shared-prefix partial is stored.
 template <int D, int KVB, int NQT, int NST>
 __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__restrict__ q, const Segment &cur, bool has_nxt,
                                             const Segment &nxt, Ring &ring, const LaneConst<D, KVB> &lc, uint8_t *lds,
-                                            uint32_t lds_addr, Pending<D> &ret)
+                                            uint32_t lds_addr, Pending<D> &ret, int lane)
 {
     using G = Geo<D, KVB>;
     using M = LdsMap<D, KVB, NST>;
     static_assert((NST - 1) * G::kDmaPerStage < 64, "the vector-memory counter holds 6 bits");
     static_assert(NQT == 1 || NQT == PrefixTiles<KVB>::value, "one tile, or a shared-prefix row");
     constexpr int QL = NQT > 1 ? 1 : 0; // this segment's first ring entry carries its query rows
-    const int lane = threadIdx.x, j = lane >> 4;
+    const int j = lane >> 4;
     const int niter = cur.stages() + QL;
     const int base = ring.waited; // ring number of this segment's first entry
     int nxt_pre = 0, nxt_ql = 0;
@@ -716,19 +769,26 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
         while (ring.issued - base < want) {
             const int rel = ring.issued - base;
             if (rel < niter) {
-                issue_stage<D, KVB, NST>(a, lc, cur, rel - QL, nid0, nid1, ring.issued % NST, lds_addr);
+                issue_stage<D, KVB, NST>(a, lc, cur, rel - QL, nid0, nid1, ring.issued % NST, lds_addr, lane);
             } else if (rel == niter && nxt_ql) {
                 issue_qrows<D, KVB, NST>(a, q, lc, nxt, ring.issued % NST, lds_addr);
             } else {
-                if (rel == niter) issue_q<D, KVB, NST>(a, q, lc, nxt, ring.qslot ^ 1, lds_addr);
-                issue_stage<D, KVB, NST>(a, lc, nxt, rel - niter - nxt_ql, nid0, nid1, ring.issued % NST, lds_addr);
+                if (rel == niter) issue_q<D, KVB, NST>(a, q, lc, nxt, lds_addr);
+                issue_stage<D, KVB, NST>(a, lc, nxt, rel - niter - nxt_ql, nid0, nid1, ring.issued % NST, lds_addr, lane);
             }
             ring.issued++;
             nid0 = page_id(ring.issued - base, 0);
             nid1 = page_id(ring.issued - base, 1);
         }
     };
-    if (QL) {
+    if (!QL) {
+        // The query rows were loaded into the query slot ahead of this segment's first entries; fetch them before
+        // anything else is issued, because the next segment's may be (there is one slot).
+        WaitTail<NST - 1, G::kDmaPerStage>::run(ring.issued - base);
+#pragma unroll
+        for (int i = 0; i < G::kKSteps; i++) qf[0][i] = *(const bf16x8 *)(lds + M::kQBase + lc.kq_off[i]);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    } else {
         // the first ring entry holds the query rows
         issue_ahead(0);
         WaitTail<NST - 1, G::kDmaPerStage>::run(ring.issued - base - 1);
@@ -749,12 +809,6 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
         WaitTail<NST - 1, G::kDmaPerStage>::run(ring.issued - base - 1 - it);
         const int rslot = (base + it) % NST;
         const uint8_t *st = lds + rslot * G::kStage;
-        if (!QL && it == 0) {
-            // the query rows were loaded into the query slot ahead of this segment's first stage, so they have landed too
-#pragma unroll
-            for (int i = 0; i < G::kKSteps; i++)
-                qf[0][i] = *(const bf16x8 *)(lds + M::kQBase + ring.qslot * M::kQTile + lc.kq_off[i]);
-        }
         const int pg0 = cur.pg_lo + 2 * (it - QL); // first page of this stage
 
         // scores of the 2 x 16 keys of this stage
@@ -857,7 +911,6 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         ring.waited++;
     }
-    ring.qslot ^= 1; // the next segment's query rows, if it keeps them in a query slot, went to the other one
 
 #pragma unroll
     for (int t = 0; t < NQT; t++) {
@@ -880,6 +933,272 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
     }
 }
 
+// ------------------------------------------------------------------------------------------------------
+// A wave that plans its own span (no schedule kernel).
+//
+// For batches whose tables fit beside the ring, the schedule kernels are not launched: every attention wave works
+// the rows out for itself in the LDS it will stream through afterwards (they are a function of the lengths and the
+// groups alone, so all waves get the same rows), cuts the stream, and lists the segments of its own span in the
+// work-list area of its LDS.  If the list fills up, the wave streams what it has listed, drains, and plans again
+// from where it stopped.  What the merge kernel needs to find an item's partials (the first and the last span that
+// hold own pages of it, and the same for its prefix row, with the row and the sequence's place in it) is written by
+// the waves that hold those pieces, while they plan.
+// ------------------------------------------------------------------------------------------------------
+
+struct SpanPlan {
+    int nR, nPR; // work rows, of which shared-prefix rows
+    int lo, hi;  // the span's cost units
+    int r, kvh;  // the first item not yet listed
+    bool done;
+};
+
+__device__ __forceinline__ int ufl(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
+// Tables of a wave that plans for itself (LDS, in the ring's space while it is idle).  Leaner than the schedule
+// kernels' rows phase: a wave needs the rows' costs to find its span, and the members of a prefix row only if the row
+// has pages in its span, so no rank is worked out for the other groups.
+struct WaveTables {
+    int32_t *len;    // [B]      clamped lengths
+    int32_t *grp;    // [B]      the group whose shared pass the sequence uses, or -1
+    int32_t *poff;   // [NG + 1]
+    int32_t *gcnt;   // [NG + 1] members per group
+    int32_t *rowgrp; // [prefix rows]  group | row's number in its group << 16
+    int32_t *rs;     // [rows + 1]     first cost unit of every row (per kv head)
+};
+constexpr int kSelfPerLane = 8; // sequences (and groups) a lane takes: batches of up to 512 sequences and 511 groups
+__host__ __device__ inline size_t wave_tables_bytes(int B, int NG, int mpr)
+{
+    const size_t rows = (size_t)rows_most(B, NG, mpr);
+    return 4 * (2 * (size_t)B + 2 * ((size_t)NG + 1) + (rows - B + 1) + rows + 1 + 8);
+}
+__device__ __forceinline__ void carve_wave_tables(WaveTables &T, void *base, int B, int NG, int mpr)
+{
+    const int rows = rows_most(B, NG, mpr);
+    int32_t *p = (int32_t *)base;
+    auto take = [&](int n) {
+        int32_t *r = p;
+        p += n;
+        return r;
+    };
+    T.len = take(B);
+    T.grp = take(B);
+    T.poff = take(NG + 1);
+    T.gcnt = take(NG + 1);
+    T.rowgrp = take(rows - B + 1);
+    T.rs = take(rows + 1);
+}
+
+// Exclusive scan of x over the 64 lanes; total: the sum.
+__device__ __forceinline__ int wave_scan(int x, int lane, int &total)
+{
+    int v = x;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int y = __shfl_up(v, d);
+        if (lane >= d) v += y;
+    }
+    total = __builtin_amdgcn_readlane(v, 63);
+    return v - x;
+}
+
+// The rows and where they start in the cost stream, by one wave for itself (see rows_phase for what a row is and
+// costs).  A lane takes runs of consecutive sequences and of consecutive groups and keeps them in registers; the
+// tables in LDS are what the listing below looks up.
+__device__ __forceinline__ void wave_rows(const Launch &a, const WaveTables &T, int &nR_out, int &nPR_out, int lane)
+{
+    constexpr int N = kSelfPerLane;
+    const int B = a.B;
+    const int NG = a.share ? a.num_groups : 0;
+    const int MPR = a.members_per_row;
+    const int rMPR = ((1 << 20) + MPR - 1) / MPR; // (x * rMPR) >> 20 == x / MPR for x < 2^14
+    const int KB = (B + 63) >> 6, KG = (NG + 64) >> 6; // per lane: sequences, entries of the groups' offsets
+    // one trip to memory for everything the schedule depends on
+    int L[N], g[N], po[N];
+#pragma unroll
+    for (int k = 0; k < N; k++) {
+        const int b = lane * KB + k, gl = lane * KG + k;
+        L[k] = 0, g[k] = -1, po[k] = 0;
+        if (k < KB && b < B) {
+            L[k] = a.seq_lens[b];
+            if (NG) g[k] = a.seq_group[b];
+        }
+        if (NG && k < KG && gl <= NG) po[k] = a.pfx_off[gl];
+    }
+#pragma unroll
+    for (int k = 0; k < N; k++) {
+        const int gl = lane * KG + k;
+        if (k < KG && gl <= NG) {
+            T.poff[gl] = po[k];
+            T.gcnt[gl] = 0;
+        }
+    }
+    __syncthreads();
+    // membership: a sequence uses the shared pass when its group has shared pages and it holds all of them
+    int np[N];
+#pragma unroll
+    for (int k = 0; k < N; k++) {
+        const int b = lane * KB + k;
+        np[k] = 0;
+        if (k < KB && b < B) {
+            L[k] = L[k] < 0 ? 0 : (L[k] > a.max_pages * kPage ? a.max_pages * kPage : L[k]); // never walk past the table row
+            if (g[k] < 0 || g[k] >= NG) g[k] = -1;
+            if (g[k] >= 0) {
+                np[k] = T.poff[g[k] + 1] - T.poff[g[k]];
+                if (np[k] > 0 && L[k] >= np[k] * kPage) atomicAdd(&T.gcnt[g[k]], 1);
+                else g[k] = -1, np[k] = 0;
+            }
+            T.len[b] = L[k];
+            T.grp[b] = g[k];
+        }
+    }
+    __syncthreads();
+    // prefix rows: ceil(members / MPR) per group, all of a group's rows cost the same
+    int rows_l = 0, cost_l = 0, rows_g[N], cost_g[N];
+#pragma unroll
+    for (int k = 0; k < N; k++) {
+        const int gl = lane * KG + k;
+        rows_g[k] = 0, cost_g[k] = 0;
+        if (k < KG && gl < NG) {
+            rows_g[k] = ((T.gcnt[gl] + MPR - 1) * rMPR) >> 20;
+            cost_g[k] = a.cost_item + (T.poff[gl + 1] - T.poff[gl]) * a.cost_prefix;
+            rows_l += rows_g[k];
+            cost_l += rows_g[k] * cost_g[k];
+        }
+    }
+    int nPR, P;
+    int row = wave_scan(rows_l, lane, nPR), at = wave_scan(cost_l, lane, P);
+#pragma unroll
+    for (int k = 0; k < N; k++) {
+#pragma unroll 1
+        for (int j = 0; j < rows_g[k]; j++) {
+            T.rs[row] = at;
+            T.rowgrp[row] = (lane * KG + k) | (j << 16);
+            row++;
+            at += cost_g[k];
+        }
+    }
+    // sequence rows: an item of n > 0 pages costs cost_item + weight*n (see rows_phase)
+    int cost[N], c_l = 0;
+#pragma unroll
+    for (int k = 0; k < N; k++) {
+        const int pages = L[k] > 0 ? (L[k] + kPage - 1) / kPage - np[k] : 0;
+        cost[k] = pages > 0 ? a.cost_item + pages * kCostSuffix : 0;
+        c_l += cost[k];
+    }
+    int S;
+    at = P + wave_scan(c_l, lane, S);
+#pragma unroll
+    for (int k = 0; k < N; k++) {
+        const int b = lane * KB + k;
+        if (k < KB && b < B) T.rs[nPR + b] = at;
+        at += cost[k];
+    }
+    if (lane == 0) T.rs[nPR + B] = P + S;
+    __syncthreads();
+    nR_out = B + nPR;
+    nPR_out = nPR;
+}
+
+// Lists the segments of span c from item (sp.r, sp.kvh) on into recs (LDS): 8 ints per segment as in the schedule
+// kernels' work lists, except that a shared-pages segment carries its members' count in place of their offset and is
+// followed by its members' sequence numbers, 8 to a record (the members of a group in ascending order, MPR to a row).
+// Also writes, for the merge kernel, what the holder of an item's first or last piece knows: merge_desc's first and
+// last span, and for the members of a prefix row the row and their place in it.  Stops when cap records would be
+// exceeded (sp.done stays false).  Returns the number of records.  All lanes call it with the same arguments.
+__device__ __forceinline__ int list_segments(const Launch &a, const WaveTables &T, SpanPlan &sp, int c, int32_t *recs, int cap, int lane)
+{
+    int n = 0;
+    const int MPR = a.members_per_row;
+    int32_t *md = (int32_t *)a.ws.merge_desc; // per item: {pages, first span, last span, -} of own pages, then of shared pages
+#pragma unroll 1
+    while (sp.r < sp.nR) {
+        const int r = sp.r;
+        const int rs = a.Hkv * ufl(T.rs[r]);
+        if (rs >= sp.hi) break;
+        const int ic = ufl(T.rs[r + 1]) - ufl(T.rs[r]); // cost of one item of the row
+        if (ic == 0) {
+            sp.r++;
+            sp.kvh = 0;
+            continue;
+        }
+        const bool prefix = r < sp.nPR;
+        // prefix row: {index of the group's first page id, group, members, pages}; sequence row: {sequence, pages
+        // skipped, tokens after the skip, pages}
+        int4 info;
+        int grp_k = 0;
+        if (prefix) {
+            const int gk = ufl(T.rowgrp[r]), g = gk & 0xffff;
+            grp_k = gk >> 16;
+            const int left = ufl(T.gcnt[g]) - grp_k * MPR;
+            info = make_int4(ufl(T.poff[g]), g, left < MPR ? left : MPR, ufl(T.poff[g + 1]) - ufl(T.poff[g]));
+        } else {
+            const int b = r - sp.nPR, g = ufl(T.grp[b]), Lb = ufl(T.len[b]);
+            const int skip = g >= 0 ? ufl(T.poff[g + 1]) - ufl(T.poff[g]) : 0;
+            info = make_int4(b, skip, Lb - skip * kPage, (Lb + kPage - 1) / kPage - skip);
+        }
+        const int cw = prefix ? a.cost_prefix : kCostSuffix;
+        const int need = prefix ? 1 + ((info.z + 7) >> 3) : 1;
+        bool past = false;
+#pragma unroll 1
+        for (; sp.kvh < a.Hkv; sp.kvh++) {
+            const int kvh = sp.kvh;
+            const int S = rs + kvh * ic;
+            if (S >= sp.hi) {
+                past = true;
+                break;
+            }
+            int p_lo, p_hi;
+            span_pages(S + a.cost_item, cw, info.w, sp.lo, sp.hi, p_lo, p_hi);
+            if (p_lo >= p_hi) continue;
+            if (n + need > cap) return n;
+            int4 r0, r1;
+            if (!prefix) {
+                r0 = make_int4(info.x * a.max_pages + info.y, p_lo, p_hi, min(info.z, p_hi * kPage));
+                r1 = make_int4(kvh, info.x, a.G, info.x * a.Hkv + kvh + c);
+            } else {
+                r0 = make_int4(info.x, p_lo, p_hi, p_hi * kPage);
+                r1 = make_int4(kvh | (1 << 16), info.z, info.z * a.G, r * a.Hkv + kvh + c);
+            }
+            if (lane == 0) {
+                *(int4 *)(recs + 8 * n) = r0;
+                *(int4 *)(recs + 8 * n + 4) = r1;
+            }
+            if (!prefix) {
+                const int i = info.x * a.Hkv + kvh;
+                if (lane == 0 && p_lo == 0) md[8 * i + 1] = c;
+                if (lane == 0 && p_hi == info.w) md[8 * i + 2] = c;
+            } else {
+                // the row's members: numbers grp_k*MPR .. of the group's members in ascending order of sequence
+                int before = 0;
+#pragma unroll 1
+                for (int b0 = 0; b0 < a.B; b0 += 64) {
+                    const int b = b0 + lane;
+                    const bool is = b < a.B && T.grp[b] == info.y;
+                    const unsigned long long m = __ballot(is);
+                    const int place = before + __popcll(m & ((1ull << lane) - 1ull)) - grp_k * MPR;
+                    if (is && place >= 0 && place < info.z) {
+                        recs[8 * (n + 1) + place] = b;
+                        const int i = b * a.Hkv + kvh;
+                        if (p_lo == 0) {
+                            md[8 * i + 5] = c;
+                            a.ws.seq_pfx_row[b] = r; // (the same from every kv head)
+                            a.ws.seq_rank_in_row[b] = place;
+                        }
+                        if (p_hi == info.w) md[8 * i + 6] = c;
+                    }
+                    before += __popcll(m);
+                }
+            }
+            n += need;
+        }
+        if (past) break;
+        sp.r++;
+        sp.kvh = 0;
+    }
+    sp.done = true;
+    return n;
+}
+
 // The read-only inputs and the schedule come in as separate restrict pointers so that the compiler can keep
 // every wave-uniform lookup on the scalar unit, away from the vector-memory counter that paces the LDS ring.
 #define RA_ATTN_PARAMS                                                                                                    \
@@ -887,39 +1206,52 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
         const int32_t *__restrict__ hdr, const uint32_t *__restrict__ seg_rec, const int32_t *__restrict__ members
 #define RA_ATTN_ARGS a, q, block_table, pfx_pages, hdr, seg_rec, members
 
-template <int D, int KVB, int NST, int NPEND> __device__ __forceinline__ void attention_body(RA_ATTN_PARAMS)
+// SELF: the wave plans its own span (see above); otherwise it reads the schedule kernels' work list.
+template <int D, int KVB, int NST, int NPEND, bool SELF> __device__ __forceinline__ void attention_body(RA_ATTN_PARAMS)
 {
+    using M = LdsMap<D, KVB, NST>;
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     const uint32_t lds_addr = (uint32_t)(uintptr_t)lds;
     const int lane = threadIdx.x;
+    const int c = blockIdx.x;
     touch_args(a);
-    const int nspans = uniform_load(hdr, 7);
-    if ((int)blockIdx.x >= nspans) return;
+    if (!SELF) {
+        const int nspans = uniform_load(hdr, 7);
+        if (c >= nspans) return;
+    }
 
     LaneConst<D, KVB> lc;
-    lane_setup<D, KVB>(lc, lane, a.stride_token_b);
-    Ring ring = {0, 0, 0};
+    if (!SELF) lane_setup<D, KVB>(lc, lane, a.stride_token_b);
+    Ring ring = {0, 0};
     Pending<D> pend[NPEND], fresh; // finished partials wait in registers for the end of the wave
     int npend = 0;
 
-    // ---- walker: yields this wave's segments in stream order ----
-    // A span's work list is a chain of chunks of eight 8-dword records (a header and up to seven segments).
-    // A chunk is one dword per lane, so it is held in one register and a field is a cross-lane read.
+    // ---- the work list: segments in stream order ----
+    // Schedule kernels' list: a chain of chunks of eight 8-dword records (a header and up to seven segments); a chunk
+    // is one dword per lane, so it is held in one register and a field is a cross-lane read.  Own list: records in LDS.
+    int32_t *recs = (int32_t *)(lds + M::kPlanBase);
     uint32_t chunk = 0;
     int wk_j = 0, wk_n = 0, wk_chain = -1;
     auto field = [&](int i) { return (int)__builtin_amdgcn_readlane(chunk, i); };
-    auto load_chunk = [&](int c) {
-        chunk = seg_rec[(int64_t)c * 64 + lane];
+    auto load_chunk = [&](int ch) {
+        chunk = seg_rec[(int64_t)ch * 64 + lane];
         wk_j = 0;
         wk_n = field(0);
         wk_chain = field(1);
     };
     auto advance = [&](Segment &out) -> bool {
-        while (wk_j == wk_n) {
-            if (wk_chain < 0) return false;
-            load_chunk(wk_chain);
+        int f;
+        if (SELF) {
+            if (wk_j >= wk_n) return false;
+            chunk = (uint32_t)recs[8 * wk_j + (lane & 7)];
+            f = 0;
+        } else {
+            while (wk_j == wk_n) {
+                if (wk_chain < 0) return false;
+                load_chunk(wk_chain);
+            }
+            f = 8 * (1 + wk_j++);
         }
-        const int f = 8 * (1 + wk_j++);
         const int where = field(f + 4);
         out.kvh = where & 0xffff;
         out.prefix = where >> 16;
@@ -932,7 +1264,12 @@ template <int D, int KVB, int NST, int NPEND> __device__ __forceinline__ void at
         out.nrows = field(f + 6);
         out.slot = field(f + 7);
         out.mvec = 0;
-        if (out.prefix) {
+        if (SELF) {
+            // the members follow the segment's record, one per lane
+            const int nmem = out.prefix ? out.moff : 0;
+            if (lane < nmem) out.mvec = (uint32_t)recs[8 * (wk_j + 1) + lane];
+            wk_j += 1 + ((nmem + 7) >> 3);
+        } else if (out.prefix) {
             // the work row's members, one per lane (scalar loads four at a time: the ring's loads are not waited for)
             const int nmem = (out.nrows * a.recip_g) >> 16;
             for (int i = 0; i < nmem; i += 4) {
@@ -947,87 +1284,162 @@ template <int D, int KVB, int NST, int NPEND> __device__ __forceinline__ void at
         return true;
     };
 
-    load_chunk(blockIdx.x);
-    Segment cur, nxt;
-    bool has_cur = advance(cur);
-    if (has_cur) {
-        // prime the ring with the first segment
-        if (!cur.prefix) issue_q<D, KVB, NST>(a, q, lc, cur, ring.qslot, lds_addr);
-        const int n = min(NST - 1, cur.entries());
-        for (int k = 0; k < n; k++) {
-            const int st = k - cur.prefix;
-            if (st < 0) {
-                issue_qrows<D, KVB, NST>(a, q, lc, cur, ring.issued % NST, lds_addr);
-            } else {
-                const int p = cur.pg_lo + 2 * st;
-                const int id0 = uniform_load(cur.pages, p), id1 = p + 1 < cur.pg_hi ? uniform_load(cur.pages, p + 1) : 0;
-                issue_stage<D, KVB, NST>(a, lc, cur, st, id0, id1, ring.issued % NST, lds_addr);
+    SpanPlan sp;
+    sp.done = !SELF;
+    bool first_pass = true;
+    do {
+        if (SELF) {
+            // plan: the rows, the cut, this span's list (the ring is idle: its LDS holds the tables meanwhile)
+            // (what is computed here is wanted here only: base and lane number are made opaque so that nothing derived
+            // from them is worked out ahead of the loop and kept in registers while the wave streams)
+            uint8_t *plan_base = lds;
+            int plan_lane = lane;
+            asm volatile("" : "+s"(plan_base), "+v"(plan_lane));
+            WaveTables T;
+            carve_wave_tables(T, plan_base, a.B, a.share ? a.num_groups : 0, a.members_per_row);
+            wave_rows(a, T, sp.nR, sp.nPR, plan_lane);
+            if (first_pass) {
+                Cuts cut;
+                make_cuts(a, a.Hkv * ufl(T.rs[sp.nR]), cut);
+                sp.lo = cut.lo(c), sp.hi = cut.lo(c + 1);
+                // the span's first item: the last row that starts at or before the span's first unit (starts do not decrease)
+                int at_or_before = 0;
+#pragma unroll 1
+                for (int r0 = 0; r0 < sp.nR; r0 += 64) {
+                    const int r = r0 + plan_lane;
+                    at_or_before += __popcll(__ballot(r < sp.nR && (long)a.Hkv * T.rs[r] <= sp.lo));
+                }
+                const int r = at_or_before > 0 ? at_or_before - 1 : 0;
+                const int rs = a.Hkv * ufl(T.rs[r]), ic = ufl(T.rs[r + 1]) - ufl(T.rs[r]);
+                sp.r = r;
+                sp.kvh = sp.lo > rs && ic > 0 ? (sp.lo - rs) / ic : 0;
+                if (sp.lo >= sp.hi) sp.r = sp.nR; // nothing for this wave
+                first_pass = false;
             }
-            ring.issued++;
-        }
-    }
-    while (has_cur) {
-        const bool has_nxt = advance(nxt);
-        if (!cur.prefix) {
-            run_segment<D, KVB, 1, NST>(a, q, cur, has_nxt, nxt, ring, lc, lds, lds_addr, fresh);
-            fresh.slot = cur.slot;
-            if (npend == NPEND) { // full: write the oldest out
-                store_pending<D>(a, pend[0], lane);
+            wk_n = list_segments(a, T, sp, c, (int32_t *)(plan_base + M::kPlanBase), M::kRecCap, plan_lane);
+            wk_j = 0;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // the tables have been read: the ring may overwrite them
+            // (nothing is kept across a planning pass, neither the lane constants nor a partial: say so, or their
+            // registers stay reserved while the wave plans)
+            int stream_lane = lane;
+            asm volatile("" : "+v"(stream_lane));
+            lane_setup<D, KVB>(lc, stream_lane, a.stride_token_b);
 #pragma unroll
-                for (int k = 1; k < NPEND; k++) pend[k - 1] = pend[k];
-                npend = NPEND - 1;
+            for (int k = 0; k < NPEND; k++) {
+#pragma unroll
+                for (int dt = 0; dt < D / 16; dt++) pend[k].o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+                pend[k].lse2 = 0.f;
+                pend[k].slot = 0;
             }
-#pragma unroll
-            for (int k = 0; k < NPEND; k++)
-                if (k == npend) pend[k] = fresh;
-            npend++;
         } else {
-            run_segment<D, KVB, PrefixTiles<KVB>::value, NST>(a, q, cur, has_nxt, nxt, ring, lc, lds, lds_addr, fresh);
+            load_chunk(c);
         }
-        cur = nxt;
-        has_cur = has_nxt;
-    }
+        // (the lane number of this pass, opaque in a wave that plans, so that nothing derived from it is prepared
+        // ahead of the planning pass and held in registers through it)
+        int ln = lane;
+        if (SELF) asm volatile("" : "+v"(ln));
+        Segment cur, nxt;
+        bool has_cur = advance(cur);
+        if (has_cur) {
+            // prime the ring with the first segment
+            if (!cur.prefix) issue_q<D, KVB, NST>(a, q, lc, cur, lds_addr);
+            const int n = min(NST - 1, cur.entries());
+            for (int k = 0; k < n; k++) {
+                const int st = k - cur.prefix;
+                if (st < 0) {
+                    issue_qrows<D, KVB, NST>(a, q, lc, cur, ring.issued % NST, lds_addr);
+                } else {
+                    const int p = cur.pg_lo + 2 * st;
+                    const int id0 = uniform_load(cur.pages, p), id1 = p + 1 < cur.pg_hi ? uniform_load(cur.pages, p + 1) : 0;
+                    issue_stage<D, KVB, NST>(a, lc, cur, st, id0, id1, ring.issued % NST, lds_addr, ln);
+                }
+                ring.issued++;
+            }
+        }
+        while (has_cur) {
+            const bool has_nxt = advance(nxt);
+            if (!cur.prefix) {
+                run_segment<D, KVB, 1, NST>(a, q, cur, has_nxt, nxt, ring, lc, lds, lds_addr, fresh, ln);
+                fresh.slot = cur.slot;
+                if (npend == NPEND) { // full: write the oldest out
+                    store_pending<D>(a, pend[0], ln);
 #pragma unroll
-    for (int k = 0; k < NPEND; k++)
-        if (k < npend) store_pending<D>(a, pend[k], lane);
+                    for (int k = 1; k < NPEND; k++) pend[k - 1] = pend[k];
+                    npend = NPEND - 1;
+                }
+#pragma unroll
+                for (int k = 0; k < NPEND; k++)
+                    if (k == npend) pend[k] = fresh;
+                npend++;
+            } else {
+                run_segment<D, KVB, PrefixTiles<KVB>::value, NST>(a, q, cur, has_nxt, nxt, ring, lc, lds, lds_addr, fresh, ln);
+            }
+            cur = nxt;
+            has_cur = has_nxt;
+        }
+#pragma unroll
+        for (int k = 0; k < NPEND; k++)
+            if (k < npend) store_pending<D>(a, pend[k], ln);
+        npend = 0;
+    } while (!sp.done);
 }
 
-// Ring depths (in stages of two pages).  bf16 KV: two stages (32 KB + 8 KB of query slots, four waves per
-// compute unit) or three.  e4m3 KV: pages are half the size: three stages, or two; these kernels keep one finished
-// partial in registers instead of three and are held to half the register file, so that two waves share a SIMD.
-template <int D> __global__ __launch_bounds__(64) void attention_kernel_s3(RA_ATTN_PARAMS)
+// Ring depths (in stages of two pages).  bf16 KV: two stages (32 KB, a 4 KB query slot and a 4 KB work list, four
+// waves per compute unit) or three.  e4m3 KV: pages are half the size: three stages, or two; these kernels keep one
+// finished partial in registers instead of three and are held to half the register file, so that two waves share a SIMD.
+template <int D, bool SELF> __global__ __launch_bounds__(64) void attention_kernel_s3(RA_ATTN_PARAMS)
 {
-    attention_body<D, 2, 3, 3>(RA_ATTN_ARGS);
+    attention_body<D, 2, 3, 3, SELF>(RA_ATTN_ARGS);
 }
-template <int D> __global__ __launch_bounds__(64) void attention_kernel_s2(RA_ATTN_PARAMS)
+template <int D, bool SELF> __global__ __launch_bounds__(64) void attention_kernel_s2(RA_ATTN_PARAMS)
 {
-    attention_body<D, 2, 2, 3>(RA_ATTN_ARGS);
+    attention_body<D, 2, 2, 3, SELF>(RA_ATTN_ARGS);
 }
-template <int D> __global__ __launch_bounds__(64, 2) void attention_kernel_fp8(RA_ATTN_PARAMS)
+template <int D, bool SELF> __global__ __launch_bounds__(64, 2) void attention_kernel_fp8(RA_ATTN_PARAMS)
 {
-    attention_body<D, 1, 3, 1>(RA_ATTN_ARGS);
+    attention_body<D, 1, 3, 1, SELF>(RA_ATTN_ARGS);
 }
-template <int D> __global__ __launch_bounds__(64, 2) void attention_kernel_fp8_s2(RA_ATTN_PARAMS)
+template <int D, bool SELF> __global__ __launch_bounds__(64, 2) void attention_kernel_fp8_s2(RA_ATTN_PARAMS)
 {
-    attention_body<D, 1, 2, 1>(RA_ATTN_ARGS);
+    attention_body<D, 1, 2, 1, SELF>(RA_ATTN_ARGS);
 }
 
+// Bytes of LDS the kernel for (head dim, pool type, ring depth) asks for, and how much of it a wave that plans its
+// own span has for its tables (everything before the work list).
+static void attention_lds(int D, int kv_fp8, int stages, size_t *bytes, size_t *plan_bytes)
+{
+#define RA_LDS(DD, KVB, NST) (*bytes = LdsMap<DD, KVB, NST>::kBytes, *plan_bytes = LdsMap<DD, KVB, NST>::kPlanBase)
+    if (kv_fp8) {
+        if (D == 128) stages == 2 ? RA_LDS(128, 1, 2) : RA_LDS(128, 1, 3);
+        else stages == 2 ? RA_LDS(64, 1, 2) : RA_LDS(64, 1, 3);
+    } else {
+        if (D == 128) stages == 2 ? RA_LDS(128, 2, 2) : RA_LDS(128, 2, 3);
+        else stages == 2 ? RA_LDS(64, 2, 2) : RA_LDS(64, 2, 3);
+    }
+#undef RA_LDS
+}
 static size_t attention_lds_bytes(int D, int kv_fp8, int stages)
 {
-    if (kv_fp8) {
-        if (D == 128) return stages == 2 ? LdsMap<128, 1, 2>::kBytes : LdsMap<128, 1, 3>::kBytes;
-        return stages == 2 ? LdsMap<64, 1, 2>::kBytes : LdsMap<64, 1, 3>::kBytes;
-    }
-    if (D == 128) return stages == 2 ? LdsMap<128, 2, 2>::kBytes : LdsMap<128, 2, 3>::kBytes;
-    return stages == 2 ? LdsMap<64, 2, 2>::kBytes : LdsMap<64, 2, 3>::kBytes;
+    size_t b, p;
+    attention_lds(D, kv_fp8, stages, &b, &p);
+    return b;
 }
 
-static const void *attention_fn(int D, int kv_fp8, int stages)
+bool can_self_plan(int D, int kv_fp8, int stages, int B, int num_groups, int members_per_row)
 {
-    if (kv_fp8 && stages == 2) return D == 128 ? (const void *)attention_kernel_fp8_s2<128> : (const void *)attention_kernel_fp8_s2<64>;
-    if (kv_fp8) return D == 128 ? (const void *)attention_kernel_fp8<128> : (const void *)attention_kernel_fp8<64>;
-    if (stages == 2) return D == 128 ? (const void *)attention_kernel_s2<128> : (const void *)attention_kernel_s2<64>;
-    return D == 128 ? (const void *)attention_kernel_s3<128> : (const void *)attention_kernel_s3<64>;
+    size_t b, p;
+    attention_lds(D, kv_fp8, stages, &b, &p);
+    return B <= 64 * kSelfPerLane && num_groups < 64 * kSelfPerLane && wave_tables_bytes(B, num_groups, members_per_row) <= p;
+}
+
+static const void *attention_fn(int D, int kv_fp8, int stages, bool self)
+{
+#define RA_FN(K) (self ? (D == 128 ? (const void *)K<128, true> : (const void *)K<64, true>) : (D == 128 ? (const void *)K<128, false> : (const void *)K<64, false>))
+    if (kv_fp8 && stages == 2) return RA_FN(attention_kernel_fp8_s2);
+    if (kv_fp8) return RA_FN(attention_kernel_fp8);
+    if (stages == 2) return RA_FN(attention_kernel_s2);
+    return RA_FN(attention_kernel_s3);
+#undef RA_FN
 }
 
 hipError_t attention_config(int D, int kv_fp8, int num_cus, int *stages, int *waves)
@@ -1035,8 +1447,7 @@ hipError_t attention_config(int D, int kv_fp8, int num_cus, int *stages, int *wa
     int st = 2, per_cu = 4;
     if (const char *ev = getenv(kv_fp8 ? "ROLLOUT_ATTN_FP8_STAGES" : "ROLLOUT_ATTN_STAGES")) {
         int v = atoi(ev);
-        if (kv_fp8 && (v == 2 || v == 3)) st = v;
-        if (!kv_fp8 && (v == 2 || v == 3)) st = v;
+        if (v == 2 || v == 3) st = v;
     }
     size_t lds = attention_lds_bytes(D, kv_fp8, st);
     per_cu = (int)((160u * 1024u) / lds);
@@ -1049,8 +1460,10 @@ hipError_t attention_config(int D, int kv_fp8, int num_cus, int *stages, int *wa
         int v = atoi(ev);
         if (v >= 1 && v <= 16) per_cu = v;
     }
-    hipError_t e = hipFuncSetAttribute(attention_fn(D, kv_fp8, st), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
+    for (int self = 0; self < 2; self++) {
+        hipError_t e = hipFuncSetAttribute(attention_fn(D, kv_fp8, st, self != 0), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
     *stages = st;
     *waves = per_cu * num_cus;
     return hipSuccess;
@@ -1063,70 +1476,74 @@ hipError_t launch_attention(const Launch &a, hipStream_t s)
 #define RA_LAUNCH(K)                                                                                                      \
     hipLaunchKernelGGL(K, dim3(a.waves), dim3(64), lds, s, a, a.q, a.block_table, a.pfx_pages, w.hdr,                       \
                        (const uint32_t *)w.seg_rec, w.members)
-    if (a.kv_fp8 && a.stages == 2) {
-        if (a.D == 128) RA_LAUNCH(attention_kernel_fp8_s2<128>);
-        else RA_LAUNCH(attention_kernel_fp8_s2<64>);
-    } else if (a.kv_fp8) {
-        if (a.D == 128) RA_LAUNCH(attention_kernel_fp8<128>);
-        else RA_LAUNCH(attention_kernel_fp8<64>);
-    } else if (a.stages == 2) {
-        if (a.D == 128) RA_LAUNCH(attention_kernel_s2<128>);
-        else RA_LAUNCH(attention_kernel_s2<64>);
-    } else {
-        if (a.D == 128) RA_LAUNCH(attention_kernel_s3<128>);
-        else RA_LAUNCH(attention_kernel_s3<64>);
-    }
+#define RA_LAUNCH_D(K)                                                                                                    \
+    do {                                                                                                                  \
+        if (a.self_plan) {                                                                                                \
+            if (a.D == 128) RA_LAUNCH((K<128, true>));                                                                    \
+            else RA_LAUNCH((K<64, true>));                                                                                \
+        } else {                                                                                                          \
+            if (a.D == 128) RA_LAUNCH((K<128, false>));                                                                   \
+            else RA_LAUNCH((K<64, false>));                                                                               \
+        }                                                                                                                 \
+    } while (0)
+    if (a.kv_fp8 && a.stages == 2) RA_LAUNCH_D(attention_kernel_fp8_s2);
+    else if (a.kv_fp8) RA_LAUNCH_D(attention_kernel_fp8);
+    else if (a.stages == 2) RA_LAUNCH_D(attention_kernel_s2);
+    else RA_LAUNCH_D(attention_kernel_s3);
+#undef RA_LAUNCH_D
 #undef RA_LAUNCH
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------------------
-// die calibration: how fast does each accelerator die stream when all of them stream at once?
+// streaming probe: what the memory system delivers to the attention kernel's access pattern with no arithmetic
 //
-// The attention kernel gives every resident wave one span of the work, and a wave's speed is its die's
-// share of the memory system, which differs from die to die and from machine to machine by up to a tenth.
-// This probe has the attention kernel's launch shape (one wave per workgroup, the same LDS footprint, so
-// the same waves on the same compute units) and its memory behaviour (a two-stage LDS ring of 16 KB stages
-// fed by direct global->LDS loads from scattered 16 KB blocks); a pause stands for the arithmetic.  Every
-// wave reports how long its share took and which die it ran on.
+// The attention kernel's launch shape (one wave per workgroup, the same LDS footprint, so the same waves on the
+// same compute units) and its memory behaviour: a two-slot LDS ring of 16 KB entries fed by direct global->LDS
+// loads.  An entry is 16 KB / granule pieces, each read from a place of its own: granule 4096 is the attention
+// kernel's pattern (K0 K1 V0 V1 tiles of a 128-wide bf16 head), 16384 one contiguous block per entry.  Places are
+// a fixed permutation of the buffer's granules (scattered) or consecutive (sequential: the grid sweeps the buffer).
 // ------------------------------------------------------------------------------------------------------
 
-__global__ __launch_bounds__(64) void calibrate_kernel(const uint8_t *__restrict__ buf, int nblocks, int stages, long long *out)
+__global__ __launch_bounds__(64) void stream_probe_kernel(const uint8_t *__restrict__ buf, uint32_t granule_mask, int granule_shift,
+                                                           int scattered, int entries)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     const uint32_t lds_addr = (uint32_t)(uintptr_t)lds;
     const int lane = threadIdx.x;
-    const long long t0 = wall_clock64();
-    // block of stage s: a fixed permutation of [0, nblocks) (nblocks is a power of two, the multiplier is odd)
+    const int per = 14 - granule_shift; // log2 of the pieces per entry
+    // entry s of this wave: number w + s * waves in the sweep; its piece i is granule (that number << per) + i
     auto issue = [&](int s) {
-        const uint32_t blk = ((uint32_t)(blockIdx.x + s * gridDim.x) * 40503u) & (uint32_t)(nblocks - 1);
-        const uint8_t *src = buf + (size_t)blk * 16384;
+        const uint32_t first = ((uint32_t)blockIdx.x + (uint32_t)s * gridDim.x) << per;
 #pragma unroll
-        for (int n = 0; n < 16; n++) dma16_base((uint32_t)(1024 * n + 16 * lane), src, lds_addr + (s & 1) * 16384 + 1024 * n);
+        for (int n = 0; n < 16; n++) {
+            // load n moves 1 KB: piece (n * 1024) >> granule_shift, offset inside the piece the rest
+            const uint32_t piece = (uint32_t)(n * 1024) >> granule_shift, within = (uint32_t)(n * 1024) & ((1u << granule_shift) - 1);
+            uint32_t g = first + piece;
+            if (scattered) g = g * 2654435761u + 12345u; // odd multiplier: a permutation modulo a power of two
+            const uint8_t *src = buf + ((size_t)(g & granule_mask) << granule_shift) + within;
+            dma16_base((uint32_t)(16 * lane), src, lds_addr + (s & 1) * 16384 + 1024 * n);
+        }
     };
     issue(0);
-    for (int s = 0; s < stages; s++) {
-        if (s + 1 < stages) {
+    for (int s = 0; s < entries; s++) {
+        if (s + 1 < entries) {
             issue(s + 1);
             wait_vmcnt<16>();
         } else {
             wait_vmcnt<0>();
         }
-        // the attention kernel spends about this long on the arithmetic of a stage, issuing nothing meanwhile;
-        // a wave's speed depends on the memory latency only through the sum of the two
-        __builtin_amdgcn_s_sleep(56);
-    }
-    if (lane == 0) {
-        out[2 * blockIdx.x] = wall_clock64() - t0;
-        out[2 * blockIdx.x + 1] = __builtin_amdgcn_s_getreg((20) | (0 << 6) | (3 << 11)) & 7; // die (XCC_ID)
     }
 }
 
-hipError_t launch_calibrate(const void *buf, int nblocks, int stages, int waves, long long *out, hipStream_t s)
+hipError_t launch_stream_probe(const void *buf, size_t buf_bytes, int granule, int scattered, int entries, int waves, hipStream_t s)
 {
-    hipError_t e = hipFuncSetAttribute((const void *)calibrate_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 40960);
+    hipError_t e = hipFuncSetAttribute((const void *)stream_probe_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 40960);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(calibrate_kernel, dim3(waves), dim3(64), 40960, s, (const uint8_t *)buf, nblocks, stages, out);
+    int shift = 0;
+    while ((1 << shift) < granule) shift++;
+    hipLaunchKernelGGL(stream_probe_kernel, dim3(waves), dim3(64), 40960, s, (const uint8_t *)buf, (uint32_t)((buf_bytes >> shift) - 1), shift,
+                       scattered, entries);
     return hipGetLastError();
 }
 
@@ -1154,9 +1571,24 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(Launch a, const in
     const Workspace &w = a.ws;
     const int item = blockIdx.x, b = item / a.Hkv, kvh = item - b * a.Hkv;
     const int D = a.D, tpr = D / 4; // threads per output row
-    const int4 own = merge_desc[2 * item], pfx = merge_desc[2 * item + 1];
-    const int prow = seq_pfx_row[b];
+    int4 own = merge_desc[2 * item], pfx = merge_desc[2 * item + 1];
+    int prow = seq_pfx_row[b];
     const int row0 = seq_rank_in_row[b] * a.G;
+    if (a.self_plan) {
+        // The attention waves wrote the first and last spans of the pieces that exist, and nothing for those that do
+        // not; which exist follows from the inputs (as in the rows phase).
+        const int NG = a.share ? a.num_groups : 0;
+        int Lb = a.seq_lens[b];
+        Lb = Lb < 0 ? 0 : (Lb > a.max_pages * kPage ? a.max_pages * kPage : Lb);
+        const int g = NG ? a.seq_group[b] : -1;
+        int np = 0;
+        if (g >= 0 && g < NG) {
+            np = a.pfx_off[g + 1] - a.pfx_off[g];
+            if (np <= 0 || Lb < np * kPage) np = 0;
+        }
+        if (np == 0) pfx.y = 0, pfx.z = -1, prow = -1;
+        if ((Lb + kPage - 1) / kPage - np <= 0) own.y = 0, own.z = -1;
+    }
     PartList pl[2];
     {
         PartList &p = pl[1];

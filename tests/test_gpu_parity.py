@@ -164,6 +164,77 @@ def test_batch_beyond_the_schedules_lds_tables(dec):
     compare(*run(dec, p).results(), ref_out, ref_lse, "groups = %d" % ngroups)
 
 
+@pytest.fixture(scope="module")
+def dec_sched():
+    """A context that always launches the schedule kernels (the path of batches too large for the attention waves to
+    plan for themselves); the setting is read when the context is made."""
+    import os
+    import paper_2507_01663_amd as ra
+    old = os.environ.get("ROLLOUT_ATTN_SELF_PLAN")
+    os.environ["ROLLOUT_ATTN_SELF_PLAN"] = "0"
+    try:
+        d = ra.Decoder(0)
+    finally:
+        if old is None:
+            os.environ.pop("ROLLOUT_ATTN_SELF_PLAN", None)
+        else:
+            os.environ["ROLLOUT_ATTN_SELF_PLAN"] = old
+    yield d
+    d.close()
+
+
+@pytest.mark.parametrize("name,kv", [("tiny", "bf16"), ("mid7b", "bf16"), ("mid32b", "fp8_e4m3"), ("mid72b", "bf16"), ("grpo7b", "bf16")])
+def test_parity_with_the_schedule_kernels(dec_sched, dec, name, kv):
+    """Small batches normally take the path where every attention wave plans its own span; the same batches through
+    the schedule kernels must give the same answer within tolerance (the spans are the same, so in fact the same bytes)."""
+    from gpu_util import compare
+    p = workload.make_problem(name, seed=0, kv_dtype=kv)
+    ref = oracle.decode(p)
+    a = run(dec_sched, p)
+    compare(*a.results(), *ref, "%s %s (schedule kernels)" % (name, kv))
+    b = run(dec, p)
+    torch.cuda.synchronize()
+    assert torch.equal(a.out.view(torch.int16), b.out.view(torch.int16)) and torch.equal(a.lse, b.lse)
+
+
+@pytest.fixture(scope="module")
+def dec_few_waves():
+    """A context with one attention workgroup per compute unit instead of four: four times longer spans."""
+    import os
+    import paper_2507_01663_amd as ra
+    old = os.environ.get("ROLLOUT_ATTN_WAVES_PER_CU")
+    os.environ["ROLLOUT_ATTN_WAVES_PER_CU"] = "1"
+    try:
+        d = ra.Decoder(0)
+    finally:
+        if old is None:
+            os.environ.pop("ROLLOUT_ATTN_WAVES_PER_CU", None)
+        else:
+            os.environ["ROLLOUT_ATTN_WAVES_PER_CU"] = old
+    yield d
+    d.close()
+
+
+def test_spans_with_more_segments_than_a_wave_lists_at_once(dec_few_waves):
+    """A few very long sequences make the spans long, and hundreds of very short ones then fall into single spans
+    (about 150 segments each here): a wave that plans for itself lists at most 64 (head dim 64) or 128 segments at a
+    time and has to plan again from where it stopped; shared-prefix rows of many members (one query head per kv head)
+    take several records each."""
+    from gpu_util import compare
+    dec = dec_few_waves
+    for D, Hkv, Hq in ((64, 8, 8), (128, 4, 4)):
+        rng = np.random.default_rng(31 + D)
+        ngroups, R = 6, 70
+        resp = rng.integers(1, 3, size=ngroups * R)          # one or two tokens beyond the prompt
+        resp[::R] = 111000                                    # one long member per group
+        p = workload.build_problem("fragments", Hq, Hkv, D, [16] * ngroups, R, resp, seed=31)
+        assert p.B == 420
+        log("fragments D", D, "pages", p.num_pages)
+        ref_out, ref_lse = oracle.decode(p)
+        compare(*run(dec, p).results(), ref_out, ref_lse, "fragments D = %d" % D)
+        compare(*run(dec, p, use_hint=False).results(), ref_out, ref_lse, "fragments D = %d, no hint" % D)
+
+
 def test_sixteen_query_heads_per_kv_head(dec):
     from gpu_util import compare
     for D in (64, 128):
