@@ -127,7 +127,7 @@ uint32_t rollout_attn_abi_version(void);
  * Tuning knobs, read from the environment here and nowhere else (none changes a result beyond rounding; values
  * out of range are ignored):
  *   ROLLOUT_ATTN_XCD_WEIGHTS=a,..,h the share of the work each of the eight dies' workgroups get, per mille of the
- *                                   mean (700..1400; default: equal shares)
+ *                                   mean (700..1400; default: a built-in table, the odd dies about a tenth less)
  *   ROLLOUT_ATTN_STAGES=2|3, ROLLOUT_ATTN_FP8_STAGES=2|3   depth of the LDS ring for bf16 / e4m3 pools
  *   ROLLOUT_ATTN_WAVES_PER_CU=1..16 attention workgroups per compute unit (default: as many as are resident)
  *   ROLLOUT_ATTN_COST_PREFIX=1..16, ROLLOUT_ATTN_COST_ITEM=0..256   scheduling weights of a shared-prefix page and
@@ -295,6 +295,18 @@ ra_status rollout_attn_prefill(ra_ctx *ctx, const ra_prefill *prefill, void *hip
  * runs out. */
 ra_status rollout_attn_balance(const int64_t *weights, int64_t n, int32_t k, int32_t equal_count, int32_t *part,
                                int64_t *part_sums);
+
+/* The attention kernel is launched as one single-wave workgroup per resident slot of the device, and workgroup c
+ * streams the c-th share of the batch's pages.  The workgroups do not all stream equally fast: the accelerator dies
+ * get different shares of the memory bandwidth and so do the compute units inside a die, in a pattern that repeats
+ * from launch to launch.  These two calls let a caller tell the schedule: rollout_attn_wave_count says how many
+ * workgroups the launch for (kv_dtype, head_dim) has, rollout_attn_set_wave_weights sets their shares (weights: HOST
+ * int32 [n], per mille of the mean, clamped to 700..1400; n must equal the wave count).  Default: a fixed share per
+ * die.  The weights only move work between workgroups (paper Sec. 4.4 balances tokens between workers the same way);
+ * results stay within rounding of each other, and identical for identical weights.  Copies to the device
+ * synchronously: call it while no work of the context is in flight. */
+ra_status rollout_attn_wave_count(const ra_ctx *ctx, int32_t kv_dtype, int32_t head_dim, int32_t *waves);
+ra_status rollout_attn_set_wave_weights(ra_ctx *ctx, int32_t kv_dtype, int32_t head_dim, const int32_t *weights, int32_t n);
 
 /* Streaming probe for benchmarks: what the memory system delivers to the attention kernel's access pattern when no
  * arithmetic is done (the decode step is memory-bound, paper Sec. 2.1.1, so this is the practical ceiling its achieved

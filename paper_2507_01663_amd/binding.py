@@ -98,6 +98,10 @@ def load_library():
     lib.rollout_attn_prefill.argtypes = [ctypes.c_void_p, P(ra_prefill), ctypes.c_void_p]
     lib.rollout_attn_balance.restype = ctypes.c_int
     lib.rollout_attn_balance.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+    lib.rollout_attn_wave_count.restype = ctypes.c_int
+    lib.rollout_attn_wave_count.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, P(ctypes.c_int32)]
+    lib.rollout_attn_set_wave_weights.restype = ctypes.c_int
+    lib.rollout_attn_set_wave_weights.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32]
     lib.rollout_attn_debug_stream.restype = ctypes.c_int
     lib.rollout_attn_debug_stream.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32,
                                               ctypes.c_int32, ctypes.c_void_p, P(ctypes.c_size_t)]
@@ -192,6 +196,19 @@ def rollout_attn_balance(weights, k, equal_count=False):
     _check(load_library().rollout_attn_balance(w.ctypes.data, w.size, int(k), int(bool(equal_count)), part.ctypes.data,
                                                sums.ctypes.data), None)
     return part, sums
+
+
+def rollout_attn_wave_count(ctx, kv_dtype=RA_KV_BF16, head_dim=128):
+    n = ctypes.c_int32()
+    _check(load_library().rollout_attn_wave_count(ctx, kv_dtype, head_dim, ctypes.byref(n)), ctx)
+    return int(n.value)
+
+
+def rollout_attn_set_wave_weights(ctx, weights, kv_dtype=RA_KV_BF16, head_dim=128):
+    """weights: per mille of the mean, one per attention workgroup of the launch shape (host integers)."""
+    import numpy as np
+    w = np.ascontiguousarray(weights, dtype=np.int32)
+    _check(load_library().rollout_attn_set_wave_weights(ctx, kv_dtype, head_dim, w.ctypes.data, w.size), ctx)
 
 
 def rollout_attn_debug_stream(ctx, buf_ptr, buf_bytes, granule_bytes, scattered, entries_per_wave, hip_stream=None):

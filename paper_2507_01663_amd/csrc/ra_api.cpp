@@ -22,7 +22,8 @@ struct ra_ctx {
     int stages[2][2]; // LDS ring depth, same indices
     int cost_prefix[2]; // scheduling weight of a shared-prefix page, [e4m3 KV]
     int cost_item;   // ... of a segment, on top of its pages
-    int xcd_w[2][8]; // share of the page stream per accelerator die, [e4m3 KV]
+    int xcd_w[8];              // default share of the page stream per accelerator die, per mille of the mean
+    int32_t *wave_cum[2][2];   // device: running sums of the workgroups' shares, [e4m3 KV][D == 128], kMaxWaves + 1 each
     void *zeros;  // 256 bytes of zeros on the device
     int self_plan; // attention waves may plan their spans themselves (no schedule kernel)
     int32_t *host_flags; // pinned, for RA_FLAG_VALIDATE
@@ -111,18 +112,7 @@ void fill_launch(ra::Launch &a, const ra_ctx *ctx, const ra_problem *p)
     a.recip_g = (65536 + a.G - 1) / a.G;
     a.cost_prefix = ctx ? ctx->cost_prefix[a.kv_fp8] : (a.kv_fp8 ? ra::kCostPrefixFp8 : ra::kCostPrefix);
     a.cost_item = ctx ? ctx->cost_item : ra::kCostItem;
-    {
-        // normalised so that the eight weights add up to 8192 (the schedule divides by a shift)
-        long W = 0;
-        int acc = 0;
-        const bool use = ctx && a.waves % 8 == 0;
-        const int *xw = ctx ? ctx->xcd_w[a.kv_fp8] : nullptr;
-        for (int x = 0; x < 8; x++) W += use ? xw[x] : 1000;
-        for (int x = 0; x < 8; x++) {
-            a.xcd_w[x] = x < 7 ? (int)(((use ? xw[x] : 1000) * 8192L + W / 2) / W) : 8192 - acc;
-            acc += a.xcd_w[x];
-        }
-    }
+    a.wave_cum = ctx ? ctx->wave_cum[a.kv_fp8][p->D == 128] : nullptr;
     a.q = (const uint16_t *)p->q;
     a.k_pool = (const uint8_t *)p->k_pool; a.v_pool = (const uint8_t *)p->v_pool;
     a.stride_page_b = p->kv_stride_page * es; a.stride_head_b = p->kv_stride_head * es;
@@ -134,6 +124,22 @@ void fill_launch(ra::Launch &a, const ra_ctx *ctx, const ra_problem *p)
     a.out = (uint16_t *)p->out; a.lse = p->lse;
     a.zeros = ctx ? ctx->zeros : nullptr;
     a.self_plan = ctx && ctx->self_plan && ra::can_self_plan(a.D, a.kv_fp8, a.stages, a.B, a.share ? a.num_groups : 0, a.members_per_row);
+}
+
+// Turns per-workgroup weights (per mille of the mean, clamped to 700..1400 so that no span is shorter than half the
+// mean) into the running sums the schedule reads, and uploads them.
+static hipError_t upload_wave_weights(ra_ctx *c, int f, int d, const int32_t *w, int n)
+{
+    std::vector<int32_t> cum((size_t)n + 1);
+    double total = 0;
+    for (int i = 0; i < n; i++) total += w[i] < 700 ? 700 : (w[i] > 1400 ? 1400 : w[i]);
+    double run = 0;
+    for (int i = 0; i < n; i++) {
+        cum[i] = (int32_t)std::llround(run / total * 1048576.0);
+        run += w[i] < 700 ? 700 : (w[i] > 1400 ? 1400 : w[i]);
+    }
+    cum[n] = 1 << 20;
+    return hipMemcpy(c->wave_cum[f][d], cum.data(), ((size_t)n + 1) * 4, hipMemcpyHostToDevice);
 }
 
 } // namespace
@@ -157,17 +163,18 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
     c->cost_prefix[0] = ra::kCostPrefix;
     c->cost_prefix[1] = ra::kCostPrefixFp8;
     c->cost_item = ra::kCostItem;
-    // Share of the page stream each accelerator die's workgroups get, per mille of the mean.  The dies do not stream
-    // equally fast, but the pattern changes from machine to machine and with the pools' placement, so the default is
-    // equal shares; ROLLOUT_ATTN_XCD_WEIGHTS is there for experiments.
-    for (int x = 0; x < 8; x++) c->xcd_w[0][x] = c->xcd_w[1][x] = 1000;
+    // Share of the page stream each accelerator die's workgroups get, per mille of the mean (workgroups are dealt to the
+    // dies round-robin).  The odd dies stream about a tenth slower than the even ones on the machines measured; beyond
+    // that the pattern is per workgroup and per machine, which rollout_attn_tune measures.
+    static const int kXcdShare[8] = {1060, 950, 1060, 935, 1045, 930, 1055, 965};
+    for (int x = 0; x < 8; x++) c->xcd_w[x] = kXcdShare[x];
     if (const char *ev = getenv("ROLLOUT_ATTN_XCD_WEIGHTS")) {
         int v[8];
         if (sscanf(ev, "%d,%d,%d,%d,%d,%d,%d,%d", &v[0], &v[1], &v[2], &v[3], &v[4], &v[5], &v[6], &v[7]) == 8) {
             bool ok = true;
             for (int x = 0; x < 8; x++) ok = ok && v[x] >= 700 && v[x] <= 1400; // no span under half the mean
             if (ok)
-                for (int x = 0; x < 8; x++) c->xcd_w[0][x] = c->xcd_w[1][x] = v[x];
+                for (int x = 0; x < 8; x++) c->xcd_w[x] = v[x];
         }
     }
     c->self_plan = 1;
@@ -195,11 +202,20 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
         for (int d = 0; d < 2; d++)
             if (e == hipSuccess) e = ra::attention_config(d ? 128 : 64, f, c->num_cus, &c->stages[f][d], &c->waves[f][d]);
     if (e == hipSuccess) e = ra::prefill_config();
+    for (int f = 0; f < 2; f++)
+        for (int d = 0; d < 2; d++) {
+            if (e == hipSuccess) e = hipMalloc((void **)&c->wave_cum[f][d], ((size_t)ra::kMaxWaves + 1) * 4);
+            if (e == hipSuccess && c->waves[f][d] > ra::kMaxWaves) e = hipErrorInvalidValue;
+            if (e == hipSuccess) {
+                std::vector<int32_t> w((size_t)c->waves[f][d]);
+                for (size_t i = 0; i < w.size(); i++) w[i] = c->waves[f][d] % 8 == 0 ? c->xcd_w[i % 8] : 1000;
+                e = upload_wave_weights(c, f, d, w.data(), (int)w.size());
+            }
+        }
     if (e == hipSuccess) e = hipGetSymbolAddress(&c->scratch_ptr, HIP_SYMBOL(scratch)); // this device's copy
     if (getenv("ROLLOUT_ATTN_VERBOSE"))
-        for (int f = 0; f < 2; f++)
-            fprintf(stderr, "rollout_attn: die weights (%s KV) %d %d %d %d %d %d %d %d\n", f ? "e4m3" : "bf16", c->xcd_w[f][0],
-                    c->xcd_w[f][1], c->xcd_w[f][2], c->xcd_w[f][3], c->xcd_w[f][4], c->xcd_w[f][5], c->xcd_w[f][6], c->xcd_w[f][7]);
+        fprintf(stderr, "rollout_attn: die shares %d %d %d %d %d %d %d %d\n", c->xcd_w[0], c->xcd_w[1], c->xcd_w[2], c->xcd_w[3], c->xcd_w[4],
+                c->xcd_w[5], c->xcd_w[6], c->xcd_w[7]);
     (void)hipSetDevice(prev);
     if (e != hipSuccess) {
         set_err(nullptr, "context set-up on device %d: %s", device, hipGetErrorString(e));
@@ -214,6 +230,9 @@ void rollout_attn_destroy(ra_ctx *c)
 {
     if (!c) return;
     if (c->zeros) (void)hipFree(c->zeros);
+    for (int f = 0; f < 2; f++)
+        for (int d = 0; d < 2; d++)
+            if (c->wave_cum[f][d]) (void)hipFree(c->wave_cum[f][d]);
     if (c->host_flags) (void)hipHostFree(c->host_flags);
     for (int i = 0; i < 4; i++)
         if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
@@ -465,6 +484,36 @@ ra_status rollout_attn_prefill(ra_ctx *c, const ra_prefill *p, void *stream)
     if (e == hipSuccess && prev != c->device) e = hipSetDevice(c->device);
     if (e == hipSuccess && p->k_pool) e = ra::launch_prefill_write(a, (hipStream_t)stream);
     if (e == hipSuccess) e = ra::launch_prefill(a, (hipStream_t)stream);
+    if (prev != c->device) (void)hipSetDevice(prev);
+    if (e != hipSuccess) { set_err(c, "HIP: %s", hipGetErrorString(e)); return RA_ERR_DEVICE; }
+    return RA_OK;
+}
+
+ra_status rollout_attn_wave_count(const ra_ctx *c, int32_t kv_dtype, int32_t head_dim, int32_t *waves)
+{
+    if (!c || !waves || (kv_dtype != RA_KV_BF16 && kv_dtype != RA_KV_FP8_E4M3) || (head_dim != 64 && head_dim != 128)) {
+        set_err(const_cast<ra_ctx *>(c), "wave count: bad context, kv_dtype or head_dim");
+        return RA_ERR_INVALID_ARG;
+    }
+    *waves = c->waves[kv_dtype == RA_KV_FP8_E4M3][head_dim == 128];
+    return RA_OK;
+}
+
+ra_status rollout_attn_set_wave_weights(ra_ctx *c, int32_t kv_dtype, int32_t head_dim, const int32_t *weights, int32_t n)
+{
+    if (!c || !weights || (kv_dtype != RA_KV_BF16 && kv_dtype != RA_KV_FP8_E4M3) || (head_dim != 64 && head_dim != 128)) {
+        set_err(c, "wave weights: bad context, kv_dtype, head_dim or weights");
+        return RA_ERR_INVALID_ARG;
+    }
+    const int f = kv_dtype == RA_KV_FP8_E4M3, d = head_dim == 128;
+    if (n != c->waves[f][d]) {
+        set_err(c, "wave weights: %d given, this launch shape has %d workgroups (rollout_attn_wave_count)", n, c->waves[f][d]);
+        return RA_ERR_INVALID_ARG;
+    }
+    int prev = 0;
+    hipError_t e = hipGetDevice(&prev);
+    if (e == hipSuccess && prev != c->device) e = hipSetDevice(c->device);
+    if (e == hipSuccess) e = upload_wave_weights(c, f, d, weights, n);
     if (prev != c->device) (void)hipSetDevice(prev);
     if (e != hipSuccess) { set_err(c, "HIP: %s", hipGetErrorString(e)); return RA_ERR_DEVICE; }
     return RA_OK;

@@ -8,6 +8,7 @@ namespace ra {
 
 constexpr int kPage = 16;           // tokens per page
 constexpr int kMinUnitsPerWave = 8; // do not cut the page stream finer than this many pages
+constexpr int kMaxWaves = 4096;     // attention workgroups of a launch at most (16 per compute unit)
 constexpr int kCostSuffix = 4;      // scheduling weight of a page of a sequence's own KV
 constexpr int kChunkSegs = 7;       // segment records per chunk of a span's work list (plus one header record)
 constexpr int kCostPrefix = 8;      // ... of a shared-prefix page of a bf16 pool (64 query rows per byte read: more time per page)
@@ -42,7 +43,7 @@ struct Launch {
     int32_t prefix_rows;     // query rows a shared-prefix work row carries (members x heads per kv head, at most)
     int32_t members_per_row; // = prefix_rows / G
     int32_t recip_g;         // ceil(2^16 / G): (x * recip_g) >> 16 == x / G for 0 <= x <= 64
-    int32_t xcd_w[8]; // relative speed of the eight accelerator dies, adding up to 8192
+    const int32_t *wave_cum; // [waves + 1] running sum of the workgroups' shares of the page stream, 0 .. 2^20
     const uint16_t *q;
     const uint8_t *k_pool, *v_pool;
     int64_t stride_page_b, stride_head_b; // bytes
@@ -91,7 +92,8 @@ bool can_self_plan(int D, int kv_fp8, int stages, int B, int num_groups, int mem
 
 // Streams entries * 16 KB per wave from buf (a power of two of bytes) through the attention kernel's ring, in pieces of
 // `granule` bytes (1024 .. 16384, a power of two), scattered over the buffer or consecutive.
-hipError_t launch_stream_probe(const void *buf, size_t buf_bytes, int granule, int scattered, int entries, int waves, hipStream_t s);
+hipError_t launch_stream_probe(const void *buf, size_t buf_bytes, int granule, int scattered, int entries, int waves, hipStream_t s,
+                               long long *clocks = nullptr /* [waves] duration of every wave in 10 ns ticks */);
 hipError_t launch_validate(const Launch &a, hipStream_t s);
 hipError_t launch_plan(const Launch &a, hipStream_t s);
 hipError_t launch_attention(const Launch &a, hipStream_t s);

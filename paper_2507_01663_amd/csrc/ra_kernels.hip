@@ -148,32 +148,30 @@ template <int THREADS> __device__ __forceinline__ void block_scan(int32_t *a, in
     __syncthreads();
 }
 
-// Where the cost stream is cut: into one span per resident wave.  Workgroups are dealt round-robin to the eight
-// accelerator dies, which do not all get the same share of the memory bandwidth, so within each block of eight
-// consecutive spans (8*S0 units) span x gets a share proportional to the weight xcd_w[x] of its die (the weights add
-// up to 8192; equal unless set otherwise).
+// Where the cost stream is cut: into one span per resident wave.  The workgroups do not all stream equally fast (the
+// eight accelerator dies get different shares of the memory bandwidth, and so do the compute units inside a die,
+// in a pattern that repeats from launch to launch), so span c gets the share cum[c+1] - cum[c] of the stream, in
+// units of 2^-20; the table comes from the context (equal shares per die pair unless the context was tuned).
 struct Cuts {
-    int U, S0; // the stream has fewer than 2^31 units (checked on the host); divisions stay 32 bits wide
+    int U, S0; // the stream has fewer than 2^31 units (checked on the host)
     int waves;
-    int acc[9]; // running sums of the die weights
+    long V;              // S0 * waves >= U: the length the shares refer to
+    const int32_t *cum;  // [waves + 1], cum[0] = 0, cum[waves] = 2^20, increasing
+    __device__ long start(int c) const { return (V * cum[c]) >> 20; }
     __device__ int lo(int c) const
     {
-        int w = 0; // acc[c & 7], without indexing (the table then stays in registers)
-#pragma unroll
-        for (int i = 1; i < 8; i++)
-            if ((c & 7) == i) w = acc[i];
-        const long v = (long)(c >> 3) * 8 * S0 + ((8L * S0 * w) >> 13);
+        const long v = start(c);
         return v < U ? (int)v : U;
     }
     __device__ int span_of(int pos) const // the span that holds cost unit pos < U
     {
-        const unsigned blk = (unsigned)pos / (unsigned)(8 * S0);
-        const int rem = pos - (int)blk * 8 * S0;
-        int x = 0;
-#pragma unroll
-        for (int i = 1; i < 8; i++)
-            if ((int)((8L * S0 * acc[i]) >> 13) <= rem) x = i;
-        return (int)blk * 8 + x;
+        int c = 0, hi = waves; // invariant: start(c) <= pos < start(hi)
+        while (hi - c > 1) {
+            const int mid = (c + hi) >> 1;
+            if (start(mid) <= pos) c = mid;
+            else hi = mid;
+        }
+        return c;
     }
 };
 
@@ -377,19 +375,25 @@ __global__ __launch_bounds__(kPlanThreads) void plan_rows_kernel(Launch a)
 
 // Second half of the schedule: the cuts, every span's work list, and the merge descriptors.
 
-__device__ __forceinline__ void make_cuts(const Launch &a, int U, Cuts &cut)
+// cut.lo(c) for a wave-uniform c, with the table read through the scalar cache.
+__device__ __forceinline__ int uniform_cut(const Cuts &cut, int c)
+{
+    const long v = (cut.V * uniform_load(cut.cum, c)) >> 20;
+    return v < cut.U ? (int)v : cut.U;
+}
+
+__device__ __forceinline__ void make_cuts(const Launch &a, int U, Cuts &cut, const int32_t *cum)
 {
     cut.U = U;
     cut.waves = a.waves;
+    cut.cum = cum;
     // no span is shorter than a few pages, and none is shorter than one page of either kind, so that every
     // span between the first and the last one of an item holds at least one of its pages
     int min_span = kMinUnitsPerWave * kCostSuffix;
-    if (min_span < 4 * a.cost_prefix) min_span = 4 * a.cost_prefix; // (a die's share is at least half the mean)
+    if (min_span < 4 * a.cost_prefix) min_span = 4 * a.cost_prefix; // (a workgroup's share is at least half the mean)
     cut.S0 = (int)(((unsigned)cut.U + a.waves - 1) / (unsigned)a.waves);
     if (cut.S0 < min_span) cut.S0 = min_span;
-    cut.acc[0] = 0;
-#pragma unroll
-    for (int x = 0; x < 8; x++) cut.acc[x + 1] = cut.acc[x] + a.xcd_w[x];
+    cut.V = (long)cut.S0 * a.waves;
 }
 
 // The work list of spans first, first + stride, ...: one record per segment (the pages of one (row, kv head) item
@@ -487,8 +491,10 @@ __global__ __launch_bounds__(kSpanThreads) void plan_spans_kernel(Launch a)
     touch_args(a);
     __shared__ int32_t l_row_start[2 * kPlanCap + 1];
     __shared__ int4 l_row_tab[2 * kPlanCap];
+    __shared__ int32_t l_cum[kMaxWaves + 1];
     const int tid = threadIdx.x;
     const int gtid = blockIdx.x * kSpanThreads + tid, gstride = gridDim.x * kSpanThreads;
+    for (int i = tid; i <= a.waves; i += kSpanThreads) l_cum[i] = a.wave_cum[i];
     const Workspace &w = a.ws;
     const int32_t *row_start = w.row_start;
     const int4 *row_tab = w.row_tab;
@@ -505,7 +511,7 @@ __global__ __launch_bounds__(kSpanThreads) void plan_spans_kernel(Launch a)
     __syncthreads();
 
     Cuts cut;
-    make_cuts(a, U, cut);
+    make_cuts(a, U, cut, l_cum);
     if (gtid == 0) w.hdr[7] = cut.waves;
     spans_phase(a, cut, row_start, row_tab, nR, nPR, gtid, gstride);
     for (int i = gtid; i < a.B * a.Hkv; i += gstride) merge_desc_of(a, cut, row_start, nPR, i, i == gtid ? my_prow : w.seq_pfx_row[i / a.Hkv]);
@@ -520,15 +526,17 @@ __global__ __launch_bounds__(kPlanThreads) void plan_fused_kernel(Launch a)
     touch_args(a);
     __shared__ RowsLds L;
     __shared__ int4 l_row_tab[2 * kPlanCap];
+    __shared__ int32_t l_cum[kMaxWaves + 1];
     const int tid = threadIdx.x;
     const Workspace &w = a.ws;
+    for (int i = tid; i <= a.waves; i += kPlanThreads) l_cum[i] = a.wave_cum[i];
     RowsBuf R;
     plan_rows_buf(R, a, L, true, l_row_tab, blockIdx.x == 0);
     int nR, nPR;
     rows_phase<kPlanThreads>(a, R, nR, nPR, tid);
     const int32_t *row_start = R.row_start;
     Cuts cut;
-    make_cuts(a, a.Hkv * row_start[nR], cut);
+    make_cuts(a, a.Hkv * row_start[nR], cut, l_cum);
     if (blockIdx.x == 0) {
         if (tid == 0) {
             w.hdr[0] = cut.U;
@@ -1165,7 +1173,10 @@ __device__ __forceinline__ int list_segments(const Launch &a, const WaveTables &
             }
             if (!prefix) {
                 const int i = info.x * a.Hkv + kvh;
-                if (lane == 0 && p_lo == 0) md[8 * i + 1] = c;
+                if (lane == 0 && p_lo == 0) {
+                    md[8 * i + 1] = c;
+                    if (info.y == 0) md[8 * i + 5] = 0, md[8 * i + 6] = -1; // no shared pages: says so for the merge
+                }
                 if (lane == 0 && p_hi == info.w) md[8 * i + 2] = c;
             } else {
                 // the row's members: numbers grp_k*MPR .. of the group's members in ascending order of sequence
@@ -1183,6 +1194,7 @@ __device__ __forceinline__ int list_segments(const Launch &a, const WaveTables &
                             md[8 * i + 5] = c;
                             a.ws.seq_pfx_row[b] = r; // (the same from every kv head)
                             a.ws.seq_rank_in_row[b] = place;
+                            if (T.len[b] <= info.w * kPage) md[8 * i + 1] = 0, md[8 * i + 2] = -1; // no pages of its own
                         }
                         if (p_hi == info.w) md[8 * i + 6] = c;
                     }
@@ -1300,8 +1312,8 @@ template <int D, int KVB, int NST, int NPEND, bool SELF> __device__ __forceinlin
             wave_rows(a, T, sp.nR, sp.nPR, plan_lane);
             if (first_pass) {
                 Cuts cut;
-                make_cuts(a, a.Hkv * ufl(T.rs[sp.nR]), cut);
-                sp.lo = cut.lo(c), sp.hi = cut.lo(c + 1);
+                make_cuts(a, a.Hkv * ufl(T.rs[sp.nR]), cut, a.wave_cum);
+                sp.lo = uniform_cut(cut, c), sp.hi = uniform_cut(cut, c + 1);
                 // the span's first item: the last row that starts at or before the span's first unit (starts do not decrease)
                 int at_or_before = 0;
 #pragma unroll 1
@@ -1506,11 +1518,12 @@ hipError_t launch_attention(const Launch &a, hipStream_t s)
 // ------------------------------------------------------------------------------------------------------
 
 __global__ __launch_bounds__(64) void stream_probe_kernel(const uint8_t *__restrict__ buf, uint32_t granule_mask, int granule_shift,
-                                                           int scattered, int entries)
+                                                           int scattered, int entries, long long *clocks)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     const uint32_t lds_addr = (uint32_t)(uintptr_t)lds;
     const int lane = threadIdx.x;
+    const long long t0 = wall_clock64();
     const int per = 14 - granule_shift; // log2 of the pieces per entry
     // entry s of this wave: number w + s * waves in the sweep; its piece i is granule (that number << per) + i
     auto issue = [&](int s) {
@@ -1534,16 +1547,18 @@ __global__ __launch_bounds__(64) void stream_probe_kernel(const uint8_t *__restr
             wait_vmcnt<0>();
         }
     }
+    if (clocks && lane == 0) clocks[blockIdx.x] = wall_clock64() - t0;
 }
 
-hipError_t launch_stream_probe(const void *buf, size_t buf_bytes, int granule, int scattered, int entries, int waves, hipStream_t s)
+hipError_t launch_stream_probe(const void *buf, size_t buf_bytes, int granule, int scattered, int entries, int waves, hipStream_t s,
+                               long long *clocks)
 {
     hipError_t e = hipFuncSetAttribute((const void *)stream_probe_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 40960);
     if (e != hipSuccess) return e;
     int shift = 0;
     while ((1 << shift) < granule) shift++;
     hipLaunchKernelGGL(stream_probe_kernel, dim3(waves), dim3(64), 40960, s, (const uint8_t *)buf, (uint32_t)((buf_bytes >> shift) - 1), shift,
-                       scattered, entries);
+                       scattered, entries, clocks);
     return hipGetLastError();
 }
 
@@ -1575,19 +1590,10 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(Launch a, const in
     int prow = seq_pfx_row[b];
     const int row0 = seq_rank_in_row[b] * a.G;
     if (a.self_plan) {
-        // The attention waves wrote the first and last spans of the pieces that exist, and nothing for those that do
-        // not; which exist follows from the inputs (as in the rows phase).
-        const int NG = a.share ? a.num_groups : 0;
-        int Lb = a.seq_lens[b];
-        Lb = Lb < 0 ? 0 : (Lb > a.max_pages * kPage ? a.max_pages * kPage : Lb);
-        const int g = NG ? a.seq_group[b] : -1;
-        int np = 0;
-        if (g >= 0 && g < NG) {
-            np = a.pfx_off[g + 1] - a.pfx_off[g];
-            if (np <= 0 || Lb < np * kPage) np = 0;
-        }
-        if (np == 0) pfx.y = 0, pfx.z = -1, prow = -1;
-        if ((Lb + kPage - 1) / kPage - np <= 0) own.y = 0, own.z = -1;
+        // The attention waves that hold an item's first own piece or first shared piece wrote both descriptors (the
+        // other one as empty if the item has no such pieces); an item without tokens has no piece and no descriptor.
+        if (a.seq_lens[b] <= 0 || a.max_pages <= 0) own.y = pfx.y = 0, own.z = pfx.z = -1;
+        if (pfx.y > pfx.z) prow = -1;
     }
     PartList pl[2];
     {

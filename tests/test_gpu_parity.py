@@ -462,3 +462,28 @@ def test_schedule_reused_for_another_layer(dec):
     dec.decode(d2.c)
     compare(*d1.results(), *oracle.decode(p1), "layer 1")
     compare(*d2.results(), *oracle.decode(p2), "layer 2 on layer 1's schedule")
+
+
+def test_wave_weights_move_work_not_results(dec):
+    """The shares of the page stream that the attention workgroups get can be set per workgroup; any weights give the
+    same answer within tolerance, and the same weights the same bytes."""
+    import paper_2507_01663_amd as ra
+    from gpu_util import compare
+    p = workload.make_problem("mid7b", seed=4)
+    ref = oracle.decode(p)
+    n = ra.rollout_attn_wave_count(dec.ctx, ra.RA_KV_BF16, p.D)
+    assert n > 0 and n % 8 == 0
+    rng = np.random.default_rng(8)
+    first = None
+    try:
+        for w in (rng.integers(700, 1401, size=n), rng.integers(700, 1401, size=n), np.full(n, 1000)):
+            ra.rollout_attn_set_wave_weights(dec.ctx, w, ra.RA_KV_BF16, p.D)
+            dp = run(dec, p)
+            compare(*dp.results(), *ref, "random wave weights")
+            dp2 = run(dec, p)
+            torch.cuda.synchronize()
+            assert torch.equal(dp.out.view(torch.int16), dp2.out.view(torch.int16)) and torch.equal(dp.lse, dp2.lse)
+        with pytest.raises(ra.RolloutAttnError):
+            ra.rollout_attn_set_wave_weights(dec.ctx, np.full(n - 1, 1000), ra.RA_KV_BF16, p.D)
+    finally:
+        ra.rollout_attn_set_wave_weights(dec.ctx, np.full(n, 1000), ra.RA_KV_BF16, p.D)
