@@ -300,17 +300,25 @@ class ra_schedule_info(ctypes.Structure):
 
 
 class Decoder:
-    """A context plus a cached workspace tensor on one device."""
+    """A context plus a cached workspace tensor on one device.  The workspace grows when a larger problem arrives;
+    the tensors it outgrew stay alive until close(), because work already enqueued (or a HIP graph captured earlier)
+    may still use them.  A captured graph and a schedule that RA_FLAG_REUSE_SCHEDULE reuses are tied to the workspace
+    they were made with: after the workspace has grown, capture or schedule again."""
 
     def __init__(self, device_ordinal=0):
         self.device_ordinal = device_ordinal
         self.ctx = rollout_attn_create(device_ordinal)
         self._ws = None
+        self._retired = []
 
     def close(self):
         if self.ctx is not None:
+            import torch
+            torch.cuda.synchronize(self.device_ordinal)      # nothing enqueued may outlive the buffers
             rollout_attn_destroy(self.ctx)
             self.ctx = None
+            self._ws = None
+            self._retired = []
 
     def __del__(self):
         try:
@@ -322,6 +330,8 @@ class Decoder:
         import torch
         need = rollout_attn_workspace_size(self.ctx, problem)
         if self._ws is None or self._ws.numel() < need:
+            if self._ws is not None:
+                self._retired.append(self._ws)
             self._ws = torch.empty(need, dtype=torch.uint8, device="cuda:%d" % self.device_ordinal)
         return self._ws
 

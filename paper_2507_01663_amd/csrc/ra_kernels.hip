@@ -158,6 +158,11 @@ struct Cuts {
     long V;              // S0 * waves >= U: the length the shares refer to
     const int32_t *cum;  // [waves + 1], cum[0] = 0, cum[waves] = 2^20, increasing
     __device__ long start(int c) const { return (V * cum[c]) >> 20; }
+    __device__ int at(int share) const // the cost unit at a point of the share table
+    {
+        const long v = (V * share) >> 20;
+        return v < U ? (int)v : U;
+    }
     __device__ int lo(int c) const
     {
         const long v = start(c);
@@ -374,13 +379,6 @@ __global__ __launch_bounds__(kPlanThreads) void plan_rows_kernel(Launch a)
 }
 
 // Second half of the schedule: the cuts, every span's work list, and the merge descriptors.
-
-// cut.lo(c) for a wave-uniform c, with the table read through the scalar cache.
-__device__ __forceinline__ int uniform_cut(const Cuts &cut, int c)
-{
-    const long v = (cut.V * uniform_load(cut.cum, c)) >> 20;
-    return v < cut.U ? (int)v : cut.U;
-}
 
 __device__ __forceinline__ void make_cuts(const Launch &a, int U, Cuts &cut, const int32_t *cum)
 {
@@ -996,16 +994,20 @@ __device__ __forceinline__ void carve_wave_tables(WaveTables &T, void *base, int
     T.rs = take(rows + 1);
 }
 
-// Exclusive scan of x over the 64 lanes; total: the sum.
+// Exclusive scan of x over the 64 lanes; total: the sum.  Data-parallel-primitive moves on the VALU (no LDS trip per
+// step): shifts by 1, 2, 4, 8 inside the rows of 16 lanes, then each row's last lane broadcast into the next row
+// (rows 1 and 3) and lane 31 into the upper half; lanes without a source add 0.
 __device__ __forceinline__ int wave_scan(int x, int lane, int &total)
 {
     int v = x;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const int y = __shfl_up(v, d);
-        if (lane >= d) v += y;
-    }
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false); // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false); // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false); // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false); // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false); // row_bcast:15
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false); // row_bcast:31
     total = __builtin_amdgcn_readlane(v, 63);
+    (void)lane;
     return v - x;
 }
 
@@ -1299,6 +1301,8 @@ template <int D, int KVB, int NST, int NPEND, bool SELF> __device__ __forceinlin
     SpanPlan sp;
     sp.done = !SELF;
     bool first_pass = true;
+    // the wave's two cut points of the share table: asked for now, needed when the rows are known
+    const int share_lo = SELF ? uniform_load(a.wave_cum, c) : 0, share_hi = SELF ? uniform_load(a.wave_cum, c + 1) : 0;
     do {
         if (SELF) {
             // plan: the rows, the cut, this span's list (the ring is idle: its LDS holds the tables meanwhile)
@@ -1313,7 +1317,7 @@ template <int D, int KVB, int NST, int NPEND, bool SELF> __device__ __forceinlin
             if (first_pass) {
                 Cuts cut;
                 make_cuts(a, a.Hkv * ufl(T.rs[sp.nR]), cut, a.wave_cum);
-                sp.lo = uniform_cut(cut, c), sp.hi = uniform_cut(cut, c + 1);
+                sp.lo = cut.at(share_lo), sp.hi = cut.at(share_hi);
                 // the span's first item: the last row that starts at or before the span's first unit (starts do not decrease)
                 int at_or_before = 0;
 #pragma unroll 1
