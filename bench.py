@@ -230,8 +230,9 @@ def main():
                    "kv_tokens_per_step": int(sum(p.kv_tokens() for p in probs) / len(probs))},
         "phases_ms": {"schedule": round(float(phase[0]), 5), "attention": round(float(phase[1]), 5),
                       "merge": round(float(phase[2]), 5),
-                      "note": "HIP events around the library's launches; batches of up to 512 sequences are scheduled inside the "
-                              "attention kernel, so `schedule` is then the cost of two event records with nothing between them"},
+                      "note": "HIP events around the library's launches (each record adds a few microseconds to the phase it "
+                              "ends); batches of up to 512 sequences are scheduled inside the attention kernel: no schedule "
+                              "launch, `schedule` is 0 and its time is part of `attention`"},
         "roofline": {"bound": "hbm", "kernel": "attention_kernel", "achieved": round(att_gbps, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(att_gbps / HBM_PEAK_GBPS, 4),
                      "traffic": recorded_traffic(name + ("_noshare" if args.no_sharing else ""))},

@@ -322,7 +322,9 @@ ra_status rollout_attn_debug_stream(ra_ctx *ctx, const void *buf, size_t buf_byt
 
 /* Per-kernel timing for benchmarks.  While enabled, rollout_attn_decode records HIP events on its stream
  * around its three phases (schedule, attention, merge); rollout_attn_get_timing waits for the events of the
- * most recent decode call and returns the three durations in milliseconds.  Off by default: the events cost
+ * most recent decode call and returns the three durations in milliseconds (schedule: 0 when that call launched
+ * no schedule kernel, because its attention workgroups planned their spans themselves or the schedule was
+ * reused; the attention phase then starts at the call's first event).  Off by default: the events cost
  * a little time between kernels.  The numbers are measurements, not part of the result (the decode step is
  * memory-bound, paper Sec. 2.1.1, so the attention phase is the one to watch). */
 ra_status rollout_attn_set_timing(ra_ctx *ctx, int enable);

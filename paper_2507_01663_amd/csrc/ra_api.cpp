@@ -28,7 +28,7 @@ struct ra_ctx {
     int self_plan; // attention waves may plan their spans themselves (no schedule kernel)
     int32_t *host_flags; // pinned, for RA_FLAG_VALIDATE
     int timing;          // record events around the phases
-    int timed;           // a decode call has recorded them
+    int timed;           // a decode call has recorded them (2: with a schedule launch between the first two)
     hipEvent_t ev[4];
     char err[512];
 };
@@ -298,13 +298,14 @@ static ra_status enqueue_decode(ra_ctx *c, const ra_problem *p, const ra::Launch
     if (e == hipSuccess && tm) e = hipEventRecord(c->ev[0], s);
     // no schedule kernel when the batch's tables fit in the attention waves' LDS (they plan their spans themselves)
     const bool reuse = (p->flags & RA_FLAG_REUSE_SCHEDULE) != 0;
-    if (e == hipSuccess && !reuse && !a.self_plan) e = ra::launch_plan(a, s);
-    if (e == hipSuccess && tm) e = hipEventRecord(c->ev[1], s);
+    const bool planned = !reuse && !a.self_plan;
+    if (e == hipSuccess && planned) e = ra::launch_plan(a, s);
+    if (e == hipSuccess && tm && planned) e = hipEventRecord(c->ev[1], s); // (no launch: no phase, no event)
     if (e == hipSuccess) e = ra::launch_attention(a, s);
     if (e == hipSuccess && tm) e = hipEventRecord(c->ev[2], s);
     if (e == hipSuccess) e = ra::launch_merge(a, s);
     if (e == hipSuccess && tm) e = hipEventRecord(c->ev[3], s);
-    if (e == hipSuccess && tm) c->timed = 1;
+    if (e == hipSuccess && tm) c->timed = planned ? 2 : 1;
     if (prev != c->device) (void)hipSetDevice(prev);
     if (e != hipSuccess) { set_err(c, "HIP: %s", hipGetErrorString(e)); return RA_ERR_DEVICE; }
     return RA_OK;
@@ -560,7 +561,14 @@ ra_status rollout_attn_get_timing(ra_ctx *c, float ms[3])
     if (!c || !ms) { set_err(c, "ctx or phase_ms is NULL"); return RA_ERR_INVALID_ARG; }
     if (!c->timed) { set_err(c, "no decode call has been timed (rollout_attn_set_timing first)"); return RA_ERR_INVALID_ARG; }
     hipError_t e = hipEventSynchronize(c->ev[3]);
-    for (int i = 0; i < 3 && e == hipSuccess; i++) e = hipEventElapsedTime(&ms[i], c->ev[i], c->ev[i + 1]);
+    if (c->timed == 2) {
+        for (int i = 0; i < 3 && e == hipSuccess; i++) e = hipEventElapsedTime(&ms[i], c->ev[i], c->ev[i + 1]);
+    } else {
+        // no schedule kernel was launched in that call: the attention phase starts at the first event
+        ms[0] = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms[1], c->ev[0], c->ev[2]);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms[2], c->ev[2], c->ev[3]);
+    }
     if (e != hipSuccess) { set_err(c, "HIP: %s", hipGetErrorString(e)); return RA_ERR_DEVICE; }
     return RA_OK;
 }

@@ -197,6 +197,27 @@ def test_parity_with_the_schedule_kernels(dec_sched, dec, name, kv):
     assert torch.equal(a.out.view(torch.int16), b.out.view(torch.int16)) and torch.equal(a.lse, b.lse)
 
 
+def test_phase_timing_reports_only_the_launches_made(dec_sched, dec):
+    """The per-phase event timing: a batch planned inside the attention kernel has no schedule phase (0), the same
+    batch through the schedule kernels has one; attention and merge always do.  Results are not touched by it."""
+    import paper_2507_01663_amd as ra
+    p = workload.make_problem("mid7b", seed=0)
+    plain = run(dec, p)
+    torch.cuda.synchronize()
+    for d, has_schedule in ((dec, False), (dec_sched, True)):
+        with pytest.raises(ra.RolloutAttnError):
+            ra.rollout_attn_get_timing(d.ctx)             # nothing timed yet
+        ra.rollout_attn_set_timing(d.ctx, True)
+        try:
+            timed = run(d, p)
+            ms = ra.rollout_attn_get_timing(d.ctx)
+        finally:
+            ra.rollout_attn_set_timing(d.ctx, False)
+        assert len(ms) == 3 and ms[1] > 0 and ms[2] > 0 and all(x < 100 for x in ms), ms
+        assert (ms[0] > 0) == has_schedule, ms
+        assert torch.equal(timed.out.view(torch.int16), plain.out.view(torch.int16)) and torch.equal(timed.lse, plain.lse)
+
+
 @pytest.fixture(scope="module")
 def dec_few_waves():
     """A context with one attention workgroup per compute unit instead of four: four times longer spans."""
