@@ -260,11 +260,26 @@ def main():
         ev1.record(stream)
         torch.cuda.synchronize()
         ceil[label] = n / (ev0.elapsed_time(ev1) / 10) / 1e6
+    # the same scattered stream with its last eighth (and quarter) handed out at run time in chunks of 4 entries
+    # (64 KB, the size of eight pages of one kv head): does evening out the waves' end times buy anything?
+    tail = {}
+    for frac in (8, 4):
+        static = entries - entries // frac
+        for _ in range(3):
+            n = ra.rollout_attn_debug_stream_tail(dec.ctx, ctypes.c_void_p(buf.data_ptr()), buf.numel(), entries, static, 4, sp)
+        ev0.record(stream)
+        for _ in range(10):
+            n = ra.rollout_attn_debug_stream_tail(dec.ctx, ctypes.c_void_p(buf.data_ptr()), buf.numel(), entries, static, 4, sp)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        tail["last_1/%d_ticketed_GBps" % frac] = round(n / (ev0.elapsed_time(ev1) / 10) / 1e6, 1)
     del buf
     out["stream_ceiling"] = {"GBps": round(ceil["gather_4KB_tiles"], 1), "sequential_GBps": round(ceil["sequential"], 1), "unit": "GB/s",
                              "pct_of_hbm_peak": round(100 * ceil["gather_4KB_tiles"] / HBM_PEAK_GBPS, 2),
                              "note": "read-only probe with the attention kernel's grid and LDS ring, no arithmetic: 4 KB tiles from "
-                                     "scattered places (the kernel's own pattern) and from consecutive ones; measured in this run"}
+                                     "scattered places (the kernel's own pattern) and from consecutive ones; measured in this run",
+                             "ticketed_tail": dict(tail, note="the scattered stream again, its end handed out at run time through an "
+                                                              "atomic counter in chunks of 64 KB instead of split evenly beforehand")}
     out["pct_of_ceiling"] = round(100 * gbps / ceil["gather_4KB_tiles"], 2)
     out["roofline"]["frac_of_ceiling"] = round(att_gbps / ceil["gather_4KB_tiles"], 4)
 

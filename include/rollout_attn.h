@@ -320,6 +320,16 @@ ra_status rollout_attn_set_wave_weights(ra_ctx *ctx, int32_t kv_dtype, int32_t h
 ra_status rollout_attn_debug_stream(ra_ctx *ctx, const void *buf, size_t buf_bytes, int32_t granule_bytes, int32_t scattered,
                                     int32_t entries_per_wave, void *hip_stream, size_t *bytes_read);
 
+/* The same probe (4096-byte pieces, scattered) with the end of the stream handed out at run time: every wave
+ * streams static_entries entries of its own, then the waves draw tickets from a counter in the context and a
+ * ticket is the next chunk_entries entries of what is left of waves * entries_per_wave, until none is left.  For
+ * benchmarks that ask whether evening out the waves' end times that way would buy anything over the static split of
+ * the page stream that the attention kernel uses (paper Sec. 4.4 balances statically too); nothing else calls it.
+ * 0 <= static_entries < entries_per_wave <= 65536, chunk_entries in 1..1024; buf as above.  Launches that use the
+ * ticket counter of one context must not overlap.  Enqueued on hip_stream; the caller times it. */
+ra_status rollout_attn_debug_stream_tail(ra_ctx *ctx, const void *buf, size_t buf_bytes, int32_t entries_per_wave,
+                                         int32_t static_entries, int32_t chunk_entries, void *hip_stream, size_t *bytes_read);
+
 /* Per-kernel timing for benchmarks.  While enabled, rollout_attn_decode records HIP events on its stream
  * around its three phases (schedule, attention, merge); rollout_attn_get_timing waits for the events of the
  * most recent decode call and returns the three durations in milliseconds (schedule: 0 when that call launched

@@ -105,6 +105,9 @@ def load_library():
     lib.rollout_attn_debug_stream.restype = ctypes.c_int
     lib.rollout_attn_debug_stream.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32,
                                               ctypes.c_int32, ctypes.c_void_p, P(ctypes.c_size_t)]
+    lib.rollout_attn_debug_stream_tail.restype = ctypes.c_int
+    lib.rollout_attn_debug_stream_tail.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32,
+                                                   ctypes.c_int32, ctypes.c_void_p, P(ctypes.c_size_t)]
     lib.rollout_attn_set_timing.restype = ctypes.c_int
     lib.rollout_attn_set_timing.argtypes = [ctypes.c_void_p, ctypes.c_int]
     lib.rollout_attn_get_timing.restype = ctypes.c_int
@@ -216,6 +219,14 @@ def rollout_attn_debug_stream(ctx, buf_ptr, buf_bytes, granule_bytes, scattered,
     n = ctypes.c_size_t()
     _check(load_library().rollout_attn_debug_stream(ctx, buf_ptr, buf_bytes, granule_bytes, int(bool(scattered)), entries_per_wave,
                                                     hip_stream, ctypes.byref(n)), ctx)
+    return int(n.value)
+
+
+def rollout_attn_debug_stream_tail(ctx, buf_ptr, buf_bytes, entries_per_wave, static_entries, chunk_entries, hip_stream=None):
+    """Enqueues the streaming probe with a ticketed tail; returns the bytes the launch reads."""
+    n = ctypes.c_size_t()
+    _check(load_library().rollout_attn_debug_stream_tail(ctx, buf_ptr, buf_bytes, entries_per_wave, static_entries, chunk_entries,
+                                                         hip_stream, ctypes.byref(n)), ctx)
     return int(n.value)
 
 

@@ -24,6 +24,7 @@ struct ra_ctx {
     int cost_item;   // ... of a segment, on top of its pages
     int xcd_w[8];              // default share of the page stream per accelerator die, per mille of the mean
     int32_t *wave_cum[2][2];   // device: running sums of the workgroups' shares, [e4m3 KV][D == 128], kMaxWaves + 1 each
+    uint32_t *tickets;         // device: the streaming probe's ticket counter (cleared by every launch that uses it)
     void *zeros;  // 256 bytes of zeros on the device
     int self_plan; // attention waves may plan their spans themselves (no schedule kernel)
     int32_t *host_flags; // pinned, for RA_FLAG_VALIDATE
@@ -197,6 +198,7 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
     }
     if (e == hipSuccess) { c->num_cus = prop.multiProcessorCount; e = hipMalloc(&c->zeros, 256); }
     if (e == hipSuccess) e = hipMemset(c->zeros, 0, 256);
+    if (e == hipSuccess) e = hipMalloc((void **)&c->tickets, 256);
     if (e == hipSuccess) e = hipHostMalloc((void **)&c->host_flags, 64, hipHostMallocDefault);
     for (int i = 0; i < 4 && e == hipSuccess; i++) e = hipEventCreate(&c->ev[i]);
     for (int f = 0; f < 2; f++)
@@ -236,6 +238,7 @@ void rollout_attn_destroy(ra_ctx *c)
 {
     if (!c) return;
     if (c->zeros) (void)hipFree(c->zeros);
+    if (c->tickets) (void)hipFree(c->tickets);
     for (int f = 0; f < 2; f++)
         for (int d = 0; d < 2; d++)
             if (c->wave_cum[f][d]) (void)hipFree(c->wave_cum[f][d]);
@@ -545,6 +548,33 @@ ra_status rollout_attn_debug_stream(ra_ctx *c, const void *buf, size_t buf_bytes
     if (prev != c->device) (void)hipSetDevice(prev);
     if (e != hipSuccess) { set_err(c, "HIP: %s", hipGetErrorString(e)); return RA_ERR_DEVICE; }
     if (bytes_read) *bytes_read = (size_t)waves * entries_per_wave * 16384;
+    return RA_OK;
+}
+
+ra_status rollout_attn_debug_stream_tail(ra_ctx *c, const void *buf, size_t buf_bytes, int32_t entries_per_wave, int32_t static_entries,
+                                         int32_t chunk_entries, void *stream, size_t *bytes_read)
+{
+    if (!c) { set_err(nullptr, "ctx is NULL"); return RA_ERR_INVALID_ARG; }
+    const bool pow2 = buf_bytes && !(buf_bytes & (buf_bytes - 1));
+    if (!buf || ((uintptr_t)buf & 15) || !pow2 || buf_bytes < 16384 || buf_bytes > ((size_t)1 << 40) || entries_per_wave < 1 ||
+        entries_per_wave > 65536 || static_entries < 0 || static_entries >= entries_per_wave || chunk_entries < 1 || chunk_entries > 1024) {
+        set_err(c, "stream probe with a ticketed tail: buf must be 16-byte aligned, buf_bytes a power of two of at least 16384, "
+                   "0 <= static_entries < entries_per_wave <= 65536, chunk_entries in 1..1024");
+        return RA_ERR_INVALID_ARG;
+    }
+    const int waves = c->waves[0][1];
+    // the tail: what the static parts leave, in whole chunks (a last partial chunk is rounded up)
+    const int64_t tail = (int64_t)waves * (entries_per_wave - static_entries);
+    const int64_t tickets = (tail + chunk_entries - 1) / chunk_entries;
+    int prev = 0;
+    hipError_t e = hipGetDevice(&prev);
+    if (e == hipSuccess && prev != c->device) e = hipSetDevice(c->device);
+    if (e == hipSuccess)
+        e = ra::launch_stream_probe(buf, buf_bytes, 4096, 1, static_entries, waves, (hipStream_t)stream, chunk_entries, (uint32_t)tickets,
+                                    c->tickets);
+    if (prev != c->device) (void)hipSetDevice(prev);
+    if (e != hipSuccess) { set_err(c, "HIP: %s", hipGetErrorString(e)); return RA_ERR_DEVICE; }
+    if (bytes_read) *bytes_read = ((size_t)waves * static_entries + (size_t)tickets * chunk_entries) * 16384;
     return RA_OK;
 }
 

@@ -93,7 +93,7 @@ bool can_self_plan(int D, int kv_fp8, int stages, int B, int num_groups, int mem
 // Streams entries * 16 KB per wave from buf (a power of two of bytes) through the attention kernel's ring, in pieces of
 // `granule` bytes (1024 .. 16384, a power of two), scattered over the buffer or consecutive.
 hipError_t launch_stream_probe(const void *buf, size_t buf_bytes, int granule, int scattered, int entries, int waves, hipStream_t s,
-                               long long *clocks = nullptr /* [waves] duration of every wave in 10 ns ticks */);
+                               int chunk = 0, uint32_t tickets = 0, uint32_t *counter = nullptr, long long *clocks = nullptr);
 hipError_t launch_validate(const Launch &a, hipStream_t s);
 hipError_t launch_plan(const Launch &a, hipStream_t s);
 hipError_t launch_attention(const Launch &a, hipStream_t s);

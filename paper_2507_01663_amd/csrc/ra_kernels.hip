@@ -1521,17 +1521,21 @@ hipError_t launch_attention(const Launch &a, hipStream_t s)
 // a fixed permutation of the buffer's granules (scattered) or consecutive (sequential: the grid sweeps the buffer).
 // ------------------------------------------------------------------------------------------------------
 
+// With chunk > 0 only the first `entries` entries of a wave are its own; after them the waves draw tickets from
+// *counter (zero at launch) and ticket t streams the `chunk` entries that follow the static part at t * chunk, until
+// the tickets run out: a page stream whose tail is handed out at run time, to be timed against the static split.
 __global__ __launch_bounds__(64) void stream_probe_kernel(const uint8_t *__restrict__ buf, uint32_t granule_mask, int granule_shift,
-                                                           int scattered, int entries, long long *clocks)
+                                                           int scattered, int entries, int chunk, uint32_t tickets, uint32_t *counter,
+                                                           long long *clocks)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     const uint32_t lds_addr = (uint32_t)(uintptr_t)lds;
     const int lane = threadIdx.x;
     const long long t0 = wall_clock64();
     const int per = 14 - granule_shift; // log2 of the pieces per entry
-    // entry s of this wave: number w + s * waves in the sweep; its piece i is granule (that number << per) + i
-    auto issue = [&](int s) {
-        const uint32_t first = ((uint32_t)blockIdx.x + (uint32_t)s * gridDim.x) << per;
+    // entry number e of the sweep into ring slot `slot`: its piece i is granule (e << per) + i
+    auto issue = [&](uint32_t e, int slot) __attribute__((always_inline)) {
+        const uint32_t first = e << per;
 #pragma unroll
         for (int n = 0; n < 16; n++) {
             // load n moves 1 KB: piece (n * 1024) >> granule_shift, offset inside the piece the rest
@@ -1539,30 +1543,48 @@ __global__ __launch_bounds__(64) void stream_probe_kernel(const uint8_t *__restr
             uint32_t g = first + piece;
             if (scattered) g = g * 2654435761u + 12345u; // odd multiplier: a permutation modulo a power of two
             const uint8_t *src = buf + ((size_t)(g & granule_mask) << granule_shift) + within;
-            dma16_base((uint32_t)(16 * lane), src, lds_addr + (s & 1) * 16384 + 1024 * n);
+            dma16_base((uint32_t)(16 * lane), src, lds_addr + (slot & 1) * 16384 + 1024 * n);
         }
     };
-    issue(0);
-    for (int s = 0; s < entries; s++) {
-        if (s + 1 < entries) {
-            issue(s + 1);
-            wait_vmcnt<16>();
-        } else {
-            wait_vmcnt<0>();
+    // n entries first, first + step, ... through the two-slot ring; drained at the end
+    auto stream = [&](uint32_t first, uint32_t step, int n) __attribute__((always_inline)) {
+        if (n <= 0) return;
+        issue(first, 0);
+        for (int s = 0; s < n; s++) {
+            if (s + 1 < n) {
+                issue(first + (uint32_t)(s + 1) * step, s + 1);
+                wait_vmcnt<16>();
+            } else {
+                wait_vmcnt<0>();
+            }
+        }
+    };
+    // wave w's own entries: numbers w, w + waves, ...
+    stream(blockIdx.x, gridDim.x, entries);
+    if (chunk > 0) {
+        for (;;) { // every wave leaves when the counter has passed the last ticket
+            uint32_t t = 0;
+            if (lane == 0) t = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            t = __builtin_amdgcn_readfirstlane(t);
+            if (t >= tickets) break;
+            stream(gridDim.x * (uint32_t)entries + t * (uint32_t)chunk, 1u, chunk);
         }
     }
     if (clocks && lane == 0) clocks[blockIdx.x] = wall_clock64() - t0;
 }
 
+__global__ void clear_word_kernel(uint32_t *p) { *p = 0; }
+
 hipError_t launch_stream_probe(const void *buf, size_t buf_bytes, int granule, int scattered, int entries, int waves, hipStream_t s,
-                               long long *clocks)
+                               int chunk, uint32_t tickets, uint32_t *counter, long long *clocks)
 {
     hipError_t e = hipFuncSetAttribute((const void *)stream_probe_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 40960);
     if (e != hipSuccess) return e;
     int shift = 0;
     while ((1 << shift) < granule) shift++;
+    if (chunk > 0) hipLaunchKernelGGL(clear_word_kernel, dim3(1), dim3(1), 0, s, counter);
     hipLaunchKernelGGL(stream_probe_kernel, dim3(waves), dim3(64), 40960, s, (const uint8_t *)buf, (uint32_t)((buf_bytes >> shift) - 1), shift,
-                       scattered, entries, clocks);
+                       scattered, entries, chunk, tickets, counter, clocks);
     return hipGetLastError();
 }
 

@@ -20,7 +20,7 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     lib = ra.load_library()
     names = declared_symbols()
-    assert len(names) == 19, names
+    assert len(names) == 20, names
     for n in names:
         assert getattr(lib, n) is not None
     assert ra.rollout_attn_abi_version() == 1

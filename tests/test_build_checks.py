@@ -51,6 +51,15 @@ def test_no_scratch_and_no_full_drain_in_the_page_loop(isa):
         assert re.search(r"s_waitcnt vmcnt\([1-9][0-9]*\)", body), name
 
 
+def test_streaming_probe_is_one_flat_kernel(isa):
+    """The probe's figure is reported as the ceiling the attention kernel is judged against: its loads must be the ring's
+    direct global-to-LDS loads, with nothing called and nothing on the stack."""
+    m = re.search(r"^(_ZN2ra19stream_probe_kernel\w+):(.*?)s_endpgm", isa, flags=re.S | re.M)
+    body = m.group(2)
+    assert body.count("global_load_lds_dwordx4") >= 32 and "s_swappc" not in body and "scratch_" not in body
+    assert descriptors(isa, r"_ZN2ra19stream_probe_kernel")[m.group(1)][1] == 0
+
+
 def test_e4m3_kernels_fit_two_waves_per_simd(isa):
     """The e4m3 decode kernels are scheduled for two waves on a SIMD (six workgroups per compute unit at head dim
     128): that holds only while they stay within half of the 512 registers a lane has, without scratch."""
