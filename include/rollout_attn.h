@@ -135,6 +135,10 @@ uint32_t rollout_attn_abi_version(void);
  *   ROLLOUT_ATTN_SELF_PLAN=0        always launch the schedule kernels (default: batches of up to 512 sequences and
  *                                   511 groups are scheduled by the attention workgroups themselves, each for its own
  *                                   share of the work, which saves a kernel; the schedule is the same either way)
+ *   ROLLOUT_ATTN_PREFILL_WGS_PER_DIE=0..64   prefill: one workgroup per block of 256 query rows (0), or that many
+ *                                   per die (at most one per compute unit) that stay and take block after block,
+ *                                   loading the next one's inputs under the current one's last keys; default: one
+ *                                   per compute unit for prompts of up to 512 tokens, one per block for longer ones
  *   ROLLOUT_ATTN_VERBOSE            print the die weights to stderr */
 ra_status rollout_attn_create(ra_ctx **ctx, int device_ordinal);
 

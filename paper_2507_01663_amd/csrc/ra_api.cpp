@@ -25,6 +25,7 @@ struct ra_ctx {
     int xcd_w[8];              // default share of the page stream per accelerator die, per mille of the mean
     int32_t *wave_cum[2][2];   // device: running sums of the workgroups' shares, [e4m3 KV][D == 128], kMaxWaves + 1 each
     uint32_t *tickets;         // device: the streaming probe's ticket counter (cleared by every launch that uses it)
+    int prefill_stay;          // -1: the prefill launch chooses by prompt length; else ROLLOUT_ATTN_PREFILL_WGS_PER_DIE
     void *zeros;  // 256 bytes of zeros on the device
     int self_plan; // attention waves may plan their spans themselves (no schedule kernel)
     int32_t *host_flags; // pinned, for RA_FLAG_VALIDATE
@@ -178,6 +179,11 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
             if (ok)
                 for (int x = 0; x < 8; x++) c->xcd_w[x] = v[x];
         }
+    }
+    c->prefill_stay = -1;
+    if (const char *ev = getenv("ROLLOUT_ATTN_PREFILL_WGS_PER_DIE")) {
+        int v = atoi(ev);
+        if (v >= 0 && v <= 64) c->prefill_stay = v;
     }
     c->self_plan = 1;
     if (const char *ev = getenv("ROLLOUT_ATTN_SELF_PLAN")) c->self_plan = atoi(ev) != 0;
@@ -480,6 +486,8 @@ ra_status rollout_attn_prefill(ra_ctx *c, const ra_prefill *p, void *stream)
     a.cu = p->cu_seqlens;
     a.scale_log2 = p->softmax_scale * 1.4426950408889634f;
     a.out = (uint16_t *)p->out; a.lse = p->lse; a.zeros = c->zeros;
+    a.num_cus = c->num_cus;
+    a.stay = c->prefill_stay;
     if (p->k_pool) {
         const int es = p->kv_dtype == RA_KV_FP8_E4M3 ? 1 : 2;
         a.kv_fp8 = es == 1; a.num_pages = p->num_pages;

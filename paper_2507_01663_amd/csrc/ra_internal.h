@@ -61,6 +61,9 @@ struct Launch {
 // Prompt prefill: packed prompts, their causal attention, and where their K and V rows go in the cache.
 struct PrefillLaunch {
     int32_t num_prompts, max_len, Hq, Hkv, D, G;
+    int32_t num_cus;             // compute units of the device
+    int32_t stay;                // prefill workgroups per die that stay and take block after block (at most one per
+                                 // compute unit); 0: one workgroup per block; -1: chosen by prompt length
     const uint16_t *q, *k, *v;   // bf16 [T][Hq][D], [T][Hkv][D]
     const int32_t *cu;           // [num_prompts + 1] first token of each prompt
     float scale_log2;            // softmax_scale * log2(e)

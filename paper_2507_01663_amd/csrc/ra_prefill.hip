@@ -223,34 +223,71 @@ __device__ __forceinline__ void pf_scores(const uint8_t *k_stage, const PfLane<D
     sn += s2;
 }
 
-// One workgroup per (prompt, head, block of 256 query rows).  max_len is the host's upper bound of a prompt's
-// length; blocks past a prompt's real length leave at once.
-template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel(PrefillLaunch a)
+// A block: 256 consecutive query rows of one (prompt, head), with the keys 0 .. its last row.  All fields are the same
+// in every lane.
+struct PfBlock {
+    int h, kvh, q0, t0, len; // head, kv head, first query row; first token and length of the prompt
+    int nst, nchunks;        // stages of 32 keys, chunks of two stages
+};
+
+// Workgroups are dealt to the eight dies round-robin, and each die has its own L2.  All blocks of a (prompt, kv
+// head) pair, which read the same K and V, therefore go to one die: die x takes the pairs x, x + 8, ... one after
+// the other, each with its query blocks from the longest down and the heads of the kv head together.  `turn` counts
+// a die's blocks in that order; false past the die's last pair.  A block past its prompt's length has no stages.
+__device__ __forceinline__ bool pf_block_of(const PrefillLaunch &a, int die, int turn, PfBlock &b)
+{
+    const int nqb = (a.max_len + kPfBlock - 1) / kPfBlock;
+    const int per_pair = nqb * a.G;
+    const int pair = (turn / per_pair) * 8 + die, r = turn % per_pair;
+    if (pair >= a.num_prompts * a.Hkv) return false;
+    const int g = pair / a.Hkv;
+    b.kvh = pair % a.Hkv;
+    b.h = b.kvh * a.G + r % a.G;
+    b.q0 = (nqb - 1 - r / a.G) * kPfBlock;
+    b.t0 = uniform_load(a.cu, g);
+    b.len = uniform_load(a.cu, g + 1) - b.t0;
+    int kend = b.q0 + kPfBlock;
+    kend = kend < b.len ? kend : b.len;
+    b.nst = b.q0 < b.len ? (kend + 31) >> 5 : 0;
+    b.nchunks = (b.nst + 1) >> 1;
+    return true;
+}
+
+// The first block with stages at or after `turn` among the turns turn, turn + step, ... of the die (turn comes back
+// as that block's turn); false when the die has none left.
+__device__ __forceinline__ bool pf_next_block(const PrefillLaunch &a, int die, int &turn, int step, PfBlock &b)
+{
+    while (pf_block_of(a, die, turn, b)) {
+        if (b.nst > 0) return true;
+        turn += step;
+    }
+    return false;
+}
+
+// STAY: the workgroups stay: gridDim.x / 8 of them per die, and workgroup i of a die takes the die's blocks i, i + that
+// many, ...  K and V of one block after the other stream through one ring, so the first chunks of the next block
+// (and its query rows, into registers) are loaded while the last stages of the current one are being multiplied: a
+// block starts without a trip to memory.  Without STAY a workgroup takes the one block its number names (the launch
+// has one workgroup per block then).  max_len is the host's upper bound of a prompt's length.
+template <int D, bool STAY> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel(PrefillLaunch a)
 {
     using G = Geo<D, 2>;
-    constexpr int NSL = kPfSlots;           // ring slots; a stage s lives at (s % (2 NSL)) * G::kStage
+    constexpr int NSL = kPfSlots;           // ring slots of one chunk; stage number s (counted over all the blocks of
+                                            // the workgroup) lives at (s % (2 NSL)) * G::kStage
     static_assert((NSL & (NSL - 1)) == 0, "slot arithmetic by masking");
     extern __shared__ __attribute__((aligned(16384))) uint8_t lds[]; // the step forms LDS addresses by XOR
     const uint32_t lds_addr = (uint32_t)(uintptr_t)lds;
     const int lane = threadIdx.x & 63, n = lane & 31, hh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const int die = blockIdx.x & 7, step = gridDim.x >> 3;
 
-    // Workgroups are dealt to the eight dies round-robin, and each die has its own L2.  All workgroups of a
-    // (prompt, kv head) pair, which read the same K and V, therefore go to one die: die x takes the pairs x, x + 8,
-    // ... one after the other, each with its query blocks from the longest down and the heads of the kv head together.
-    const int nqb = (a.max_len + kPfBlock - 1) / kPfBlock;
-    const int per_pair = nqb * a.G;
-    const int die = blockIdx.x & 7, turn = blockIdx.x >> 3;
-    const int pair = (turn / per_pair) * 8 + die, r = turn % per_pair;
-    if (pair >= a.num_prompts * a.Hkv) return; // the whole workgroup
-    const int g = pair / a.Hkv, kvh = pair % a.Hkv;
-    const int h = kvh * a.G + r % a.G;
-    const int q0 = (nqb - 1 - r / a.G) * kPfBlock;
-    const int t0 = uniform_load(a.cu, g), len = uniform_load(a.cu, g + 1) - t0;
-    if (q0 >= len) return; // the whole workgroup
-    int kend = q0 + kPfBlock;
-    kend = kend < len ? kend : len;
-    const int nst = (kend + 31) >> 5;
+    // two cursors over the same sequence of blocks: the one being multiplied, and the one whose chunks are being loaded
+    PfBlock cb, lb;
+    int cturn = blockIdx.x >> 3;
+    if (!pf_next_block(a, die, cturn, step, cb)) return; // the whole workgroup
+    int lturn = cturn;
+    lb = cb;
+    bool l_ok = true;
 
     LaneConst<D, 2> lc;
     lane_setup<D, 2>(lc, lane, a.Hkv * D * 2);
@@ -260,150 +297,194 @@ template <int D> __global__ __launch_bounds__(64 * kPfWaves) void prefill_kernel
     // waves 0..3 load the chunks {K0 K1 V0 V1 | K2 K3 V2 V3}: wave w brings tile w of both stages.  (Waves 4..7, the
     // second on each SIMD, are the ones that arrive last at the barriers; they issue no loads.)
     constexpr int DPW = 2 * G::kDmaPerTile; // loads of a loading wave per chunk
-    const int nchunks = (nst + 1) >> 1;
     const int tile = wave & 3;
     const bool loader = wave < 4;
-    int tok = kPage * (tile & 1); // first key of the wave's tile in the chunk to load next
     const int64_t tok_bytes = (int64_t)a.Hkv * D * 2;
-    const uint8_t *src = (const uint8_t *)((tile < 2 ? a.k : a.v) + ((int64_t)(t0 + tok) * a.Hkv + kvh) * D);
     const uint32_t dst = lds_addr + tile * G::kTile;
-    int issued = 0;
-    auto issue = [&]() {
+    int issued = 0;  // chunks issued, counted over all blocks: chunk number c lives in ring slot c % NSL
+    int lchunk = 0;  // chunks of the block being loaded that have been issued
+    int tok = 0;     // first key of the wave's tile in the chunk to load next
+    const uint8_t *src = nullptr;
+    auto load_from = [&](const PfBlock &b) {
+        tok = kPage * (tile & 1);
+        src = (const uint8_t *)((tile < 2 ? a.k : a.v) + ((int64_t)(b.t0 + tok) * a.Hkv + b.kvh) * D);
+        lchunk = 0;
+    };
+    load_from(lb);
+    auto issue = [&]() { // the next chunk of the sequence, if there is one
+        if (!l_ok) return;
         if (loader) {
             const uint32_t d = dst + (issued & (NSL - 1)) * 2 * G::kStage;
-            issue_tile<D, 2>(lc, src, len - tok, d, a.zeros); // keys past the end read zeros
-            issue_tile<D, 2>(lc, src + 32 * tok_bytes, len - tok - 32, d + G::kStage, a.zeros);
+            issue_tile<D, 2>(lc, src, lb.len - tok, d, a.zeros); // keys past the end read zeros
+            issue_tile<D, 2>(lc, src + 32 * tok_bytes, lb.len - tok - 32, d + G::kStage, a.zeros);
         }
         src += 64 * tok_bytes;
         tok += 64;
         issued++;
+        if (++lchunk == lb.nchunks) {
+            lturn += step;
+            l_ok = STAY && pf_next_block(a, die, lturn, step, lb);
+            if (l_ok) load_from(lb);
+        }
     };
-    while (issued < 2 && issued < nchunks) issue(); // the rest follows the barriers, one chunk at a time
-
-    // The wave's 32-row tile.  Waves w and w + 4 share a SIMD; tiles w and 7 - w have the same work between them
-    // under the causal mask whatever w is.
-    const int T = wave < 4 ? wave : 11 - wave;
-    const int row = q0 + kPfRows * T + n;
-    PfState<D> st;
-#pragma unroll
-    for (int i = 0; i < D / 16; i++) {
-        bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (row < len) v = *(const bf16x8 *)(a.q + ((int64_t)(t0 + row) * a.Hq + h) * D + 16 * i + 8 * hh);
-        st.qf[i] = v;
-    }
-    st.lsum = 0.f;
-#pragma unroll
-    for (int dt = 0; dt < D / 32; dt++) {
-#pragma unroll
-        for (int e = 0; e < 16; e++) st.o[dt][e] = 0.f;
-    }
+    issue();
+    issue(); // the rest follows the barriers, one chunk at a time
 
     // The ring.  While a wave is in step s it reads V of stage s and K of stage s + 1.  The barrier that opens chunk
-    // c (before step 2 c - 1, the first to read its K) says that every wave's loads of the chunk have landed and that
-    // every wave has left the last step that read chunk c - 2, whose slot then takes chunk c + 2 (chunks 0 and 1 are
-    // loaded up front).
+    // c (before the first step that reads its K) says that every wave's loads of the chunk have landed and that
+    // every wave has left the last step that read chunk c - 2, whose slot then takes chunk c + 2 (the first two
+    // chunks are loaded up front).  Chunks are numbered over all blocks, so the same holds across a block's end.
     auto open_chunk = [&](int c) {
         if (loader) WaitTail<NSL - 1, DPW>::run(issued - 1 - c);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
+        issue();
     };
-    // the stage that holds the tile's diagonal is the last one the wave works on; earlier ones lie wholly below it
-    int last = (q0 >> 5) + T;
-    const bool diag_in_range = last < nst;
-    last = diag_in_range ? last : nst - 1;
 
-    open_chunk(0);
-    pf_scores<D>(lds, pl, st.qf, st.s);
-    if (last == 0) {
+    // The wave's 32-row tile.  Waves w and w + 4 share a SIMD; tiles w and 7 - w have the same work between them
+    // under the causal mask whatever w is.
+    const int T = wave < 4 ? wave : 11 - wave;
+    auto load_q = [&](const PfBlock &b, bf16x8 (&qf)[D / 16]) {
+        const int row = b.q0 + kPfRows * T + n;
 #pragma unroll
-        for (int e = 0; e < 16; e++) {
-            if (8 * (e / 4) + 4 * hh + (e % 4) > row) st.s[e] = -INFINITY;
-        }
-    }
-    {
-        float mx = max3(first_max(st.s[0], st.s[1]), st.s[2], st.s[2]);
-#pragma unroll
-        for (int e = 3; e < 15; e += 2) mx = max3(mx, st.s[e], st.s[e + 1]);
-        mx = max3(mx, st.s[15], st.s[15]);
-        const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-        st.m = max3(__uint_as_float(r[0]), __uint_as_float(r[1]), __uint_as_float(r[1])) * a.scale_log2;
-    }
-    // (only now, so that the wait for the query rows above does not also wait for these loads)
-    if (issued < nchunks) issue();
-    // The query rows are the one input no workgroup has touched before, so a block would start with a trip to
-    // HBM.  Each block therefore touches (one dword per 64-byte line) the query rows of the block that the same die
-    // starts a generation of workgroups later (32 compute units per die, one workgroup each), which then finds
-    // them in the die's L2.  The dwords go to a scrap area of LDS behind the ring (a load into registers would
-    // write them at a time the compiler does not know of).
-    {
-        const int turn2 = turn + 32;
-        const int pair2 = (turn2 / per_pair) * 8 + die, r2 = turn2 % per_pair;
-        bool ok = pair2 < a.num_prompts * a.Hkv;
-        const int g2 = ok ? pair2 / a.Hkv : 0;
-        const int t2 = uniform_load(a.cu, g2), len2 = uniform_load(a.cu, g2 + 1) - t2;
-        const int h2 = (pair2 % a.Hkv) * a.G + r2 % a.G;
-        const int row2 = (nqb - 1 - r2 / a.G) * kPfBlock + kPfRows * wave + (lane >> 1);
-        ok = ok && row2 < len2;
-        const uint16_t *p2 = ok ? a.q + ((int64_t)(t2 + row2) * a.Hq + h2) * D + 32 * (lane & 1) : a.q;
-#pragma unroll
-        for (int x = 0; x < D * 2 / 128; x++) dma4(p2 + 64 * x, lds_addr + NSL * 2 * G::kStage + 256 * wave);
-    }
-    // every wave keeps the ring going for all the stages; it computes up to its own last stage: full steps, then the
-    // step whose new scores cross the diagonal, then the step without new scores
-    auto ring = [&](int s) { // before step s
-        if ((s & 1) && s + 1 < nst) {
-            open_chunk((s + 1) >> 1);
-            if (issued < nchunks) issue();
+        for (int i = 0; i < D / 16; i++) {
+            bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (row < b.len) v = *(const bf16x8 *)(a.q + ((int64_t)(b.t0 + row) * a.Hq + b.h) * D + 16 * i + 8 * hh);
+            qf[i] = v;
         }
     };
+    // Query rows are asked for a block ahead: those of the block after the current one are on their way (or there) in
+    // qn while st.qf holds the current block's.  They change places when the current block's last step is done, and
+    // that is the only place where the wave waits for them (the empty asm statements pin the wait there: the compiler
+    // would otherwise leave it to the first use, inside the next block, where it would also wait for younger loads).
+    PfState<D> st;
+    bf16x8 qn[D / 16];
+    load_q(cb, st.qf);
+#pragma unroll
+    for (int i = 0; i < D / 16; i++) asm volatile("" : "+v"(st.qf[i]));
+    PfBlock nb;
+    int nturn = cturn + step;
+    bool n_ok = STAY && pf_next_block(a, die, nturn, step, nb);
+    if (n_ok) load_q(nb, qn);
+    int chunk0 = 0; // number of the current block's first chunk
+
+    for (;;) {
+        const int nst = cb.nst, q0 = cb.q0, len = cb.len;
+        const int stage0 = 2 * chunk0;
+        const int row = q0 + kPfRows * T + n;
+        st.lsum = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < D / 32; dt++) {
+#pragma unroll
+            for (int e = 0; e < 16; e++) st.o[dt][e] = 0.f;
+        }
+        // the stage that holds the tile's diagonal is the last one the wave works on; earlier ones lie wholly below it
+        int last = (q0 >> 5) + T;
+        last = last < nst ? last : nst - 1;
+
+        open_chunk(chunk0);
+        pf_scores<D>(lds + (stage0 & (2 * NSL - 1)) * G::kStage, pl, st.qf, st.s);
+        if (last == 0) {
+#pragma unroll
+            for (int e = 0; e < 16; e++) {
+                if (8 * (e / 4) + 4 * hh + (e % 4) > row) st.s[e] = -INFINITY;
+            }
+        }
+        {
+            float mx = max3(first_max(st.s[0], st.s[1]), st.s[2], st.s[2]);
+#pragma unroll
+            for (int e = 3; e < 15; e += 2) mx = max3(mx, st.s[e], st.s[e + 1]);
+            mx = max3(mx, st.s[15], st.s[15]);
+            const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+            st.m = max3(__uint_as_float(r[0]), __uint_as_float(r[1]), __uint_as_float(r[1])) * a.scale_log2;
+        }
+        // A workgroup that has no further block of its own (one workgroup per block: long prompts) cannot ask for the
+        // next block's query rows, and they are the one input no workgroup has touched before, so every block would
+        // start with a trip to HBM.  Such a block therefore touches (one dword per 64-byte line) the query rows of the
+        // block that the same die starts a generation of workgroups later (one per compute unit), which then finds
+        // them in the die's L2.  The dwords go to a scrap area of LDS behind the ring (a load into registers would
+        // write them at a time the compiler does not know of).
+        if (!n_ok) {
+            PfBlock tb;
+            const bool ok = pf_block_of(a, die, cturn + a.num_cus / 8, tb);
+            const int row2 = tb.q0 + kPfRows * wave + (lane >> 1);
+            const uint16_t *p2 = ok && row2 < tb.len ? a.q + ((int64_t)(tb.t0 + row2) * a.Hq + tb.h) * D + 32 * (lane & 1) : a.q;
+#pragma unroll
+            for (int x = 0; x < D * 2 / 128; x++) dma4(p2 + 64 * x, lds_addr + NSL * 2 * G::kStage + 256 * wave);
+        }
+        // every wave keeps the ring going for all the stages; it computes up to its own last stage: full steps, then
+        // the step whose new scores cross the diagonal, then the step without new scores
+        auto ring = [&](int s) { // before step s
+            if ((s & 1) && s + 1 < nst) open_chunk(chunk0 + ((s + 1) >> 1));
+        };
 #define PF_STEP(MASK, NEXT)                                                                                                \
-    pf_step<D, MASK, NEXT>(st, lds + ((s + 1) & (2 * NSL - 1)) * G::kStage,                                                \
-                           lds_addr + (s & (2 * NSL - 1)) * G::kStage + 2 * G::kTile, pl, a.scale_log2, 32 * (s + 1), row)
-    int s = 0;
-    for (; s + 1 < last; s++) {
+    pf_step<D, MASK, NEXT>(st, lds + ((stage0 + s + 1) & (2 * NSL - 1)) * G::kStage,                                       \
+                           lds_addr + ((stage0 + s) & (2 * NSL - 1)) * G::kStage + 2 * G::kTile, pl, a.scale_log2, 32 * (s + 1), row)
+        int s = 0;
+        for (; s + 1 < last; s++) {
+            ring(s);
+            PF_STEP(false, true);
+        }
+        if (s + 1 == last) {
+            ring(s);
+            PF_STEP(true, true);
+            s++;
+        }
         ring(s);
-        PF_STEP(false, true);
-    }
-    if (s + 1 == last) {
-        ring(s);
-        PF_STEP(true, true);
-        s++;
-    }
-    ring(s);
-    PF_STEP(false, false);
-    for (s++; s < nst; s++) ring(s);
+        PF_STEP(false, false);
+        for (s++; s < nst; s++) ring(s);
 #undef PF_STEP
 
-    wait_vmcnt<0>(); // nothing may land in LDS after the workgroup has left
-    // a row's sum is spread over its two lanes
-    float l;
-    {
-        const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(st.lsum), __float_as_uint(st.lsum), false, false);
-        l = __uint_as_float(r[0]) + __uint_as_float(r[1]);
-    }
-    const float inv = 1.0f / l;
-    const int64_t rh = (int64_t)(t0 + row) * a.Hq + h;
+        // the next block's query rows take their place, and those of the block after it are asked for, before this
+        // block's results are stored (the other way round the wave would wait for its own stores to be acknowledged)
+        const PfBlock done = cb;
+        const bool more = n_ok;
+        if (more) {
 #pragma unroll
-    for (int dt = 0; dt < D / 32; dt++) {
-#pragma unroll
-        for (int qp = 0; qp < 2; qp++) {
-            // elements 8 qp .. + 3 are d = 32 dt + 16 qp + 4 hh .. + 3, elements 8 qp + 4 .. + 7 the same 8 further on;
-            // the two lanes of a row trade halves so that each holds eight consecutive d
-            f32x4 lo, hi;
-#pragma unroll
-            for (int x = 0; x < 4; x++) {
-                lo[x] = st.o[dt][8 * qp + x] * inv;
-                hi[x] = st.o[dt][8 * qp + 4 + x] * inv;
+            for (int i = 0; i < D / 16; i++) {
+                st.qf[i] = qn[i];
+                asm volatile("" : "+v"(st.qf[i]));
             }
-            const bf16x4 blo = __builtin_convertvector(lo, bf16x4), bhi = __builtin_convertvector(hi, bf16x4);
-            const u32x2 wlo = __builtin_bit_cast(u32x2, blo), whi = __builtin_bit_cast(u32x2, bhi);
-            const u32x2 s0 = __builtin_amdgcn_permlane32_swap(wlo[0], whi[0], false, false);
-            const u32x2 s1 = __builtin_amdgcn_permlane32_swap(wlo[1], whi[1], false, false);
-            // lane hh = 0 now has d = 32 dt + 16 qp + 0..7, lane hh = 1 has + 8..15
-            if (row < len) *(u32x4 *)(a.out + rh * D + 32 * dt + 16 * qp + 8 * hh) = u32x4{s0[0], s1[0], s0[1], s1[1]};
+            chunk0 += cb.nchunks;
+            cb = nb;
+            cturn = nturn;
+            nturn = cturn + step;
+            n_ok = STAY && pf_next_block(a, die, nturn, step, nb);
+            if (n_ok) load_q(nb, qn);
         }
+
+        // a row's sum is spread over its two lanes
+        float l;
+        {
+            const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(st.lsum), __float_as_uint(st.lsum), false, false);
+            l = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+        }
+        const float inv = 1.0f / l;
+        const int64_t rh = (int64_t)(done.t0 + row) * a.Hq + done.h;
+#pragma unroll
+        for (int dt = 0; dt < D / 32; dt++) {
+#pragma unroll
+            for (int qp = 0; qp < 2; qp++) {
+                // elements 8 qp .. + 3 are d = 32 dt + 16 qp + 4 hh .. + 3, elements 8 qp + 4 .. + 7 the same 8 further on;
+                // the two lanes of a row trade halves so that each holds eight consecutive d
+                f32x4 lo, hi;
+#pragma unroll
+                for (int x = 0; x < 4; x++) {
+                    lo[x] = st.o[dt][8 * qp + x] * inv;
+                    hi[x] = st.o[dt][8 * qp + 4 + x] * inv;
+                }
+                const bf16x4 blo = __builtin_convertvector(lo, bf16x4), bhi = __builtin_convertvector(hi, bf16x4);
+                const u32x2 wlo = __builtin_bit_cast(u32x2, blo), whi = __builtin_bit_cast(u32x2, bhi);
+                const u32x2 s0 = __builtin_amdgcn_permlane32_swap(wlo[0], whi[0], false, false);
+                const u32x2 s1 = __builtin_amdgcn_permlane32_swap(wlo[1], whi[1], false, false);
+                // lane hh = 0 now has d = 32 dt + 16 qp + 0..7, lane hh = 1 has + 8..15
+                if (row < len) *(u32x4 *)(a.out + rh * D + 32 * dt + 16 * qp + 8 * hh) = u32x4{s0[0], s1[0], s0[1], s1[1]};
+            }
+        }
+        if (row < len && hh == 0) a.lse[rh] = (st.m + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+        if (!more) break;
     }
-    if (row < len && hh == 0) a.lse[rh] = (st.m + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+    wait_vmcnt<0>(); // nothing may land in LDS after the workgroup has left
 }
 
 // LDS of a prefill workgroup: the ring and a scrap area
@@ -411,23 +492,44 @@ template <int D> constexpr int prefill_lds_bytes() { return kPfSlots * 2 * Geo<D
 
 hipError_t prefill_config()
 {
-    hipError_t e = hipFuncSetAttribute((const void *)prefill_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       prefill_lds_bytes<128>());
-    if (e != hipSuccess) return e;
-    return hipFuncSetAttribute((const void *)prefill_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, prefill_lds_bytes<64>());
+    const void *k[4] = {(const void *)prefill_kernel<128, false>, (const void *)prefill_kernel<128, true>,
+                        (const void *)prefill_kernel<64, false>, (const void *)prefill_kernel<64, true>};
+    for (int i = 0; i < 4; i++) {
+        hipError_t e = hipFuncSetAttribute(k[i], hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           i < 2 ? prefill_lds_bytes<128>() : prefill_lds_bytes<64>());
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_prefill(const PrefillLaunch &a, hipStream_t s)
 {
     const int nqb = (a.max_len + kPfBlock - 1) / kPfBlock;
     const int64_t pairs = (int64_t)a.num_prompts * a.Hkv; // dealt to eight dies, see the kernel
-    const int64_t blocks = 8 * ((pairs + 7) / 8) * nqb * a.G;
-    if (blocks == 0) return hipSuccess;
-    if (blocks > INT32_MAX) return hipErrorInvalidValue;
-    if (a.D == 128)
-        hipLaunchKernelGGL(prefill_kernel<128>, dim3((unsigned)blocks), dim3(64 * kPfWaves), prefill_lds_bytes<128>(), s, a);
-    else
-        hipLaunchKernelGGL(prefill_kernel<64>, dim3((unsigned)blocks), dim3(64 * kPfWaves), prefill_lds_bytes<64>(), s, a);
+    const int64_t turns = ((pairs + 7) / 8) * nqb * a.G;  // blocks of a die
+    if (turns == 0) return hipSuccess;
+    if (turns > INT32_MAX / 16) return hipErrorInvalidValue;
+    // Short prompts (one or two blocks of query rows each): the blocks are alike and a block's start-up is a third of
+    // its time, so the workgroups stay, one per compute unit (the ring takes most of a unit's LDS), and each takes
+    // every (units per die)-th block of its die.  Longer prompts: blocks differ by up to the prompt's length and
+    // start-up is small beside them, so there is one workgroup per block and the hardware hands them out as units
+    // become free (the same kernel: a workgroup that finds no further block of its own ends).
+    int per_die = a.num_cus / 8;
+    per_die = per_die < 1 ? 1 : per_die;
+    if (a.stay > 0 && a.stay < per_die) per_die = a.stay; // fewer were asked for
+    const bool stay = a.stay < 0 ? nqb <= 2 : a.stay != 0;
+    const bool one_each = !stay || turns <= per_die;
+    if (one_each) per_die = (int)turns;
+#define RA_PF_LAUNCH(DD, ST)                                                                                                \
+    hipLaunchKernelGGL((prefill_kernel<DD, ST>), dim3(8u * per_die), dim3(64 * kPfWaves), prefill_lds_bytes<DD>(), s, a)
+    if (a.D == 128) {
+        if (one_each) RA_PF_LAUNCH(128, false);
+        else RA_PF_LAUNCH(128, true);
+    } else {
+        if (one_each) RA_PF_LAUNCH(64, false);
+        else RA_PF_LAUNCH(64, true);
+    }
+#undef RA_PF_LAUNCH
     return hipGetLastError();
 }
 

@@ -22,9 +22,26 @@ def compare(out, lse, ref_out, ref_lse, what=""):
     return compare_decode(out, lse, ref_out, ref_lse, what, abs_rel=OUT_ULP)
 
 
-@pytest.fixture(scope="module")
-def dec():
-    d = ra.Decoder(0)
+@pytest.fixture(scope="module", params=["by prompt length", "one workgroup per block", "two workgroups per die that stay",
+                                        "one per compute unit that stays"])
+def dec(request):
+    """Every test runs in the launch shape the library picks and in each of those it can be told to use: the results must
+    not depend on how the blocks of query rows are dealt to workgroups (the setting is read when the context is made)."""
+    import os
+    value = {"by prompt length": None, "one workgroup per block": "0", "two workgroups per die that stay": "2",
+             "one per compute unit that stays": "64"}[request.param]
+    old = os.environ.get("ROLLOUT_ATTN_PREFILL_WGS_PER_DIE")
+    if value is None:
+        os.environ.pop("ROLLOUT_ATTN_PREFILL_WGS_PER_DIE", None)
+    else:
+        os.environ["ROLLOUT_ATTN_PREFILL_WGS_PER_DIE"] = value
+    try:
+        d = ra.Decoder(0)
+    finally:
+        if old is None:
+            os.environ.pop("ROLLOUT_ATTN_PREFILL_WGS_PER_DIE", None)
+        else:
+            os.environ["ROLLOUT_ATTN_PREFILL_WGS_PER_DIE"] = old
     yield d
     d.close()
 
