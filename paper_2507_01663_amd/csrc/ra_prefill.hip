@@ -18,6 +18,9 @@ constexpr int kPfRows = 32;                  // query rows per wave: one 32x32 M
 constexpr int kPfBlock = kPfRows * kPfWaves; // query rows per workgroup
 constexpr int kPfSlots = 4;                  // ring slots of one chunk (two stages of 32 keys) each
 
+constexpr int kPfStageRow = 128;                    // bytes of a row in a wave's staging area: 64 bf16
+constexpr int kPfStageBytes = kPfRows * kPfStageRow; // 4 KB per wave
+
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
@@ -59,6 +62,10 @@ template <int D> struct PfState {
     f32x16 s;          // scores of the stage whose weights are computed next: element e is key 8 (e / 4) + 4 hh + e % 4
     float m, lsum;     // reference point of the exponent (same in both lanes of a row); this lane's part of the row sum
 };
+
+// The 16-byte pieces of a staging row are XOR-swizzled by the row, so that neither the lanes of a row group that write
+// the same piece of different rows nor the eight lanes that read one row meet in a bank.
+__device__ __forceinline__ int pf_stage_swz(int r) { return (r + (r >> 3)) & 7; }
 
 // max(a, b, c) as the instruction computes it.  (Through fmaxf the compiler first quiets possible signalling NaNs of
 // every operand with an instruction of its own, which doubles the cost of the reduction.)  The compiler does not
@@ -344,28 +351,37 @@ template <int D, bool STAY> __global__ __launch_bounds__(64 * kPfWaves) void pre
     // The wave's 32-row tile.  Waves w and w + 4 share a SIMD; tiles w and 7 - w have the same work between them
     // under the causal mask whatever w is.
     const int T = wave < 4 ? wave : 11 - wave;
+    // A lane's part of its query row (a row past the prompt's end reads the prompt's last row instead, and is
+    // zeroed by keep_q when the registers are taken into use: nothing writes the registers but the loads themselves,
+    // so the compiler has no reason to wait for older loads before them).
     auto load_q = [&](const PfBlock &b, bf16x8 (&qf)[D / 16]) {
-        const int row = b.q0 + kPfRows * T + n;
+        int row = b.q0 + kPfRows * T + n;
+        row = row < b.len ? row : b.len - 1;
+#pragma unroll
+        for (int i = 0; i < D / 16; i++) qf[i] = *(const bf16x8 *)(a.q + ((int64_t)(b.t0 + row) * a.Hq + b.h) * D + 16 * i + 8 * hh);
+    };
+    auto keep_q = [&](const PfBlock &b, bf16x8 (&qf)[D / 16]) {
+        const bool ok = b.q0 + kPfRows * T + n < b.len;
 #pragma unroll
         for (int i = 0; i < D / 16; i++) {
-            bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (row < b.len) v = *(const bf16x8 *)(a.q + ((int64_t)(b.t0 + row) * a.Hq + b.h) * D + 16 * i + 8 * hh);
-            qf[i] = v;
+            if (!ok) qf[i] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+            asm volatile("" : "+v"(qf[i]));
         }
     };
-    // Query rows are asked for a block ahead: those of the block after the current one are on their way (or there) in
-    // qn while st.qf holds the current block's.  They change places when the current block's last step is done, and
-    // that is the only place where the wave waits for them (the empty asm statements pin the wait there: the compiler
-    // would otherwise leave it to the first use, inside the next block, where it would also wait for younger loads).
+    // the wave's staging area behind the ring (32 rows of 128 bytes)
+    uint8_t *const stage = lds + NSL * 2 * G::kStage + kPfStageBytes * wave;
+    const uint32_t stage_addr = lds_addr + NSL * 2 * G::kStage + kPfStageBytes * wave;
+    // Query rows come straight from memory, 16 bytes per lane and row.  A workgroup that stays asks for those of the
+    // block after the current one (into qn) when the current block has its first scores, and waits for them when its
+    // last step is done: qn and st.qf change places there.  (The empty asm statements pin the compiler's wait for the
+    // loads to these places; left to the first use it would sit inside a block and wait for younger loads as well.)
     PfState<D> st;
     bf16x8 qn[D / 16];
     load_q(cb, st.qf);
-#pragma unroll
-    for (int i = 0; i < D / 16; i++) asm volatile("" : "+v"(st.qf[i]));
+    keep_q(cb, st.qf);
     PfBlock nb;
     int nturn = cturn + step;
     bool n_ok = STAY && pf_next_block(a, die, nturn, step, nb);
-    if (n_ok) load_q(nb, qn);
     int chunk0 = 0; // number of the current block's first chunk
 
     for (;;) {
@@ -402,19 +418,21 @@ template <int D, bool STAY> __global__ __launch_bounds__(64 * kPfWaves) void pre
         // next block's query rows, and they are the one input no workgroup has touched before, so every block would
         // start with a trip to HBM.  Such a block therefore touches (one dword per 64-byte line) the query rows of the
         // block that the same die starts a generation of workgroups later (one per compute unit), which then finds
-        // them in the die's L2.  The dwords go to a scrap area of LDS behind the ring (a load into registers would
-        // write them at a time the compiler does not know of).
-        if (!n_ok) {
+        // them in the die's L2.  The dwords go to the wave's staging area (a load into registers would write them at a
+        // time the compiler does not know of).
+        if (n_ok) load_q(nb, qn);
+        const bool touched = !n_ok;
+        if (touched) {
             PfBlock tb;
             const bool ok = pf_block_of(a, die, cturn + a.num_cus / 8, tb);
             const int row2 = tb.q0 + kPfRows * wave + (lane >> 1);
             const uint16_t *p2 = ok && row2 < tb.len ? a.q + ((int64_t)(tb.t0 + row2) * a.Hq + tb.h) * D + 32 * (lane & 1) : a.q;
 #pragma unroll
-            for (int x = 0; x < D * 2 / 128; x++) dma4(p2 + 64 * x, lds_addr + NSL * 2 * G::kStage + 256 * wave);
+            for (int x = 0; x < D * 2 / 128; x++) dma4(p2 + 64 * x, stage_addr);
         }
         // every wave keeps the ring going for all the stages; it computes up to its own last stage: full steps, then
         // the step whose new scores cross the diagonal, then the step without new scores
-        auto ring = [&](int s) { // before step s
+        auto ring = [&](int s) __attribute__((always_inline)) { // before step s
             if ((s & 1) && s + 1 < nst) open_chunk(chunk0 + ((s + 1) >> 1));
         };
 #define PF_STEP(MASK, NEXT)                                                                                                \
@@ -435,22 +453,18 @@ template <int D, bool STAY> __global__ __launch_bounds__(64 * kPfWaves) void pre
         for (s++; s < nst; s++) ring(s);
 #undef PF_STEP
 
-        // the next block's query rows take their place, and those of the block after it are asked for, before this
-        // block's results are stored (the other way round the wave would wait for its own stores to be acknowledged)
+        // the next block's query rows take their place (the staging area is free for the results after that)
         const PfBlock done = cb;
         const bool more = n_ok;
         if (more) {
 #pragma unroll
-            for (int i = 0; i < D / 16; i++) {
-                st.qf[i] = qn[i];
-                asm volatile("" : "+v"(st.qf[i]));
-            }
+            for (int i = 0; i < D / 16; i++) st.qf[i] = qn[i];
+            keep_q(nb, st.qf);
             chunk0 += cb.nchunks;
             cb = nb;
             cturn = nturn;
             nturn = cturn + step;
             n_ok = STAY && pf_next_block(a, die, nturn, step, nb);
-            if (n_ok) load_q(nb, qn);
         }
 
         // a row's sum is spread over its two lanes
@@ -461,8 +475,37 @@ template <int D, bool STAY> __global__ __launch_bounds__(64 * kPfWaves) void pre
         }
         const float inv = 1.0f / l;
         const int64_t rh = (int64_t)(done.t0 + row) * a.Hq + done.h;
+        // A workgroup that stays sends its results through the wave's staging area, 64 d (128 bytes of every row) at a
+        // time: a lane holds four consecutive d of its own row per accumulator quarter, and storing from there is 32
+        // separate pieces of 16 bytes per instruction, which keeps the compute unit's one memory pipeline busy for
+        // microseconds per block; read back eight lanes to a row, an instruction stores whole 128-byte lines.  (A
+        // workgroup with one long block stores directly: the detour's latency would be the last thing before it ends.)
+        if (STAY && touched) wait_vmcnt<0>(); // the dwords of the touch above land in this area
+        int sl = lane;
+        if (STAY) asm volatile("" : "+v"(sl));
+        const int sn = sl & 31, sh = sl >> 5;
 #pragma unroll
-        for (int dt = 0; dt < D / 32; dt++) {
+        for (int p = 0; p < (STAY ? D / 64 : 0); p++) {
+#pragma unroll
+            for (int dtl = 0; dtl < 2; dtl++) {
+#pragma unroll
+                for (int j = 0; j < 4; j++) {
+                    f32x4 v;
+#pragma unroll
+                    for (int x = 0; x < 4; x++) v[x] = st.o[2 * p + dtl][4 * j + x] * inv; // d = 64 p + 32 dtl + 8 j + 4 hh + x
+                    *(bf16x4 *)(stage + kPfStageRow * sn + 16 * ((4 * dtl + j) ^ pf_stage_swz(sn)) + 8 * sh) = __builtin_convertvector(v, bf16x4);
+                }
+            }
+#pragma unroll
+            for (int m = 0; m < 4; m++) {
+                const int r = 8 * m + (sl >> 3), c = sl & 7; // row of the tile, 16-byte piece of its 128 bytes
+                const u32x4 v = *(const u32x4 *)(stage + kPfStageRow * r + 16 * (c ^ pf_stage_swz(r)));
+                const int orow = q0 + kPfRows * T + r;
+                if (orow < len) *(u32x4 *)(a.out + ((int64_t)(done.t0 + orow) * a.Hq + done.h) * D + 64 * p + 8 * c) = v;
+            }
+        }
+#pragma unroll
+        for (int dt = 0; dt < (STAY ? 0 : D / 32); dt++) {
 #pragma unroll
             for (int qp = 0; qp < 2; qp++) {
                 // elements 8 qp .. + 3 are d = 32 dt + 16 qp + 4 hh .. + 3, elements 8 qp + 4 .. + 7 the same 8 further on;
@@ -487,8 +530,8 @@ template <int D, bool STAY> __global__ __launch_bounds__(64 * kPfWaves) void pre
     wait_vmcnt<0>(); // nothing may land in LDS after the workgroup has left
 }
 
-// LDS of a prefill workgroup: the ring and a scrap area
-template <int D> constexpr int prefill_lds_bytes() { return kPfSlots * 2 * Geo<D, 2>::kStage + 256 * kPfWaves; }
+// LDS of a prefill workgroup: the ring and the waves' staging areas
+template <int D> constexpr int prefill_lds_bytes() { return kPfSlots * 2 * Geo<D, 2>::kStage + kPfStageBytes * kPfWaves; }
 
 hipError_t prefill_config()
 {
