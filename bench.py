@@ -299,8 +299,9 @@ def main():
     reuse_wall = time.perf_counter() - t0
     out["schedule_reused"] = {"ms_per_step": round(reuse_wall * 1e3 / args.steps, 5),
                               "GBps": round(total_bytes / reuse_wall / 1e9, 1),
-                              "note": "the same rotation with RA_FLAG_REUSE_SCHEDULE on a schedule computed once per instance (no "
-                                      "difference for batches that the attention kernel schedules itself)"}
+                              "note": "the same rotation with RA_FLAG_REUSE_SCHEDULE on a schedule computed once per instance, as "
+                                      "the layers of a model after the first would call it (the attention workgroups take the "
+                                      "lists they kept instead of planning again); `value` always includes the schedule"}
     for d in devs:
         d.set(flags)
     del wss

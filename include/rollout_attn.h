@@ -61,9 +61,10 @@ enum {
     RA_FLAG_VALIDATE = 1u,          /* check device-side lengths / page ids / hint first (one extra kernel + a
                                        stream synchronisation) */
     RA_FLAG_NO_PREFIX_SHARING = 2u, /* ignore the prompt-group hint (for A/B comparison) */
-    RA_FLAG_REUSE_SCHEDULE = 4u     /* skip the schedule kernels (when the batch is large enough for them to be launched
-                                       at all) and use the schedule that the previous
-                                       rollout_attn_decode call on the same context left in the same workspace.
+    RA_FLAG_REUSE_SCHEDULE = 4u     /* skip the schedule (its kernels for a large batch; for a smaller one, which the
+                                       attention workgroups plan for themselves, their planning pass: each takes the
+                                       list it kept) and use the schedule that the previous rollout_attn_decode call
+                                       without this flag on the same context left in the same workspace.
                                        For the layers of one decode step: the schedule depends only on B, the head
                                        counts, D, max_pages_per_seq, seq_lens, seq_group, prefix_page_offsets and
                                        RA_FLAG_NO_PREFIX_SHARING, which must all be what they were in that call; q,

@@ -126,6 +126,7 @@ void fill_launch(ra::Launch &a, const ra_ctx *ctx, const ra_problem *p)
     a.out = (uint16_t *)p->out; a.lse = p->lse;
     a.zeros = ctx ? ctx->zeros : nullptr;
     a.self_plan = ctx && ctx->self_plan && ra::can_self_plan(a.D, a.kv_fp8, a.stages, a.B, a.share ? a.num_groups : 0, a.members_per_row);
+    a.reuse_lists = a.self_plan && (p->flags & RA_FLAG_REUSE_SCHEDULE) != 0;
 }
 
 // Turns per-workgroup weights (per mille of the mean, clamped to 700..1400 so that no span is shorter than half the

@@ -11,6 +11,7 @@ constexpr int kMinUnitsPerWave = 8; // do not cut the page stream finer than thi
 constexpr int kMaxWaves = 4096;     // attention workgroups of a launch at most (16 per compute unit)
 constexpr int kCostSuffix = 4;      // scheduling weight of a page of a sequence's own KV
 constexpr int kChunkSegs = 7;       // segment records per chunk of a span's work list (plus one header record)
+constexpr int kSelfListBytes = 4096; // room for the list a self-planning wave keeps (its LDS work list is at most this)
 constexpr int kCostPrefix = 8;      // ... of a shared-prefix page of a bf16 pool (64 query rows per byte read: more time per page)
 constexpr int kCostPrefixFp8 = 5;   // ... of an e4m3 pool (32 query rows)
 constexpr int kCostItem = 16;       // ... of a segment, on top of its pages
@@ -35,6 +36,8 @@ struct Workspace {
     float *suf_lse;          // [(B*Hkv + spans)][G]      partial log2-sum-exp
     float *pfx_o;            // [(prefix_rows_max*Hkv + spans)][prefix_rows][D]
     float *pfx_lse;          // [(prefix_rows_max*Hkv + spans)][prefix_rows]
+    int32_t *self_cnt;       // [spans]  records in the list that the wave of a span made for itself and kept, or -1
+    uint8_t *self_rec;       // [spans][kSelfListBytes]  those lists (for a later call that reuses the schedule)
 };
 
 struct Launch {
@@ -55,6 +58,7 @@ struct Launch {
     float *lse;
     const void *zeros;                    // >= 16 bytes of zeros
     int32_t self_plan;                    // the attention waves plan their spans themselves: no schedule kernel
+    int32_t reuse_lists;                  // ... and take the lists that an earlier call's waves kept in the workspace
     Workspace ws;
 };
 

@@ -68,6 +68,8 @@ size_t carve_workspace(Workspace &ws, void *base, int B, int Hkv, int G, int D, 
     size_t npfx = prm ? (size_t)prm * Hkv + spans : 0;
     ws.pfx_o = (float *)take(npfx * prefix_rows * D * 4);
     ws.pfx_lse = (float *)take(npfx * prefix_rows * 4);
+    ws.self_cnt = (int32_t *)take(spans * 4);
+    ws.self_rec = (uint8_t *)take(spans * kSelfListBytes);
     return off;
 }
 
@@ -605,6 +607,7 @@ template <int D, int KVB, int NST> struct LdsMap {
     static constexpr int kPlanBytes = kQTile;         // everything before it is free while the wave plans
     static constexpr int kRecCap = kPlanBytes / 32;   // records the work list holds
     static constexpr int kBytes = kPlanBase + kPlanBytes;
+    static_assert(kPlanBytes <= kSelfListBytes, "a wave's list fits the room the workspace keeps for it");
     static_assert(PrefixTiles<KVB>::value * kQTile <= G::kStage, "the query rows of a shared-prefix row fill one ring entry");
     static_assert(PrefixTiles<KVB>::value * (D * 2 / 64) <= G::kDmaPerStage, "... with no more loads than two pages take");
 };
@@ -1311,6 +1314,19 @@ template <int D, int KVB, int NST, int NPEND, bool SELF> __device__ __forceinlin
             uint8_t *plan_base = lds;
             int plan_lane = lane;
             asm volatile("" : "+s"(plan_base), "+v"(plan_lane));
+            // A call that reuses the schedule takes the list that the span's wave kept in the workspace when it planned
+            // (one trip to memory in place of the planning pass), if that wave's whole span went into one list.
+            const bool was_first = first_pass;
+            int kept = -1;
+            if (a.reuse_lists && was_first) kept = uniform_load(a.ws.self_cnt, c);
+            if (kept >= 0) {
+                const uint8_t *src = a.ws.self_rec + (int64_t)c * kSelfListBytes + 16 * plan_lane;
+                for (int off = 0; off < 32 * kept; off += 1024) dma16(src + off, lds_addr + M::kPlanBase + off);
+                wait_vmcnt<0>();
+                wk_n = kept;
+                sp.done = true;
+                first_pass = false;
+            } else {
             WaveTables T;
             carve_wave_tables(T, plan_base, a.B, a.share ? a.num_groups : 0, a.members_per_row);
             wave_rows(a, T, sp.nR, sp.nPR, plan_lane);
@@ -1333,6 +1349,15 @@ template <int D, int KVB, int NST, int NPEND, bool SELF> __device__ __forceinlin
                 first_pass = false;
             }
             wk_n = list_segments(a, T, sp, c, (int32_t *)(plan_base + M::kPlanBase), M::kRecCap, plan_lane);
+            if (was_first && !a.reuse_lists) {
+                // keep the list for later calls on this schedule (the layers of one decode step)
+                const int keep = sp.done ? wk_n : -1;
+                uint8_t *dst = a.ws.self_rec + (int64_t)c * kSelfListBytes;
+                for (int off = 16 * plan_lane; off < 32 * keep; off += 1024)
+                    *(int4 *)(dst + off) = *(const int4 *)(plan_base + M::kPlanBase + off);
+                if (plan_lane == 0) a.ws.self_cnt[c] = keep;
+            }
+            }
             wk_j = 0;
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // the tables have been read: the ring may overwrite them
             // (nothing is kept across a planning pass, neither the lane constants nor a partial: say so, or their

@@ -485,6 +485,31 @@ def test_schedule_reused_for_another_layer(dec):
     compare(*d2.results(), *oracle.decode(p2), "layer 2 on layer 1's schedule")
 
 
+@pytest.mark.parametrize("which", ["self-planned", "schedule kernels", "few waves"])
+def test_reused_schedule_gives_the_same_bytes(dec, dec_sched, dec_few_waves, which):
+    """A call that reuses the schedule (RA_FLAG_REUSE_SCHEDULE) streams exactly the spans of the call that made it:
+    the same problem with and without the flag must give the same bytes, whether the schedule came from the schedule
+    kernels, from attention waves that kept their lists, or from waves whose spans did not fit one list (those plan
+    again).  bf16 and e4m3 pools; after a call on another batch the flag must not be used, and is not here."""
+    import paper_2507_01663_amd as ra
+    d = {"self-planned": dec, "schedule kernels": dec_sched, "few waves": dec_few_waves}[which]
+    cases = [workload.make_problem("mid7b", seed=2), workload.make_problem("mid32b", seed=2, kv_dtype="fp8_e4m3"),
+             workload.make_problem("grpo7b", seed=1)]
+    if which == "few waves":
+        rng = np.random.default_rng(159)
+        resp = rng.integers(1, 3, size=6 * 70)
+        resp[::70] = 111000
+        cases.append(workload.build_problem("fragments", 4, 4, 128, [16] * 6, 70, resp, seed=31))
+    for p in cases:
+        plain = run(d, p)
+        again = run(d, p, flags=ra.RA_FLAG_REUSE_SCHEDULE)
+        third = run(d, p, flags=ra.RA_FLAG_REUSE_SCHEDULE)
+        torch.cuda.synchronize()
+        for other in (again, third):
+            assert torch.equal(plain.out.view(torch.int16), other.out.view(torch.int16)) and torch.equal(plain.lse, other.lse)
+        assert bool(torch.isfinite(plain.lse[torch.from_numpy(p.seq_lens > 0).to(plain.lse.device)]).all())
+
+
 def test_wave_weights_move_work_not_results(dec):
     """The shares of the page stream that the attention workgroups get can be set per workgroup; any weights give the
     same answer within tolerance, and the same weights the same bytes."""
