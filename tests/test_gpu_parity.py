@@ -486,6 +486,44 @@ def test_schedule_reused_for_another_layer(dec):
 
 
 @pytest.mark.parametrize("which", ["self-planned", "schedule kernels", "few waves"])
+def test_random_batches_against_the_oracle(dec, dec_sched, dec_few_waves, which):
+    """Seeded random shapes: head counts, head dim, group sizes, prompts that are not whole pages, empty and one-token
+    responses beside long ones, relabelled and missing group ids, both pool types, hint on and off, and a second call on
+    the first one's schedule.  Every element against the oracle, on each of the schedule's three paths.
+    Sequences of one to three tokens do not average: their outputs are as large as single V entries (up to about 4.5
+    with N(0,1) values), where the two bf16 roundings of the arithmetic (the weights, with the e4m3 scale folded in,
+    and the output itself, 2^-9 relative each) already exceed 1e-2 absolute; the element-wise bound is therefore
+    1e-2 + 2^-8 |ref| here, as for the prefill.  The row-relative and log-sum-exp bounds are the usual ones."""
+    import paper_2507_01663_amd as ra
+    from gpu_util import compare
+    ulp = 2.0 ** -8
+    d = {"self-planned": dec, "schedule kernels": dec_sched, "few waves": dec_few_waves}[which]
+    rng = np.random.default_rng({"self-planned": 101, "schedule kernels": 202, "few waves": 303}[which])
+    for case in range(10):
+        Hkv = int(rng.choice([1, 2, 4, 8]))
+        G = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 16]))
+        D = int(rng.choice([64, 128]))
+        ngroups, R = int(rng.integers(1, 9)), int(rng.integers(1, 13))
+        prompts = rng.choice([0, 1, 15, 16, 17, 40, 64, 100, 333], size=ngroups)
+        kind = rng.integers(0, 4, size=ngroups * R)
+        resp = np.where(kind == 0, 0, np.where(kind == 1, rng.integers(1, 4, size=ngroups * R),
+                        np.where(kind == 2, rng.integers(4, 200, size=ngroups * R), rng.integers(200, 2500, size=ngroups * R))))
+        kv = "fp8_e4m3" if rng.integers(0, 3) == 0 else "bf16"
+        p = workload.build_problem("random", Hkv * G, Hkv, D, prompts, R, resp, kv_dtype=kv, seed=1000 + case)
+        if rng.integers(0, 2):                              # group ids need not be contiguous in b; some opt out
+            perm = rng.permutation(p.B)
+            for name in ("q", "block_table", "seq_lens", "seq_group"):
+                setattr(p, name, np.ascontiguousarray(getattr(p, name)[perm]))
+            p.seq_group[rng.integers(0, p.B)] = -1
+        what = "%s case %d: Hq %d Hkv %d D %d groups %d x %d %s" % (which, case, Hkv * G, Hkv, D, ngroups, R, kv)
+        log(what)
+        ref = oracle.decode(p)
+        compare(*run(d, p).results(), *ref, what, abs_rel=ulp)
+        compare(*run(d, p, flags=ra.RA_FLAG_REUSE_SCHEDULE).results(), *ref, what + ", schedule reused", abs_rel=ulp)
+        compare(*run(d, p, use_hint=False).results(), *ref, what + ", no hint", abs_rel=ulp)
+
+
+@pytest.mark.parametrize("which", ["self-planned", "schedule kernels", "few waves"])
 def test_reused_schedule_gives_the_same_bytes(dec, dec_sched, dec_few_waves, which):
     """A call that reuses the schedule (RA_FLAG_REUSE_SCHEDULE) streams exactly the spans of the call that made it:
     the same problem with and without the flag must give the same bytes, whether the schedule came from the schedule
