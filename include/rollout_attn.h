@@ -175,7 +175,7 @@ ra_status rollout_attn_decode(ra_ctx *ctx, const ra_problem *problem, void *work
  * device memory that every GPU the library is loaded on holds until the process ends.  Neither this call nor
  * anything it launches allocates or frees memory.  RA_ERR_WORKSPACE_TOO_SMALL when the problem's shape needs more
  * than 64 MiB (rollout_attn_workspace_size says how much a shape needs; the 7B-shaped batch of 256 sequences needs
- * about 50 MiB); nothing is enqueued then.  All calls on one GPU share the one array, whatever their context or
+ * about 51 MiB); nothing is enqueued then.  All calls on one GPU share the one array, whatever their context or
  * stream: calls that overlap in time on one GPU race, so order them on one stream or with events.  RA_FLAG_REUSE_SCHEDULE
  * refers to the schedule the previous call on the GPU left in the array.  Everything else is as for
  * rollout_attn_decode. */
