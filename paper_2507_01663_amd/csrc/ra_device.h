@@ -35,19 +35,27 @@ template <int DPS> struct WaitTail<0, DPS> {
 // Two address forms: a full 64-bit address per lane, or a wave-uniform base plus a 32-bit lane offset.
 // (The LDS address and the base are wave-uniform by construction; readfirstlane says so to the compiler, which
 // may have computed them on the vector unit.)
-__device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_addr)
+// STREAM marks data that is read once (the pages of a decode step): the loads carry the non-temporal hint, which tells
+// the caches not to keep the lines.  Measured on the streaming probe, 4 KB tiles from scattered places: 6.1 TB/s
+// without the hint, 6.9 TB/s with it (consecutive tiles: 6.4 and 7.1); the system-coherence bits change nothing.
+template <bool STREAM = false> __device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_addr)
 {
     const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_addr);
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(m0) : "memory", "m0");
+    if (STREAM) asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt" ::"v"(gptr), "s"(m0) : "memory", "m0");
+    else asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(m0) : "memory", "m0");
 }
-__device__ __forceinline__ void dma16_base(uint32_t lane_off, const void *uniform_base, uint32_t lds_addr)
+template <bool STREAM = false> __device__ __forceinline__ void dma16_base(uint32_t lane_off, const void *uniform_base, uint32_t lds_addr)
 {
     const uint64_t u = (uint64_t)(uintptr_t)uniform_base;
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u), hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
     const uint64_t sbase = ((uint64_t)hi << 32) | lo;
     const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_addr);
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(sbase), "s"(m0)
-                 : "memory", "m0");
+    if (STREAM)
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt" ::"v"(lane_off), "s"(sbase), "s"(m0)
+                     : "memory", "m0");
+    else
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(sbase), "s"(m0)
+                     : "memory", "m0");
 }
 __device__ __forceinline__ void dma4(const void *gptr, uint32_t lds_addr) // 4 bytes per lane, to lds_addr + lane*4
 {
@@ -168,19 +176,19 @@ __device__ __forceinline__ bf16x8 fp8x8_to_bf16(int c0, int c1)
 // One tile.  A full page goes the cheap way (uniform base + lane offset).  In the last page of a sequence
 // the rows at or past nvalid come from the zero block instead, so stale or poisoned slots never reach the
 // MFMA; a page id is only dereferenced when the page exists.
-template <int D, int KVB>
+template <int D, int KVB, bool STREAM = false>
 __device__ __forceinline__ void issue_tile(const LaneConst<D, KVB> &lc, const uint8_t *tile, int nvalid, uint32_t lds_addr,
                                            const void *zeros)
 {
     using G = Geo<D, KVB>;
     if (nvalid >= kPage) {
 #pragma unroll
-        for (int n = 0; n < G::kDmaPerTile; n++) dma16_base((uint32_t)lc.dma_off[n], tile, lds_addr + 1024 * n);
+        for (int n = 0; n < G::kDmaPerTile; n++) dma16_base<STREAM>((uint32_t)lc.dma_off[n], tile, lds_addr + 1024 * n);
     } else {
 #pragma unroll
         for (int n = 0; n < G::kDmaPerTile; n++) {
             const void *src = lc.dma_row[n] < nvalid ? (const void *)(tile + lc.dma_off[n]) : zeros;
-            dma16(src, lds_addr + 1024 * n);
+            dma16<STREAM>(src, lds_addr + 1024 * n);
         }
     }
 }

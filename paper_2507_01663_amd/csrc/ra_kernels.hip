@@ -644,10 +644,11 @@ __device__ __forceinline__ void issue_stage(const Launch &a, const LaneConst<D, 
     const uint32_t sb = lds_addr + ring_slot * G::kStage;
     const int64_t off0 = (int64_t)pid0 * a.stride_page_b + (int64_t)sg.kvh * a.stride_head_b;
     const int64_t off1 = (int64_t)pid1 * a.stride_page_b + (int64_t)sg.kvh * a.stride_head_b;
-    issue_tile<D, KVB>(lc, a.k_pool + off0, nv0, sb, a.zeros);
-    issue_tile<D, KVB>(lc, a.k_pool + off1, nv1, sb + G::kTile, a.zeros);
-    issue_tile<D, KVB>(lc, a.v_pool + off0, nv0, sb + 2 * G::kTile, a.zeros);
-    issue_tile<D, KVB>(lc, a.v_pool + off1, nv1, sb + 3 * G::kTile, a.zeros);
+    // (a decode step reads every page once: streaming loads)
+    issue_tile<D, KVB, true>(lc, a.k_pool + off0, nv0, sb, a.zeros);
+    issue_tile<D, KVB, true>(lc, a.k_pool + off1, nv1, sb + G::kTile, a.zeros);
+    issue_tile<D, KVB, true>(lc, a.v_pool + off0, nv0, sb + 2 * G::kTile, a.zeros);
+    issue_tile<D, KVB, true>(lc, a.v_pool + off1, nv1, sb + 3 * G::kTile, a.zeros);
     if (KVB == 1) {
         // the pages' scales land behind the tiles: lanes 0..3 bring k0, v0, k1, v1
         const int64_t si = (int64_t)((lane & 2) ? pid1 : pid0) * a.Hkv + sg.kvh;
@@ -1568,7 +1569,7 @@ __global__ __launch_bounds__(64) void stream_probe_kernel(const uint8_t *__restr
             uint32_t g = first + piece;
             if (scattered) g = g * 2654435761u + 12345u; // odd multiplier: a permutation modulo a power of two
             const uint8_t *src = buf + ((size_t)(g & granule_mask) << granule_shift) + within;
-            dma16_base((uint32_t)(16 * lane), src, lds_addr + (slot & 1) * 16384 + 1024 * n);
+            dma16_base<true>((uint32_t)(16 * lane), src, lds_addr + (slot & 1) * 16384 + 1024 * n); // as the attention kernel's page loads
         }
     };
     // n entries first, first + step, ... through the two-slot ring; drained at the end
