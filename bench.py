@@ -251,7 +251,7 @@ def main():
     waves = ra.rollout_attn_wave_count(dec.ctx, ra.RA_KV_BF16, 128)
     entries = max(1, (1 << 30) // (waves * 16384))
     ceil = {}
-    for label, scattered in (("gather_4KB_tiles", 1), ("sequential", 0)):
+    for label, scattered in (("gather_4KB_tiles", 1), ("sequential", 0), ("gather_plain_loads", 3), ("sequential_plain_loads", 2)):
         for _ in range(3):
             n = ra.rollout_attn_debug_stream(dec.ctx, ctypes.c_void_p(buf.data_ptr()), buf.numel(), 4096, scattered, entries, sp)
         ev0.record(stream)
@@ -277,7 +277,10 @@ def main():
     out["stream_ceiling"] = {"GBps": round(ceil["gather_4KB_tiles"], 1), "sequential_GBps": round(ceil["sequential"], 1), "unit": "GB/s",
                              "pct_of_hbm_peak": round(100 * ceil["gather_4KB_tiles"] / HBM_PEAK_GBPS, 2),
                              "note": "read-only probe with the attention kernel's grid and LDS ring, no arithmetic: 4 KB tiles from "
-                                     "scattered places (the kernel's own pattern) and from consecutive ones; measured in this run",
+                                     "scattered places (the kernel's own pattern) and from consecutive ones, by loads with the "
+                                     "non-temporal hint as the kernel's page loads are; measured in this run",
+                             "without_the_hint": {"GBps": round(ceil["gather_plain_loads"], 1),
+                                                  "sequential_GBps": round(ceil["sequential_plain_loads"], 1)},
                              "ticketed_tail": dict(tail, note="the scattered stream again, its end handed out at run time through an "
                                                               "atomic counter in chunks of 64 KB instead of split evenly beforehand")}
     out["pct_of_ceiling"] = round(100 * gbps / ceil["gather_4KB_tiles"], 2)

@@ -319,8 +319,10 @@ ra_status rollout_attn_set_wave_weights(ra_ctx *ctx, int32_t kv_dtype, int32_t h
  * workgroup, all resident) with its LDS ring of 16 KB entries fed by direct global-to-LDS loads; every wave reads
  * entries_per_wave entries, each as 16384 / granule_bytes pieces of granule_bytes (a power of two, 1024..16384; 4096
  * is the K or V tile of one page and head at head dim 128 in bf16), each piece from a place of its own: a fixed
- * permutation of the buffer's granules when scattered != 0, consecutive granules (the grid sweeps the buffer, wrapping
- * around) otherwise.  buf: dev, read only, 16-byte aligned, buf_bytes a power of two >= 16384.  *bytes_read (may be
+ * permutation of the buffer's granules when bit 0 of scattered is set, consecutive granules (the grid sweeps the
+ * buffer, wrapping around) otherwise.  The loads carry the non-temporal hint, as the attention kernel's page loads do
+ * (a decode step reads every page once); with bit 1 of scattered set they are ordinary loads, for comparison.
+ * buf: dev, read only, 16-byte aligned, buf_bytes a power of two >= 16384.  *bytes_read (may be
  * NULL) receives the bytes the launch reads.  Enqueued on hip_stream; the caller times it. */
 ra_status rollout_attn_debug_stream(ra_ctx *ctx, const void *buf, size_t buf_bytes, int32_t granule_bytes, int32_t scattered,
                                     int32_t entries_per_wave, void *hip_stream, size_t *bytes_read);

@@ -217,7 +217,7 @@ def rollout_attn_set_wave_weights(ctx, weights, kv_dtype=RA_KV_BF16, head_dim=12
 def rollout_attn_debug_stream(ctx, buf_ptr, buf_bytes, granule_bytes, scattered, entries_per_wave, hip_stream=None):
     """Enqueues the streaming probe; returns the bytes the launch reads."""
     n = ctypes.c_size_t()
-    _check(load_library().rollout_attn_debug_stream(ctx, buf_ptr, buf_bytes, granule_bytes, int(bool(scattered)), entries_per_wave,
+    _check(load_library().rollout_attn_debug_stream(ctx, buf_ptr, buf_bytes, granule_bytes, int(scattered) & 3, entries_per_wave,
                                                     hip_stream, ctypes.byref(n)), ctx)
     return int(n.value)
 

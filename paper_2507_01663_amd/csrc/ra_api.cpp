@@ -553,7 +553,7 @@ ra_status rollout_attn_debug_stream(ra_ctx *c, const void *buf, size_t buf_bytes
     int prev = 0;
     hipError_t e = hipGetDevice(&prev);
     if (e == hipSuccess && prev != c->device) e = hipSetDevice(c->device);
-    if (e == hipSuccess) e = ra::launch_stream_probe(buf, buf_bytes, granule_bytes, scattered != 0, entries_per_wave, waves, (hipStream_t)stream);
+    if (e == hipSuccess) e = ra::launch_stream_probe(buf, buf_bytes, granule_bytes, scattered & 3, entries_per_wave, waves, (hipStream_t)stream);
     if (prev != c->device) (void)hipSetDevice(prev);
     if (e != hipSuccess) { set_err(c, "HIP: %s", hipGetErrorString(e)); return RA_ERR_DEVICE; }
     if (bytes_read) *bytes_read = (size_t)waves * entries_per_wave * 16384;

@@ -1567,9 +1567,11 @@ __global__ __launch_bounds__(64) void stream_probe_kernel(const uint8_t *__restr
             // load n moves 1 KB: piece (n * 1024) >> granule_shift, offset inside the piece the rest
             const uint32_t piece = (uint32_t)(n * 1024) >> granule_shift, within = (uint32_t)(n * 1024) & ((1u << granule_shift) - 1);
             uint32_t g = first + piece;
-            if (scattered) g = g * 2654435761u + 12345u; // odd multiplier: a permutation modulo a power of two
+            if (scattered & 1) g = g * 2654435761u + 12345u; // odd multiplier: a permutation modulo a power of two
             const uint8_t *src = buf + ((size_t)(g & granule_mask) << granule_shift) + within;
-            dma16_base<true>((uint32_t)(16 * lane), src, lds_addr + (slot & 1) * 16384 + 1024 * n); // as the attention kernel's page loads
+            // streaming loads, as the attention kernel's page loads are (bit 1 of `scattered`: ordinary loads, to compare)
+            if (scattered & 2) dma16_base<false>((uint32_t)(16 * lane), src, lds_addr + (slot & 1) * 16384 + 1024 * n);
+            else dma16_base<true>((uint32_t)(16 * lane), src, lds_addr + (slot & 1) * 16384 + 1024 * n);
         }
     };
     // n entries first, first + step, ... through the two-slot ring; drained at the end

@@ -22,7 +22,7 @@ def test_probes_run_and_report_their_bytes(dec):
     buf = torch.zeros(1 << 26, dtype=torch.uint8, device="cuda:0")
     ptr = ctypes.c_void_p(buf.data_ptr())
     waves = ra.rollout_attn_wave_count(dec.ctx, ra.RA_KV_BF16, 128)
-    for scattered in (0, 1):
+    for scattered in (0, 1, 2, 3):         # bit 0: scattered places; bit 1: ordinary loads instead of streaming ones
         for granule in (1024, 4096, 16384):
             assert ra.rollout_attn_debug_stream(dec.ctx, ptr, buf.numel(), granule, scattered, 5) == waves * 5 * 16384
     # static part of 3 entries, the other 2 per wave as tickets of 4 entries (the last chunk rounded up), twice in a
