@@ -1305,6 +1305,7 @@ template <int D, int KVB, int NST, int NPEND, bool SELF> __device__ __forceinlin
     SpanPlan sp;
     sp.done = !SELF;
     bool first_pass = true;
+    int keep = -2; // records of the list to keep in the workspace (-1: say that there is none), -2: nothing to do
     // the wave's two cut points of the share table: asked for now, needed when the rows are known
     const int share_lo = SELF ? uniform_load(a.wave_cum, c) : 0, share_hi = SELF ? uniform_load(a.wave_cum, c + 1) : 0;
     do {
@@ -1318,6 +1319,7 @@ template <int D, int KVB, int NST, int NPEND, bool SELF> __device__ __forceinlin
             // A call that reuses the schedule takes the list that the span's wave kept in the workspace when it planned
             // (one trip to memory in place of the planning pass), if that wave's whole span went into one list.
             const bool was_first = first_pass;
+            keep = -2;
             int kept = -1;
             if (a.reuse_lists && was_first) kept = uniform_load(a.ws.self_cnt, c);
             if (kept >= 0) {
@@ -1350,14 +1352,7 @@ template <int D, int KVB, int NST, int NPEND, bool SELF> __device__ __forceinlin
                 first_pass = false;
             }
             wk_n = list_segments(a, T, sp, c, (int32_t *)(plan_base + M::kPlanBase), M::kRecCap, plan_lane);
-            if (was_first && !a.reuse_lists) {
-                // keep the list for later calls on this schedule (the layers of one decode step)
-                const int keep = sp.done ? wk_n : -1;
-                uint8_t *dst = a.ws.self_rec + (int64_t)c * kSelfListBytes;
-                for (int off = 16 * plan_lane; off < 32 * keep; off += 1024)
-                    *(int4 *)(dst + off) = *(const int4 *)(plan_base + M::kPlanBase + off);
-                if (plan_lane == 0) a.ws.self_cnt[c] = keep;
-            }
+            if (was_first && !a.reuse_lists) keep = sp.done ? wk_n : -1;
             }
             wk_j = 0;
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // the tables have been read: the ring may overwrite them
@@ -1397,6 +1392,15 @@ template <int D, int KVB, int NST, int NPEND, bool SELF> __device__ __forceinlin
                 }
                 ring.issued++;
             }
+        }
+        if (SELF && keep >= -1) {
+            // Keep the list for later calls on this schedule (the layers of one decode step), now that the first loads
+            // are on their way: the stores cost nothing that way.  (They are younger than those loads, so the waits
+            // for the ring's first entries are only stricter for them.)
+            uint8_t *dst = a.ws.self_rec + (int64_t)c * kSelfListBytes;
+            for (int off = 16 * ln; off < 32 * keep; off += 1024) *(int4 *)(dst + off) = *(const int4 *)(lds + M::kPlanBase + off);
+            if (ln == 0) a.ws.self_cnt[c] = keep;
+            keep = -2;
         }
         while (has_cur) {
             const bool has_nxt = advance(nxt);
