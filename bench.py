@@ -55,7 +55,7 @@ def child_summary(extra, timeout=600):
     try:
         r = subprocess.run(cmd, capture_output=True, text=True, timeout=timeout)
         e = json.loads([l for l in r.stdout.splitlines() if l.startswith("{")][-1])
-        keep = ("value", "unit", "ms_per_step", "steps_per_s", "pct_of_hbm_peak", "phases_ms", "roofline", "schedule_reused", "consecutive_steps")
+        keep = ("value", "unit", "ms_per_step", "steps_per_s", "pct_of_hbm_peak", "phases_ms", "roofline", "schedule_reused", "two_streams", "consecutive_steps")
         out = {k: e[k] for k in keep if k in e}
         out["workload"] = e["config"]["workload"]
         out["algorithmic_MB_per_step"] = e["config"]["algorithmic_MB_per_step"]
@@ -308,6 +308,25 @@ def main():
     for d in devs:
         d.set(flags)
     del wss
+
+    # Two independent batches taking turns on two streams (two contexts, two workspaces; even and odd steps of the same
+    # rotation): a step's planning pass and the thinning out at its end run under the other stream's page stream.  Not
+    # what `value` measures (one stream, as one model's decode steps come), reported beside it.
+    if len(devs) % 2 == 0:
+        dec2 = ra.Decoder(0)
+        two = [(dec, torch.cuda.Stream(0)), (dec2, torch.cuda.Stream(0))]      # default priority
+        for i in range(2 * len(devs)):
+            two[i % 2][0].decode(devs[i % len(devs)].c, two[i % 2][1])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            two[i % 2][0].decode(devs[i % len(devs)].c, two[i % 2][1])
+        torch.cuda.synchronize()
+        two_wall = time.perf_counter() - t0
+        out["two_streams"] = {"ms_per_step": round(two_wall * 1e3 / args.steps, 5), "GBps": round(total_bytes / two_wall / 1e9, 1),
+                              "note": "the same steps issued alternately on two streams by two contexts (an instance always on "
+                                      "the same stream): independent batches overlap each other's planning and tail"}
+        dec2.close()
 
     # instance 0's result for the parity check at the end, taken before anything below writes to the pools
     dec.decode(devs[0].c, stream)
