@@ -87,7 +87,8 @@ def main():
     ap.add_argument("--no-sharing", action="store_true", help="ignore the prompt-group hint (A/B)")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run three 1 GiB device copies (counter calibration)")
     ap.add_argument("--no-extras", "--no-e4m3", dest="no_extras", action="store_true",
-                    help="leave out the child-process runs (e4m3 cache, tail32b, stream72b) that the default run appends")
+                    help="leave out the child-process runs (e4m3 cache, tail32b, stream72b) and the two-stream run that the default "
+                         "run appends (a profiler then sees the one-stream steps alone, no launches that overlap)")
     ap.add_argument("--consecutive", action="store_true",
                     help="streaming workloads: time the configuration's consecutive decode steps one after the other, each with "
                          "its own lengths, block table and queries uploaded before it (the upload timed separately)")
@@ -312,7 +313,7 @@ def main():
     # Two independent batches taking turns on two streams (two contexts, two workspaces; even and odd steps of the same
     # rotation): a step's planning pass and the thinning out at its end run under the other stream's page stream.  Not
     # what `value` measures (one stream, as one model's decode steps come), reported beside it.
-    if len(devs) % 2 == 0:
+    if len(devs) % 2 == 0 and not args.no_extras:
         dec2 = ra.Decoder(0)
         two = [(dec, torch.cuda.Stream(0)), (dec2, torch.cuda.Stream(0))]      # default priority
         for i in range(2 * len(devs)):
