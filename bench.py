@@ -242,15 +242,22 @@ def main():
         out["weight_copy"] = copy_info
 
     # What the memory system delivers to this access pattern with no arithmetic at all: the attention kernel's grid
-    # and LDS ring streaming 4 KB tiles from scattered places (its own pattern), and consecutive ones.  A buffer of
-    # 4 GiB, far beyond the last-level cache; 1 GiB per launch.
-    buf = torch.empty(1 << 32, dtype=torch.uint8, device="cuda:0")
+    # and LDS ring streaming 4 KB tiles from scattered places (its own pattern), and consecutive ones.  The buffer is
+    # as large as the K/V pools the timed steps rotate through (a power of two, 4 to 64 GiB: what the probe reaches
+    # falls with the memory it ranges over, 7.1 TB/s over 1 GiB, 6.5-6.65 from 16 GiB up), a launch reads what a step does.
+    pools = {}
+    for d in devs:
+        for t in (d.k_pool, d.v_pool):
+            pools[t.data_ptr()] = t.numel() * t.element_size()
+    footprint = sum(pools.values())
+    buf_log2 = min(36, max(32, (footprint - 1).bit_length()))
+    buf = torch.empty(1 << buf_log2, dtype=torch.uint8, device="cuda:0")
     buf.random_(0, 255)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     import ctypes
     sp = ctypes.c_void_p(stream.cuda_stream)
     waves = ra.rollout_attn_wave_count(dec.ctx, ra.RA_KV_BF16, 128)
-    entries = max(1, (1 << 30) // (waves * 16384))
+    entries = max(1, int(round(sum(alg_bytes) / len(alg_bytes) / (waves * 16384))))
     ceil = {}
     for label, scattered in (("gather_4KB_tiles", 1), ("sequential", 0), ("gather_plain_loads", 3), ("sequential_plain_loads", 2)):
         for _ in range(3):
@@ -276,6 +283,8 @@ def main():
         tail["last_1/%d_ticketed_GBps" % frac] = round(n / (ev0.elapsed_time(ev1) / 10) / 1e6, 1)
     del buf
     out["stream_ceiling"] = {"GBps": round(ceil["gather_4KB_tiles"], 1), "sequential_GBps": round(ceil["sequential"], 1), "unit": "GB/s",
+                             "buffer_GiB": 1 << (buf_log2 - 30), "kv_pools_GiB": round(footprint / 2**30, 2),
+                             "MB_per_launch": round(entries * waves * 16384 / 1e6, 1),
                              "pct_of_hbm_peak": round(100 * ceil["gather_4KB_tiles"] / HBM_PEAK_GBPS, 2),
                              "note": "read-only probe with the attention kernel's grid and LDS ring, no arithmetic: 4 KB tiles from "
                                      "scattered places (the kernel's own pattern) and from consecutive ones, by loads with the "
