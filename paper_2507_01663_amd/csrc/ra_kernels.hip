@@ -1578,29 +1578,30 @@ __global__ __launch_bounds__(64) void stream_probe_kernel(const uint8_t *__restr
             else dma16_base<true>((uint32_t)(16 * lane), src, lds_addr + (slot & 1) * 16384 + 1024 * n);
         }
     };
-    // n entries first, first + step, ... through the two-slot ring; drained at the end
-    auto stream = [&](uint32_t first, uint32_t step, int n) __attribute__((always_inline)) {
-        if (n <= 0) return;
-        issue(first, 0);
-        for (int s = 0; s < n; s++) {
-            if (s + 1 < n) {
-                issue(first + (uint32_t)(s + 1) * step, s + 1);
-                wait_vmcnt<16>();
-            } else {
-                wait_vmcnt<0>();
-            }
-        }
+    // The wave's own entries (numbers w, w + waves, ...), then chunks of consecutive entries drawn from the counter,
+    // through the two-slot ring without a drain in between: the ticket is asked for while the run's last entry is
+    // still in flight, and its wait is that entry's wait.  Every wave leaves when the counter has passed the last ticket.
+    uint32_t cur = blockIdx.x, step = gridDim.x;
+    int n = entries, slot = 0;
+    auto ticket = [&]() __attribute__((always_inline)) {
+        uint32_t t = 0;
+        if (lane == 0) t = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        t = __builtin_amdgcn_readfirstlane(t);
+        if (t < tickets) cur = gridDim.x * (uint32_t)entries + t * (uint32_t)chunk, step = 1u, n = chunk;
     };
-    // wave w's own entries: numbers w, w + waves, ...
-    stream(blockIdx.x, gridDim.x, entries);
-    if (chunk > 0) {
-        for (;;) { // every wave leaves when the counter has passed the last ticket
-            uint32_t t = 0;
-            if (lane == 0) t = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            t = __builtin_amdgcn_readfirstlane(t);
-            if (t >= tickets) break;
-            stream(gridDim.x * (uint32_t)entries + t * (uint32_t)chunk, 1u, chunk);
+    if (n <= 0 && chunk > 0) ticket();
+    if (n > 0) issue(cur, slot);
+    while (n > 0) {
+        n--;
+        cur += step;
+        if (n == 0 && chunk > 0) ticket();
+        if (n > 0) {
+            issue(cur, slot ^ 1);
+            wait_vmcnt<16>();
+        } else {
+            wait_vmcnt<0>();
         }
+        slot ^= 1;
     }
     if (clocks && lane == 0) clocks[blockIdx.x] = wall_clock64() - t0;
 }
