@@ -1677,12 +1677,13 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(Launch a, const in
         const int d4 = (threadIdx.x % tpr) * 4;
         float M = -INFINITY, wsum = 0.f;
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        if (npfx <= 2 && nown <= 3) {
-            // the usual case: at most two prefix partials and three own ones; all ten loads go out together
-            float l[5];
-            f32x4 v[5];
+        if (npfx <= 2 && nown <= 4) {
+            // the usual case: at most two prefix partials and four own ones; all twelve loads go out together
+            constexpr int NP = 6;
+            float l[NP];
+            f32x4 v[NP];
 #pragma unroll
-            for (int i = 0; i < 5; i++) {
+            for (int i = 0; i < NP; i++) {
                 const PartList &p = pl[i < 2 ? 0 : 1];
                 const int c = p.c_lo + (i < 2 ? i : i - 2);
                 const bool have = c <= p.c_hi;
@@ -1690,9 +1691,9 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(Launch a, const in
                 v[i] = have ? *(const f32x4 *)(p.o + c * p.ostride + (int64_t)hl * D + d4) : f32x4{0.f, 0.f, 0.f, 0.f};
             }
 #pragma unroll
-            for (int i = 0; i < 5; i++) M = fmaxf(M, l[i]);
+            for (int i = 0; i < NP; i++) M = fmaxf(M, l[i]);
 #pragma unroll
-            for (int i = 0; i < 5; i++) {
+            for (int i = 0; i < NP; i++) {
                 const float wgt = l[i] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(l[i] - M);
                 wsum += wgt;
                 acc += wgt * v[i];
