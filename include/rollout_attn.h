@@ -133,6 +133,8 @@ uint32_t rollout_attn_abi_version(void);
  *   ROLLOUT_ATTN_WAVES_PER_CU=1..16 attention workgroups per compute unit (default: as many as are resident)
  *   ROLLOUT_ATTN_COST_PREFIX=1..16, ROLLOUT_ATTN_COST_ITEM=0..256   scheduling weights of a shared-prefix page and
  *                                   of a segment (a page of a sequence's own weighs 4)
+ *   ROLLOUT_ATTN_COST_ITEM_PREFIX=0..1024   ... of a segment of shared-prefix pages, whose partial result is
+ *                                   written in mid-stream (default: 16 for bf16 pools, 48 for e4m3 pools)
  *   ROLLOUT_ATTN_SELF_PLAN=0        always launch the schedule kernels (default: batches of up to 512 sequences and
  *                                   511 groups are scheduled by the attention workgroups themselves, each for its own
  *                                   share of the work, which saves a kernel; the schedule is the same either way)

@@ -22,6 +22,7 @@ struct ra_ctx {
     int stages[2][2]; // LDS ring depth, same indices
     int cost_prefix[2]; // scheduling weight of a shared-prefix page, [e4m3 KV]
     int cost_item;   // ... of a segment, on top of its pages
+    int cost_item_pfx[2]; // ... of a shared-prefix row's segment (bf16, e4m3 pools)
     int xcd_w[8];              // default share of the page stream per accelerator die, per mille of the mean
     int32_t *wave_cum[2][2];   // device: running sums of the workgroups' shares, [e4m3 KV][D == 128], kMaxWaves + 1 each
     uint32_t *tickets;         // device: the streaming probe's ticket counter (cleared by every launch that uses it)
@@ -114,6 +115,7 @@ void fill_launch(ra::Launch &a, const ra_ctx *ctx, const ra_problem *p)
     a.recip_g = (65536 + a.G - 1) / a.G;
     a.cost_prefix = ctx ? ctx->cost_prefix[a.kv_fp8] : (a.kv_fp8 ? ra::kCostPrefixFp8 : ra::kCostPrefix);
     a.cost_item = ctx ? ctx->cost_item : ra::kCostItem;
+    a.cost_item_pfx = ctx ? ctx->cost_item_pfx[a.kv_fp8] : (a.kv_fp8 ? ra::kCostItemPrefixFp8 : ra::kCostItemPrefix);
     a.wave_cum = ctx ? ctx->wave_cum[a.kv_fp8][p->D == 128] : nullptr;
     a.q = (const uint16_t *)p->q;
     a.k_pool = (const uint8_t *)p->k_pool; a.v_pool = (const uint8_t *)p->v_pool;
@@ -166,6 +168,8 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
     c->cost_prefix[0] = ra::kCostPrefix;
     c->cost_prefix[1] = ra::kCostPrefixFp8;
     c->cost_item = ra::kCostItem;
+    c->cost_item_pfx[0] = ra::kCostItemPrefix;
+    c->cost_item_pfx[1] = ra::kCostItemPrefixFp8;
     // Share of the page stream each accelerator die's workgroups get, per mille of the mean (workgroups are dealt to the
     // dies round-robin).  The odd dies stream about a tenth slower than the even ones on the machines measured; beyond
     // that the pattern is per workgroup and per machine: rollout_attn_set_wave_weights takes a measured one.
@@ -195,6 +199,10 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
     if (const char *ev = getenv("ROLLOUT_ATTN_COST_ITEM")) {
         int v = atoi(ev);
         if (v >= 0 && v <= 256) c->cost_item = v;
+    }
+    if (const char *ev = getenv("ROLLOUT_ATTN_COST_ITEM_PREFIX")) {
+        int v = atoi(ev);
+        if (v >= 0 && v <= 1024) c->cost_item_pfx[0] = c->cost_item_pfx[1] = v;
     }
     hipDeviceProp_t prop;
     e = hipGetDeviceProperties(&prop, device);

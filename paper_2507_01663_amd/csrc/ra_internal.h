@@ -15,6 +15,8 @@ constexpr int kSelfListBytes = 4096; // room for the list a self-planning wave k
 constexpr int kCostPrefix = 8;      // ... of a shared-prefix page of a bf16 pool (64 query rows per byte read: more time per page)
 constexpr int kCostPrefixFp8 = 5;   // ... of an e4m3 pool (32 query rows)
 constexpr int kCostItem = 16;       // ... of a segment, on top of its pages
+constexpr int kCostItemPrefix = 16;    // ... of a shared-prefix row's segment (bf16 pools)
+constexpr int kCostItemPrefixFp8 = 48; // ... (e4m3 pools)
 
 // Device pointers into the caller's workspace.  All offsets are fixed by the shape alone.
 struct Workspace {
@@ -42,7 +44,7 @@ struct Workspace {
 
 struct Launch {
     int32_t B, Hq, Hkv, D, G, num_pages, max_pages, num_groups;
-    int32_t kv_fp8, share, waves, stages, cost_prefix, cost_item;
+    int32_t kv_fp8, share, waves, stages, cost_prefix, cost_item, cost_item_pfx;
     int32_t prefix_rows;     // query rows a shared-prefix work row carries (members x heads per kv head, at most)
     int32_t members_per_row; // = prefix_rows / G
     int32_t recip_g;         // ceil(2^16 / G): (x * recip_g) >> 16 == x / G for 0 <= x <= 64

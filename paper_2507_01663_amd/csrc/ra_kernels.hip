@@ -298,7 +298,7 @@ __device__ __forceinline__ void rows_phase(const Launch &a, const RowsBuf &R, in
 #pragma unroll 1
         for (int k = 0; k * MPR < cnt; k++) {
             const int left = cnt - k * MPR;
-            row_start[r0 + k] = a.cost_item + np * a.cost_prefix;
+            row_start[r0 + k] = a.cost_item_pfx + np * a.cost_prefix;
             tab[r0 + k] = make_int4(poff[g], grp_membase[g] + k * MPR, left < MPR ? left : MPR, np);
         }
     }
@@ -432,7 +432,7 @@ __device__ __forceinline__ void spans_phase(const Launch &a, const Cuts &cut, co
                     const int S = rs + kvh * ic;
                     if (S >= hi) break;
                     int p_lo, p_hi;
-                    span_pages(S + a.cost_item, cw, info.w, lo, hi, p_lo, p_hi);
+                    span_pages(S + (prefix ? a.cost_item_pfx : a.cost_item), cw, info.w, lo, hi, p_lo, p_hi);
                     if (p_lo >= p_hi) continue;
                     if (chain < 0) chain = nspans + (r * a.Hkv + kvh) / kChunkSegs; // where this span's further chunks go
                     if (n == kChunkSegs) { // chain another chunk
@@ -474,8 +474,8 @@ __device__ __forceinline__ void merge_desc_of(const Launch &a, const Cuts &cut, 
     }
     if (prow >= 0) {
         const int ic = row_start[prow + 1] - row_start[prow];
-        const int n = (ic - a.cost_item) / a.cost_prefix;
-        const int S = a.Hkv * row_start[prow] + kvh * ic + a.cost_item;
+        const int n = (ic - a.cost_item_pfx) / a.cost_prefix;
+        const int S = a.Hkv * row_start[prow] + kvh * ic + a.cost_item_pfx;
         pfx = make_int4(n, cut.span_of(S), cut.span_of(S + a.cost_prefix * (n - 1)), 0);
     }
     a.ws.merge_desc[2 * i] = own;
@@ -1074,7 +1074,7 @@ __device__ __forceinline__ void wave_rows(const Launch &a, const WaveTables &T, 
         rows_g[k] = 0, cost_g[k] = 0;
         if (k < KG && gl < NG) {
             rows_g[k] = ((T.gcnt[gl] + MPR - 1) * rMPR) >> 20;
-            cost_g[k] = a.cost_item + (T.poff[gl + 1] - T.poff[gl]) * a.cost_prefix;
+            cost_g[k] = a.cost_item_pfx + (T.poff[gl + 1] - T.poff[gl]) * a.cost_prefix;
             rows_l += rows_g[k];
             cost_l += rows_g[k] * cost_g[k];
         }
@@ -1162,7 +1162,7 @@ __device__ __forceinline__ int list_segments(const Launch &a, const WaveTables &
                 break;
             }
             int p_lo, p_hi;
-            span_pages(S + a.cost_item, cw, info.w, sp.lo, sp.hi, p_lo, p_hi);
+            span_pages(S + (prefix ? a.cost_item_pfx : a.cost_item), cw, info.w, sp.lo, sp.hi, p_lo, p_hi);
             if (p_lo >= p_hi) continue;
             if (n + need > cap) return n;
             int4 r0, r1;
