@@ -631,6 +631,22 @@ template <int D> __device__ __forceinline__ void store_pending(const Launch &a, 
     }
 }
 
+// The partial of a shared-prefix segment (NQT tiles of 16 query rows), held one tile to a Pending: written out.
+template <int D, int NQT, int NP> __device__ __forceinline__ void store_prefix_partial(const Launch &a, const Pending<D> (&pk)[NP], int64_t slot, int nrows, int lane)
+{
+    const int j = lane >> 4;
+#pragma unroll
+    for (int t = 0; t < NQT; t++) {
+        const int row = 16 * t + (lane & 15);
+        if (row < nrows) {
+            float *dst = a.ws.pfx_o + (slot * a.prefix_rows + row) * D + 4 * j;
+#pragma unroll
+            for (int dt = 0; dt < D / 16; dt++) *(f32x4 *)(dst + 16 * dt) = pk[t].o[dt];
+            if (j == 0) a.ws.pfx_lse[slot * a.prefix_rows + row] = pk[t].lse2;
+        }
+    }
+}
+
 // Loads of one stage (two pages: K0 K1 V0 V1, and for e4m3 the four scales) of a segment into a ring slot.
 template <int D, int KVB, int NST>
 __device__ __forceinline__ void issue_stage(const Launch &a, const LaneConst<D, KVB> &lc, const Segment &sg, int st, int pid0,
@@ -721,11 +737,12 @@ __device__ __forceinline__ void issue_qrows(const Launch &a, const uint16_t *__r
 // min(NST-1, entries) entries of this segment are in flight; on exit the same holds for `nxt`.  Query rows of an
 // own-pages segment (NQT == 1) wait in the query slot; those of a shared-pages segment are its first ring entry.
 // A one-tile partial goes back in `ret` (normalised, with its log2-sum-exp); a shared-prefix partial is stored.
-template <int D, int KVB, int NQT, int NST>
+template <int D, int KVB, int NQT, int NST, int NP>
 __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__restrict__ q, const Segment &cur, bool has_nxt,
                                             const Segment &nxt, Ring &ring, const LaneConst<D, KVB> &lc, uint8_t *lds,
-                                            uint32_t lds_addr, Pending<D> &ret, int lane)
+                                            uint32_t lds_addr, Pending<D> &ret, Pending<D> (&pk)[NP], bool park, int lane)
 {
+    static_assert(NQT == 1 || NQT <= NP, "a shared-prefix partial has a waiting register set per tile");
     using G = Geo<D, KVB>;
     using M = LdsMap<D, KVB, NST>;
     static_assert((NST - 1) * G::kDmaPerStage < 64, "the vector-memory counter holds 6 bits");
@@ -931,6 +948,11 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
 #pragma unroll
             for (int dt = 0; dt < G::kDTiles; dt++) ret.o[dt] = o[t][dt] * inv;
             ret.lse2 = lse2;
+        } else if (KVB == 2 && park) {
+            // kept in the registers that wait for own partials (the caller has seen that they are free)
+#pragma unroll
+            for (int dt = 0; dt < G::kDTiles; dt++) pk[t < NP ? t : 0].o[dt] = o[t][dt] * inv;
+            pk[t < NP ? t : 0].lse2 = lse2;
         } else {
             const int row = 16 * t + (lane & 15);
             if (row < cur.nrows) {
@@ -1241,8 +1263,16 @@ template <int D, int KVB, int NST, int NPEND, bool SELF> __device__ __forceinlin
     LaneConst<D, KVB> lc;
     if (!SELF) lane_setup<D, KVB>(lc, lane, a.stride_token_b);
     Ring ring = {0, 0};
-    Pending<D> pend[NPEND], fresh; // finished partials wait in registers for the end of the wave
+    // Finished partials wait in registers for the end of the wave: up to NPEND of own-pages segments (and the one
+    // just finished, `fresh`), or, while none of those waits, one of a shared-prefix segment, a tile to each of them.
+    // Stores in mid-stream cost more than their bytes: the ring's next wait is also a wait for them, and writes among
+    // the reads slow every wave's stream.
+    static_assert(PrefixTiles<KVB>::value == NPEND + 1, "a shared-prefix partial fills the waiting registers exactly");
+    Pending<D> pend[NPEND + 1];
+    Pending<D> &fresh = pend[NPEND];
     int npend = 0;
+    int parked_rows = 0; // > 0: a shared-prefix partial of that many rows waits in pend[]
+    int64_t parked_slot = 0;
 
     // ---- the work list: segments in stream order ----
     // Schedule kernels' list: a chain of chunks of eight 8-dword records (a header and up to seven segments); a chunk
@@ -1405,7 +1435,11 @@ template <int D, int KVB, int NST, int NPEND, bool SELF> __device__ __forceinlin
         while (has_cur) {
             const bool has_nxt = advance(nxt);
             if (!cur.prefix) {
-                run_segment<D, KVB, 1, NST>(a, q, cur, has_nxt, nxt, ring, lc, lds, lds_addr, fresh, ln);
+                if (parked_rows) { // the registers are wanted
+                    store_prefix_partial<D, PrefixTiles<KVB>::value>(a, pend, parked_slot, parked_rows, ln);
+                    parked_rows = 0;
+                }
+                run_segment<D, KVB, 1, NST>(a, q, cur, has_nxt, nxt, ring, lc, lds, lds_addr, fresh, pend, false, ln);
                 fresh.slot = cur.slot;
                 if (npend == NPEND) { // full: write the oldest out
                     store_pending<D>(a, pend[0], ln);
@@ -1418,7 +1452,10 @@ template <int D, int KVB, int NST, int NPEND, bool SELF> __device__ __forceinlin
                     if (k == npend) pend[k] = fresh;
                 npend++;
             } else {
-                run_segment<D, KVB, PrefixTiles<KVB>::value, NST>(a, q, cur, has_nxt, nxt, ring, lc, lds, lds_addr, fresh, ln);
+                // (bf16 pools only: the e4m3 kernels, held to half the register file, have no room for it)
+                const bool park = KVB == 2 && npend == 0 && parked_rows == 0;
+                run_segment<D, KVB, PrefixTiles<KVB>::value, NST>(a, q, cur, has_nxt, nxt, ring, lc, lds, lds_addr, fresh, pend, park, ln);
+                if (park) parked_rows = cur.nrows, parked_slot = cur.slot;
             }
             cur = nxt;
             has_cur = has_nxt;
@@ -1427,6 +1464,8 @@ template <int D, int KVB, int NST, int NPEND, bool SELF> __device__ __forceinlin
         for (int k = 0; k < NPEND; k++)
             if (k < npend) store_pending<D>(a, pend[k], ln);
         npend = 0;
+        if (parked_rows) store_prefix_partial<D, PrefixTiles<KVB>::value>(a, pend, parked_slot, parked_rows, ln);
+        parked_rows = 0;
     } while (!sp.done);
 }
 
