@@ -100,7 +100,6 @@ template <int D, int KVB> struct Geo {
 template <int D, int KVB> struct LaneConst {
     int dma_row[Geo<D, KVB>::kDmaPerTile];
     int dma_off[Geo<D, KVB>::kDmaPerTile];
-    int q_row[D * 2 / 64], q_off[D * 2 / 64]; // placement of a tile of 16 contiguous bf16 query rows
     int kq_off[D / 32];                       // where lane (row, j) finds its Q operand of k-step i in that tile
     int k_off[Geo<D, KVB>::kKReads];
     int v_off[Geo<D, KVB>::kDTiles];
@@ -121,13 +120,6 @@ template <int D, int KVB> __device__ __forceinline__ void lane_setup(LaneConst<D
     {
         // query tile: 16 rows of D bf16, 16-byte units swizzled inside the row like a bf16 K tile
         constexpr int QU = D * 2 / 16, QM = QU - 1;
-#pragma unroll
-        for (int n = 0; n < D * 2 / 64; n++) {
-            int slot = 64 * n + lane;
-            int r = slot / QU, cp = slot % QU;
-            lc.q_row[n] = r;
-            lc.q_off[n] = r * (D * 2) + (cp ^ (swz(r) & QM)) * 16;
-        }
         const int r = lane & 15, j = lane >> 4;
 #pragma unroll
         for (int i = 0; i < D / 32; i++) {

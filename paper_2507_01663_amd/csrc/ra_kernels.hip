@@ -677,14 +677,20 @@ __device__ __forceinline__ void issue_stage(const Launch &a, const LaneConst<D, 
 // Query rows of an own-pages segment: the G heads of (b, kvh) are contiguous in q; rows G..15 read zeros.
 template <int D, int KVB, int NST>
 __device__ __forceinline__ void issue_q(const Launch &a, const uint16_t *__restrict__ q, const LaneConst<D, KVB> &lc,
-                                        const Segment &sg, uint32_t lds_addr)
+                                        const Segment &sg, uint32_t lds_addr, int lane)
 {
     using M = LdsMap<D, KVB, NST>;
     const uint8_t *src = (const uint8_t *)(q + ((int64_t)sg.b * a.Hq + (int64_t)sg.kvh * a.G) * D);
     const uint32_t dst = lds_addr + M::kQBase;
+    // the tile in LDS: 16 rows of D bf16, 16-byte units swizzled inside the row like a bf16 K tile (worked out here,
+    // once per segment, rather than kept in registers through the stream)
+    constexpr int QU = D * 2 / 16, QM = QU - 1;
+    asm volatile("" : "+v"(lane)); // (opaque, or the compiler works the placement out ahead of the loop after all)
 #pragma unroll
     for (int n = 0; n < D * 2 / 64; n++) {
-        const void *p = lc.q_row[n] < a.G ? (const void *)(src + lc.q_off[n]) : a.zeros;
+        const int slot = 64 * n + lane;
+        const int r = slot / QU, cp = slot % QU;
+        const void *p = r < a.G ? (const void *)(src + r * (D * 2) + (cp ^ (swz(r) & QM)) * 16) : a.zeros;
         dma16(p, dst + 1024 * n);
     }
 }
@@ -800,7 +806,7 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
             } else if (rel == niter && nxt_ql) {
                 issue_qrows<D, KVB, NST>(a, q, lc, nxt, ring.issued % NST, lds_addr);
             } else {
-                if (rel == niter) issue_q<D, KVB, NST>(a, q, lc, nxt, lds_addr);
+                if (rel == niter) issue_q<D, KVB, NST>(a, q, lc, nxt, lds_addr, lane);
                 issue_stage<D, KVB, NST>(a, lc, nxt, rel - niter - nxt_ql, nid0, nid1, ring.issued % NST, lds_addr, lane);
             }
             ring.issued++;
@@ -927,7 +933,9 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
                 const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(vb + G::kTile + lc.v_off[dt]));
                 vf = __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7));
             } else {
-                const i32x2 vc = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2)(vb + lc.v_off[dt]));
+                // (the tile swizzle is an XOR of the unit number and the ring's slots start on multiples of 256 bytes, so
+                // tile dt's address is tile 0's with 16 * dt XORed in: one lane constant instead of one per tile)
+                const i32x2 vc = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2)((vb + lc.v_off[0]) ^ (uint32_t)(16 * dt)));
                 vf = fp8x8_to_bf16(vc[0], vc[1]);
             }
 #pragma unroll
@@ -948,7 +956,7 @@ __device__ __forceinline__ void run_segment(const Launch &a, const uint16_t *__r
 #pragma unroll
             for (int dt = 0; dt < G::kDTiles; dt++) ret.o[dt] = o[t][dt] * inv;
             ret.lse2 = lse2;
-        } else if (KVB == 2 && park) {
+        } else if (park) {
             // kept in the registers that wait for own partials (the caller has seen that they are free)
 #pragma unroll
             for (int dt = 0; dt < G::kDTiles; dt++) pk[t < NP ? t : 0].o[dt] = o[t][dt] * inv;
@@ -1409,7 +1417,7 @@ template <int D, int KVB, int NST, int NPEND, bool SELF> __device__ __forceinlin
         bool has_cur = advance(cur);
         if (has_cur) {
             // prime the ring with the first segment
-            if (!cur.prefix) issue_q<D, KVB, NST>(a, q, lc, cur, lds_addr);
+            if (!cur.prefix) issue_q<D, KVB, NST>(a, q, lc, cur, lds_addr, ln);
             const int n = min(NST - 1, cur.entries());
             for (int k = 0; k < n; k++) {
                 const int st = k - cur.prefix;
@@ -1452,8 +1460,7 @@ template <int D, int KVB, int NST, int NPEND, bool SELF> __device__ __forceinlin
                     if (k == npend) pend[k] = fresh;
                 npend++;
             } else {
-                // (bf16 pools only: the e4m3 kernels, held to half the register file, have no room for it)
-                const bool park = KVB == 2 && npend == 0 && parked_rows == 0;
+                const bool park = npend == 0 && parked_rows == 0;
                 run_segment<D, KVB, PrefixTiles<KVB>::value, NST>(a, q, cur, has_nxt, nxt, ring, lc, lds, lds_addr, fresh, pend, park, ln);
                 if (park) parked_rows = cur.nrows, parked_slot = cur.slot;
             }
