@@ -174,7 +174,7 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
     // dies round-robin).  The odd dies stream about a tenth slower than the even ones on the machines measured; beyond
     // that the pattern is per workgroup and per machine: rollout_attn_set_wave_weights takes a measured one.
     static const int kXcdShare[8] = {1060, 950, 1060, 935, 1045, 930, 1055, 965};
-    static const int kYoungerWaveShare = 870; // per mille of its die's share
+    static const int kYoungerWaveShare = 820; // per mille of its die's share
     for (int x = 0; x < 8; x++) c->xcd_w[x] = kXcdShare[x];
     if (const char *ev = getenv("ROLLOUT_ATTN_XCD_WEIGHTS")) {
         int v[8];
@@ -229,7 +229,7 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
                 for (size_t i = 0; i < w.size(); i++) {
                     w[i] = c->waves[f][d] % 8 == 0 ? c->xcd_w[i % 8] : 1000;
                     // A compute unit has four SIMDs: its fifth and later workgroups (e4m3 pools) each share one with an
-                    // older wave, which the SIMD serves first; measured, they stream an eighth slower than the others.
+                    // older wave, which the SIMD serves first; measured, they stream a sixth slower than the others.
                     if ((int)i >= 4 * c->num_cus) w[i] = w[i] * kYoungerWaveShare / 1000;
                 }
                 e = upload_wave_weights(c, f, d, w.data(), (int)w.size());
