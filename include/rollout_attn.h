@@ -128,7 +128,8 @@ uint32_t rollout_attn_abi_version(void);
  * Tuning knobs, read from the environment here and nowhere else (none changes a result beyond rounding; values
  * out of range are ignored):
  *   ROLLOUT_ATTN_XCD_WEIGHTS=a,..,h the share of the work each of the eight dies' workgroups get, per mille of the
- *                                   mean (700..1400; default: a built-in table, the odd dies about a tenth less)
+ *                                   mean (700..1400; default: a built-in table, the odd dies about a tenth less
+ *                                   for bf16 pools and a twentieth less for e4m3 pools)
  *   ROLLOUT_ATTN_STAGES=2|3, ROLLOUT_ATTN_FP8_STAGES=2|3   depth of the LDS ring for bf16 / e4m3 pools
  *   ROLLOUT_ATTN_WAVES_PER_CU=1..16 attention workgroups per compute unit (default: as many as are resident)
  *   ROLLOUT_ATTN_COST_PREFIX=1..16, ROLLOUT_ATTN_COST_ITEM=0..256   scheduling weights of a shared-prefix page and

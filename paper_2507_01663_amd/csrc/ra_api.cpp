@@ -176,13 +176,16 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
     static const int kXcdShare[8] = {1060, 950, 1060, 935, 1045, 930, 1055, 965};
     static const int kYoungerWaveShare = 820; // per mille of its die's share
     for (int x = 0; x < 8; x++) c->xcd_w[x] = kXcdShare[x];
+    bool own_table = true;
     if (const char *ev = getenv("ROLLOUT_ATTN_XCD_WEIGHTS")) {
         int v[8];
         if (sscanf(ev, "%d,%d,%d,%d,%d,%d,%d,%d", &v[0], &v[1], &v[2], &v[3], &v[4], &v[5], &v[6], &v[7]) == 8) {
             bool ok = true;
             for (int x = 0; x < 8; x++) ok = ok && v[x] >= 700 && v[x] <= 1400; // no span under half the mean
-            if (ok)
+            if (ok) {
                 for (int x = 0; x < 8; x++) c->xcd_w[x] = v[x];
+                own_table = false;
+            }
         }
     }
     c->prefill_stay = -1;
@@ -228,6 +231,9 @@ ra_status rollout_attn_create(ra_ctx **out, int device)
                 std::vector<int32_t> w((size_t)c->waves[f][d]);
                 for (size_t i = 0; i < w.size(); i++) {
                     w[i] = c->waves[f][d] % 8 == 0 ? c->xcd_w[i % 8] : 1000;
+                    // (e4m3 pools: a wave spends more of its time on arithmetic, so the dies' memory paths matter half
+                    // as much; measured with the built-in table at 0, 0.5, 0.75, 1, 1.25 and 1.5 times its spread)
+                    if (f == 1 && own_table) w[i] = 1000 + (w[i] - 1000) / 2;
                     // A compute unit has four SIMDs: its fifth and later workgroups (e4m3 pools) each share one with an
                     // older wave, which the SIMD serves first; measured, they stream a sixth slower than the others.
                     if ((int)i >= 4 * c->num_cus) w[i] = w[i] * kYoungerWaveShare / 1000;
