@@ -361,34 +361,35 @@ def main():
         # per group, causal attention on the matrix cores plus the write of their K/V rows into pages of instance 0's pool
         # layout.  Algorithmic operations: 4 D per (query, key) pair under the causal mask and per head.
         del zero_rows
-        pb = workload.make_prefill(args.workload, seed=0)
-        pq, pk, pv = (bits_to_bf16(x, "cuda:0") for x in (pb.q, pb.k, pb.v))
-        pcu = torch.from_numpy(pb.cu_seqlens).to("cuda:0")
-        pout = torch.empty_like(pq)
-        plse = torch.empty(pq.shape[:2], dtype=torch.float32, device="cuda:0")
-        kpool = torch.empty((pb.num_pages, pb.Hkv, 16, pb.D), dtype=torch.bfloat16, device="cuda:0")
-        vpool = torch.empty_like(kpool)
-        poff, ppages = torch.from_numpy(pb.page_offsets).to("cuda:0"), torch.from_numpy(pb.pages).to("cuda:0")
-        pf_att = ra.prefill_from_tensors(pq, pk, pv, pcu, int(pb.lens.max()), pout, plse, float(pb.softmax_scale))
-        pf_all = ra.prefill_from_tensors(pq, pk, pv, pcu, int(pb.lens.max()), pout, plse, float(pb.softmax_scale), k_pool=kpool,
-                                         v_pool=vpool, page_offsets=poff, pages=ppages)
-        pf_us = []
-        for desc in (pf_att, pf_all):
-            for _ in range(5):
-                dec.prefill(desc, stream)
-            ev0.record(stream)
-            for _ in range(20):
-                dec.prefill(desc, stream)
-            ev1.record(stream)
-            torch.cuda.synchronize()
-            pf_us.append(ev0.elapsed_time(ev1) * 1e3 / 20)
-        pf_tflops = pb.flops() / pf_us[0] / 1e6
-        out["prefill"] = {"us_per_call": round(pf_us[1], 1), "attention_us": round(pf_us[0], 1), "prompts": int(pb.lens.size),
-                          "prompt_len": int(pb.lens[0]), "algorithmic_GFLOP": round(pb.flops() / 1e9, 2),
-                          "roofline": {"bound": "mfma", "kernel": "prefill_kernel", "achieved": round(pf_tflops, 1), "peak": 2500.0,
-                                       "unit": "TFLOP/s", "frac": round(pf_tflops / 2500.0, 4), "traffic": None},
-                          "note": "causal attention of the prompts (bf16 MFMA, fp32 accumulation); us_per_call includes the cache write"}
-        del pq, pk, pv, pout, plse, kpool, vpool
+        if cfg["prompt"] > 0:            # (a workload without prompts has no prefill to time)
+            pb = workload.make_prefill(args.workload, seed=0)
+            pq, pk, pv = (bits_to_bf16(x, "cuda:0") for x in (pb.q, pb.k, pb.v))
+            pcu = torch.from_numpy(pb.cu_seqlens).to("cuda:0")
+            pout = torch.empty_like(pq)
+            plse = torch.empty(pq.shape[:2], dtype=torch.float32, device="cuda:0")
+            kpool = torch.empty((pb.num_pages, pb.Hkv, 16, pb.D), dtype=torch.bfloat16, device="cuda:0")
+            vpool = torch.empty_like(kpool)
+            poff, ppages = torch.from_numpy(pb.page_offsets).to("cuda:0"), torch.from_numpy(pb.pages).to("cuda:0")
+            pf_att = ra.prefill_from_tensors(pq, pk, pv, pcu, int(pb.lens.max()), pout, plse, float(pb.softmax_scale))
+            pf_all = ra.prefill_from_tensors(pq, pk, pv, pcu, int(pb.lens.max()), pout, plse, float(pb.softmax_scale), k_pool=kpool,
+                                             v_pool=vpool, page_offsets=poff, pages=ppages)
+            pf_us = []
+            for desc in (pf_att, pf_all):
+                for _ in range(5):
+                    dec.prefill(desc, stream)
+                ev0.record(stream)
+                for _ in range(20):
+                    dec.prefill(desc, stream)
+                ev1.record(stream)
+                torch.cuda.synchronize()
+                pf_us.append(ev0.elapsed_time(ev1) * 1e3 / 20)
+            pf_tflops = pb.flops() / pf_us[0] / 1e6
+            out["prefill"] = {"us_per_call": round(pf_us[1], 1), "attention_us": round(pf_us[0], 1), "prompts": int(pb.lens.size),
+                              "prompt_len": int(pb.lens[0]), "algorithmic_GFLOP": round(pb.flops() / 1e9, 2),
+                              "roofline": {"bound": "mfma", "kernel": "prefill_kernel", "achieved": round(pf_tflops, 1), "peak": 2500.0,
+                                           "unit": "TFLOP/s", "frac": round(pf_tflops / 2500.0, 4), "traffic": None},
+                              "note": "causal attention of the prompts (bf16 MFMA, fp32 accumulation); us_per_call includes the cache write"}
+            del pq, pk, pv, pout, plse, kpool, vpool
 
     if not args.no_cpu_baseline:
         import oracle

@@ -35,6 +35,9 @@ CONFIGS = {
     # 72B-shaped streaming: 16 x 16, prompt 2048, responses up to 30720, 64 consecutive decode steps.
     "stream72b": dict(id=4, Hq=64, Hkv=8, D=128, groups=16, R=16, prompt=2048, resp="stream",
                       resp_max=30720, p_finish=0.02, steps=64),
+    # A batch of the 7B shape without structure, for comparison with "grpo7b" in benchmarks: 256 sequences of
+    # 2304 tokens (the GRPO batch's mean), no shared prompts, so every sequence is a group of its own.
+    "regular7b": dict(id=21, Hq=28, Hkv=4, D=128, groups=256, R=1, prompt=0, resp="fixed", resp_len=2304),
     # Reduced shapes for element-by-element parity (the oracle finishes them in seconds):
     # several KV tiles per sequence, ragged tails, empty responses, more than one group.
     "mid7b": dict(id=11, Hq=28, Hkv=4, D=128, groups=3, R=8, prompt=80, resp="uniform", resp_max=700),
@@ -221,6 +224,8 @@ def response_lengths(cfg, seed, step=0):
     kind = cfg["resp"]
     if kind == "tiny":
         return np.array([1, 48, 84, 240], dtype=np.int64)
+    if kind == "fixed":
+        return np.full(B, cfg["resp_len"], dtype=np.int64)
     if kind == "uniform":
         return _rng(seed, cfg["id"], 0, 1).integers(0, cfg["resp_max"] + 1, size=B)
     if kind == "lognormal":
